@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the Tucker-2 convolution hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the whole hot path over the ResNet-18-shaped sweep at batch 1
+(four layers: C=N in {64,128,256,512} at 56/28/14/7 pixels, R1=R2=C/4, 3x3, stride 1, pad 1,
+fp32), each layer one tdc_conv_tucker2 call on the current stream with inputs and re-laid-out
+weights already resident in HBM.  Prints ONE JSON line.
+
+  value        effective GFLOP/s of the sweep: algorithmic FLOPs of the four layers / step time
+  layers       per-layer latency (us, event-timed over back-to-back launches), GFLOP/s and the
+               fraction of that layer's roofline max(bytes/8 TB/s, flops/157.3 TFLOP/s)
+  roofline     the same for the dominant (slowest) layer's kernel
+  null_launch_us  an empty kernel timed the same way: the floor any batch-1 layer sits on
+  cpu_baseline the CPU oracle (three-stage, fp64) timed on the host cores on the same sweep
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
+# layer name; None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def _time_events(fn, iters, torch):
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) * 1e-3 / iters   # seconds per call
+
+
+def cpu_baseline(layers, inputs, budget_s=12.0, max_sweeps=400):
+    """The oracle as it stands (three-stage, Eqs. 2-4, fp64 accumulation, OpenMP over output channels)."""
+    from oracle import tdc_oracle as orc
+    from paper_2211_03715_amd import roofline as R
+    orc.load()
+    shapes = [orc.Shape(**L.asdict()) for L in layers]
+    fl = sum(R.flops(L) for L in layers)
+    for sh, inp in zip(shapes, inputs):          # warm caches / thread pool
+        orc.conv_factored(sh, **inp)
+    t0 = time.perf_counter()
+    sweeps = 0
+    while sweeps < max_sweeps and time.perf_counter() - t0 < budget_s:
+        for sh, inp in zip(shapes, inputs):
+            orc.conv_factored(sh, **inp)
+        sweeps += 1
+    dt = time.perf_counter() - t0
+    return {"value": fl * sweeps / dt / 1e9, "unit": "GFLOP/s", "cores": orc.max_threads(), "kind": "oracle",
+            "sample": "%d passes of the same 4-layer sweep, three-stage path, %.1f s wall" % (sweeps, dt),
+            "us_per_sweep": dt / sweeps * 1e6}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default: the ResNet-18-shaped sweep)")
+    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2211_03715_amd import binding as B
+    from paper_2211_03715_amd import roofline as R
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    from paper_2211_03715_amd.workloads import config_layers, layer_seed, make_inputs
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.load()                                   # fails loudly if libtdc.so has not been built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    variant = {"auto": B.VARIANT_AUTO, "naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT,
+               "fused": B.VARIANT_FUSED}[args.variant]
+
+    layers = config_layers(args.config)
+    host_inputs = [make_inputs(L, layer_seed(args.config, i)) for i, L in enumerate(layers)]
+    convs, xs, ys = [], [], []
+    for L, inp in zip(layers, host_inputs):
+        t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
+        conv = TuckerConv2d(L, 0, B.make_tuning(variant=variant) if variant else None)
+        conv.pack(t["U_in"], t["core"], t["U_out"])         # one-off re-layout, untimed (as in the paper)
+        convs.append(conv)
+        xs.append(t["x"])
+        ys.append(torch.empty((L.batch, L.N, conv.Ho, conv.Wo), device=dev, dtype=torch.float32))
+    torch.cuda.synchronize()
+
+    def step():
+        for conv, x, y in zip(convs, xs, ys):
+            conv(x, y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    total_flops = sum(R.flops(L) for L in layers)
+
+    # per-layer: events around back-to-back launches of that layer alone, on the launch stream
+    iters = max(200, min(2000, args.steps))
+    per_layer = []
+    for L, conv, x, y in zip(layers, convs, xs, ys):
+        for _ in range(20):
+            conv(x, y)
+        sec = _time_events(lambda: conv(x, y), iters, torch)
+        bound, t_roof, t_hbm, t_mfma = R.roofline(L)
+        per_layer.append({
+            "layer": L.name(), "plan": conv.describe(), "kernels": conv.kernel_count(),
+            "latency_us": sec * 1e6, "gflops": R.flops(L) / sec / 1e9,
+            "dense_equiv_gflops": R.dense_flops(L) / sec / 1e9,
+            "bound": bound, "roofline_us": t_roof * 1e6, "roofline_frac": t_roof / sec,
+        })
+    null_us = _time_events(lambda: B.tdc_launch_null(), 2000, torch) * 1e6
+
+    dom = max(range(len(layers)), key=lambda i: per_layer[i]["latency_us"])
+    Ld, pd = layers[dom], per_layer[dom]
+    sec = pd["latency_us"] * 1e-6
+    if pd["bound"] == "hbm":
+        roof = {"bound": "hbm", "achieved": R.bytes_compulsory(Ld) / sec / 1e9, "peak": R.HBM_PEAK / 1e9, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": R.flops(Ld) / sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = MEASURED_TRAFFIC.get(Ld.name())
+    roof["kernel"] = pd["plan"]
+    roof["layer"] = Ld.name()
+    roof["launch_us"] = pd["latency_us"]
+
+    out = {
+        "metric": "effective GFLOP/s (algorithmic FLOPs of the Tucker-2 layers / time), batch 1, per-layer latency in `layers`",
+        "value": total_flops / (dt / args.steps) / 1e9, "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config %d: %s" % (args.config, {
+            1: "single Tucker-2 3x3 layer 64->16->16->64 at 56x56, batch 1",
+            2: "ResNet-18-shaped sweep, batch 1, 3x3 s1 p1, (C=N,HxW) in (64,56) (128,28) (256,14) (512,7), R1=R2=C/4",
+            3: "rank sweep at C=N=256, 14x14, (R1,R2) in {8,16,32,64,128}^2, batch 1",
+            4: "stride/batch variants: 128->256 s2 56->28 r32/64 and 128->128 28x28 r32, batch 1/8/32",
+            5: "ResNet-50-style chain of 16 Tucker-2 3x3 layers, ranks round(0.3C) to 8, batch 1"}[args.config]),
+            "layers_per_step": len(layers), "variant": args.variant},
+        "roofline": roof,
+        "layers": per_layer,
+        "null_launch_us": null_us,
+        "sum_layer_latency_us": sum(p["latency_us"] for p in per_layer),
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
+    for conv in convs:
+        conv.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,137 @@
+/*
+ * tdc.h -- C ABI of the MI355X (gfx950) Tucker-2 convolution library.
+ *
+ * One call evaluates one Tucker-2-format convolution layer (paper section 3,
+ * "Basics of TKD-based Convolution"): a 1x1 projection C -> R1 with the factor
+ * U_in (Eq. 2), a K x K "core" convolution R1 -> R2 on the core tensor (Eq. 3)
+ * and a 1x1 expansion R2 -> N with the factor U_out (Eq. 4).  The result equals
+ * the dense convolution with the kernel of Eq. 1,
+ *   K(c,n,r,s) = sum_{d1,d2} core(d1,d2,r,s) * U_in(c,d1) * U_out(d2,n),
+ * up to fp32 rounding.  R1, R2 are the paper's Tucker ranks D1, D2; K is the
+ * paper's stencil size R = S.
+ *
+ * All tensor arguments are DEVICE pointers to contiguous fp32 arrays, at least
+ * 16-byte aligned, resident on the plan's device:
+ *   x      [batch][C][H][W]          input, NCHW
+ *   U_in   [C][R1]                   U1(c,d1)
+ *   core   [R1][R2][K][K]            core(d1,d2,r,s)  (mode 1 contracts with U_in,
+ *                                    mode 2 with U_out; cross-correlation, no flip)
+ *   U_out  [R2][N]                   U2(d2,n) as Eq. 4 uses it
+ *   y      [batch][N][Ho][Wo]        output, NCHW, Ho = floor((H+2*pad-K)/stride)+1
+ * Zero padding `pad` and `stride` apply to the core convolution; stage 1 runs on
+ * every input pixel.  There is no bias or activation: the layer is linear in x.
+ *
+ * Ownership: the caller owns x, the weights, y and the stream.  The library
+ * never frees or reallocates them.  A plan owns its workspace (intermediates
+ * and re-laid-out weights) and releases it in tdc_plan_destroy.  y is fully
+ * overwritten; x and y must not overlap.  A plan may be used by one stream at
+ * a time (its workspace is not re-entrant).
+ *
+ * Asynchrony: tdc_conv_tucker2 and tdc_plan_pack_weights only enqueue work on
+ * the given stream (NULL = the default stream) and return; they never
+ * synchronise with the host and never allocate.
+ *
+ * Errors: every function returns a tdc_status (0 = success, negative =
+ * failure).  Nothing aborts, throws or prints.
+ */
+#ifndef TDC_H
+#define TDC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tdc_status {
+    TDC_OK = 0,
+    TDC_ERR_NULL = -1,            /* a required pointer is NULL                               */
+    TDC_ERR_BAD_SHAPE = -2,       /* non-positive size, stride < 1, pad < 0, H + 2*pad < K    */
+    TDC_ERR_SHAPE_MISMATCH = -3,  /* shape passed to a call differs from the plan's           */
+    TDC_ERR_UNSUPPORTED = -4,     /* valid layer outside the supported domain (see below)     */
+    TDC_ERR_ALLOC = -5,           /* device or host allocation failed                         */
+    TDC_ERR_HIP = -6,             /* a HIP runtime call or a kernel launch failed             */
+    TDC_ERR_BAD_TUNING = -7       /* a forced tuning does not fit the shape or the hardware   */
+} tdc_status;
+
+/* Layer geometry.  Supported domain: layout 0 (NCHW); square K in 1..7;
+ * stride in 1..4; pad in 0..K-1; any positive batch, C, N, H, W, R1, R2 for which
+ * every tensor has fewer than 2^31 elements. */
+typedef struct tdc_shape {
+    int32_t batch, C, N, H, W;
+    int32_t R1, R2, K;
+    int32_t stride, pad;
+    int32_t layout;               /* 0 = NCHW.  Other values: TDC_ERR_UNSUPPORTED */
+} tdc_shape;
+
+/* Kernel families the selector chooses between (section 5.5 of the paper picks tile
+ * sizes with an analytical model; the selector here is this library's own). */
+enum {
+    TDC_VARIANT_AUTO = 0,   /* let the selector decide                                          */
+    TDC_VARIANT_NAIVE = 1,  /* three plain fp32 kernels, one thread per output pixel            */
+    TDC_VARIANT_SPLIT = 2,  /* three fp32-MFMA GEMM kernels, intermediates z1/z2 in workspace   */
+    TDC_VARIANT_FUSED = 3   /* one fp32-MFMA kernel per spatial tile, z1/z2 kept in LDS         */
+};
+
+/* Launch parameters.  Zero in any field means "selector's choice".
+ *   tile_h, tile_w : output tile of one workgroup            (FUSED)
+ *   waves          : wavefronts (of 64 lanes) per workgroup  (SPLIT: per stage, FUSED: waves[0])
+ *   mb, pb         : 16-channel and 16-pixel blocks per wavefront register tile, per stage */
+typedef struct tdc_tuning {
+    int32_t variant;
+    int32_t tile_h, tile_w;
+    int32_t waves[3];
+    int32_t mb[3];
+    int32_t pb[3];
+} tdc_tuning;
+
+typedef struct tdc_plan tdc_plan;   /* opaque, library-owned */
+
+/* Validate `shape`, run the selector (or take `forced` when not NULL), and allocate the
+ * workspace on `device`.  On success *out holds the plan. */
+int tdc_plan_create(tdc_plan **out, const tdc_shape *shape, int device);
+int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, const tdc_tuning *forced);
+
+/* Re-lay the weights out for the kernels, once, into plan-owned memory (the paper's
+ * section 5.2 does the same conversion offline).  Later tdc_conv_tucker2 calls that pass
+ * these same three pointers use the stored copy; the caller thereby promises not to
+ * change the weights in place without calling this again.  Without this call every
+ * tdc_conv_tucker2 re-lays the weights out on the stream first (correct, slower). */
+int tdc_plan_pack_weights(tdc_plan *plan, void *hip_stream,
+                          const float *U_in, const float *core, const float *U_out);
+
+/* Enqueue y = TuckerConv(x; U_in, core, U_out) (Eqs. 2-4).  `shape` must equal the plan's. */
+int tdc_conv_tucker2(tdc_plan *plan, void *hip_stream,
+                     const float *x, const float *U_in, const float *core, const float *U_out,
+                     float *y, const tdc_shape *shape);
+
+/* Release the plan and its workspace.  NULL is accepted. */
+int tdc_plan_destroy(tdc_plan *plan);
+
+/* Introspection (host only). */
+int tdc_plan_get_tuning(const tdc_plan *plan, tdc_tuning *out);          /* what will be launched   */
+int tdc_plan_describe(const tdc_plan *plan, char *buf, size_t buf_len);  /* one line of text        */
+size_t tdc_plan_workspace_bytes(const tdc_plan *plan);                   /* device bytes owned      */
+int tdc_plan_kernel_count(const tdc_plan *plan);                         /* launches per conv call (weights packed) */
+const char *tdc_status_string(int status);                               /* static string           */
+int tdc_version(void);
+
+/* The selector by itself (host only, touches no device): fill every zero field of *inout for a
+ * device with `compute_units` CUs and `lds_bytes` of LDS per workgroup.  This is the a-priori
+ * model tdc_plan_create uses; see tdc_select.cpp for its terms. */
+int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, tdc_tuning *inout);
+
+/* Measurement aid: enqueue one empty kernel (a single wavefront that does nothing) on the stream,
+ * so that a harness can report the launch floor next to per-layer latencies, which at batch 1
+ * are of the same order (the paper, section 6, also notes that launch time of the extra 1x1
+ * kernels can outweigh the saved FLOPs). */
+int tdc_launch_null(void *hip_stream);
+
+/* Output size rule used everywhere: floor((in + 2*pad - K)/stride) + 1; returns 0 on bad input. */
+int tdc_out_size(int in, int K, int stride, int pad);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TDC_H */

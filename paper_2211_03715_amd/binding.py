@@ -1,0 +1,219 @@
+"""Thin ctypes binding of libtdc.so, with the same names as ``include/tdc.h``.
+
+Argument marshalling only: every step of the layer runs in the library's HIP
+kernels.  PyTorch is used for device memory and streams.  There is no CPU
+fallback: if the built library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libtdc.so")
+
+TDC_OK = 0
+TDC_ERR_NULL = -1
+TDC_ERR_BAD_SHAPE = -2
+TDC_ERR_SHAPE_MISMATCH = -3
+TDC_ERR_UNSUPPORTED = -4
+TDC_ERR_ALLOC = -5
+TDC_ERR_HIP = -6
+TDC_ERR_BAD_TUNING = -7
+
+VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
+VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused"}
+
+# every symbol include/tdc.h declares
+EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", "tdc_conv_tucker2",
+           "tdc_plan_destroy", "tdc_plan_get_tuning", "tdc_plan_describe", "tdc_plan_workspace_bytes",
+           "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
+           "tdc_select_tuning", "tdc_launch_null"]
+
+
+class tdc_shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("batch", "C", "N", "H", "W", "R1", "R2", "K", "stride", "pad", "layout")]
+
+
+class tdc_tuning(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("tile_h", ctypes.c_int32), ("tile_w", ctypes.c_int32),
+                ("waves", ctypes.c_int32 * 3), ("mb", ctypes.c_int32 * 3), ("pb", ctypes.c_int32 * 3)]
+
+    def as_dict(self):
+        return {"variant": VARIANT_NAMES.get(self.variant, self.variant), "tile_h": self.tile_h,
+                "tile_w": self.tile_w, "waves": list(self.waves), "mb": list(self.mb), "pb": list(self.pb)}
+
+
+class TdcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, status_string(status)))
+
+
+_lib = None
+
+
+def load(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libtdc.so and declare prototypes.  Raises if the library has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise RuntimeError("%s is missing: build it first (python -m paper_2211_03715_amd.build); "
+                           "there is no CPU fallback" % p)
+    lib = ctypes.CDLL(p)
+    vp, ip = ctypes.c_void_p, ctypes.c_int
+    sp, tp = ctypes.POINTER(tdc_shape), ctypes.POINTER(tdc_tuning)
+    lib.tdc_plan_create.argtypes = [ctypes.POINTER(vp), sp, ip]
+    lib.tdc_plan_create.restype = ip
+    lib.tdc_plan_create_tuned.argtypes = [ctypes.POINTER(vp), sp, ip, tp]
+    lib.tdc_plan_create_tuned.restype = ip
+    lib.tdc_plan_pack_weights.argtypes = [vp, vp, vp, vp, vp]
+    lib.tdc_plan_pack_weights.restype = ip
+    lib.tdc_conv_tucker2.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp]
+    lib.tdc_conv_tucker2.restype = ip
+    lib.tdc_plan_destroy.argtypes = [vp]
+    lib.tdc_plan_destroy.restype = ip
+    lib.tdc_plan_get_tuning.argtypes = [vp, tp]
+    lib.tdc_plan_get_tuning.restype = ip
+    lib.tdc_plan_describe.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t]
+    lib.tdc_plan_describe.restype = ip
+    lib.tdc_plan_workspace_bytes.argtypes = [vp]
+    lib.tdc_plan_workspace_bytes.restype = ctypes.c_size_t
+    lib.tdc_plan_kernel_count.argtypes = [vp]
+    lib.tdc_plan_kernel_count.restype = ip
+    lib.tdc_status_string.argtypes = [ip]
+    lib.tdc_status_string.restype = ctypes.c_char_p
+    lib.tdc_version.argtypes = []
+    lib.tdc_version.restype = ip
+    lib.tdc_out_size.argtypes = [ip, ip, ip, ip]
+    lib.tdc_out_size.restype = ip
+    lib.tdc_select_tuning.argtypes = [sp, ip, ip, tp]
+    lib.tdc_select_tuning.restype = ip
+    lib.tdc_launch_null.argtypes = [vp]
+    lib.tdc_launch_null.restype = ip
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().tdc_status_string(int(status)).decode()
+
+
+tdc_status_string = status_string
+
+
+def tdc_version() -> int:
+    return load().tdc_version()
+
+
+def tdc_out_size(n: int, K: int, stride: int, pad: int) -> int:
+    return load().tdc_out_size(n, K, stride, pad)
+
+
+def make_shape(batch, C, N, H, W, R1, R2, K=3, stride=1, pad=1, layout=0) -> tdc_shape:
+    return tdc_shape(batch, C, N, H, W, R1, R2, K, stride, pad, layout)
+
+
+def make_tuning(variant=0, tile_h=0, tile_w=0, waves=(0, 0, 0), mb=(0, 0, 0), pb=(0, 0, 0)) -> tdc_tuning:
+    t = tdc_tuning()
+    t.variant, t.tile_h, t.tile_w = variant, tile_h, tile_w
+    for i in range(3):
+        t.waves[i], t.mb[i], t.pb[i] = waves[i], mb[i], pb[i]
+    return t
+
+
+def tdc_select_tuning(shape: tdc_shape, compute_units: int = 256, lds_bytes: int = 160 * 1024,
+                      tuning: Optional[tdc_tuning] = None) -> tdc_tuning:
+    t = tuning if tuning is not None else tdc_tuning()
+    rc = load().tdc_select_tuning(ctypes.byref(shape), compute_units, lds_bytes, ctypes.byref(t))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_select_tuning")
+    return t
+
+
+def tdc_plan_create(shape: tdc_shape, device: int = 0, tuning: Optional[tdc_tuning] = None) -> ctypes.c_void_p:
+    lib = load()
+    plan = ctypes.c_void_p()
+    if tuning is None:
+        rc = lib.tdc_plan_create(ctypes.byref(plan), ctypes.byref(shape), device)
+    else:
+        rc = lib.tdc_plan_create_tuned(ctypes.byref(plan), ctypes.byref(shape), device, ctypes.byref(tuning))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_create")
+    return plan
+
+
+def tdc_plan_create_tuned(shape: tdc_shape, device: int, tuning: tdc_tuning) -> ctypes.c_void_p:
+    return tdc_plan_create(shape, device, tuning)
+
+
+def tdc_plan_destroy(plan) -> None:
+    rc = load().tdc_plan_destroy(plan)
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_destroy")
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or pass an int / None through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def tdc_plan_pack_weights(plan, U_in, core, U_out, stream=None) -> None:
+    rc = load().tdc_plan_pack_weights(plan, _stream(stream), _ptr(U_in), _ptr(core), _ptr(U_out))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_pack_weights")
+
+
+def tdc_conv_tucker2(plan, x, U_in, core, U_out, y, shape: tdc_shape, stream=None) -> None:
+    rc = load().tdc_conv_tucker2(plan, _stream(stream), _ptr(x), _ptr(U_in), _ptr(core), _ptr(U_out),
+                                 _ptr(y), ctypes.byref(shape))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_conv_tucker2")
+
+
+def tdc_plan_get_tuning(plan) -> tdc_tuning:
+    t = tdc_tuning()
+    rc = load().tdc_plan_get_tuning(plan, ctypes.byref(t))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_get_tuning")
+    return t
+
+
+def tdc_plan_describe(plan) -> str:
+    buf = ctypes.create_string_buffer(512)
+    rc = load().tdc_plan_describe(plan, buf, 512)
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_describe")
+    return buf.value.decode()
+
+
+def tdc_plan_workspace_bytes(plan) -> int:
+    return int(load().tdc_plan_workspace_bytes(plan))
+
+
+def tdc_plan_kernel_count(plan) -> int:
+    return int(load().tdc_plan_kernel_count(plan))
+
+
+def tdc_launch_null(stream=None) -> None:
+    rc = load().tdc_launch_null(_stream(stream))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_launch_null")

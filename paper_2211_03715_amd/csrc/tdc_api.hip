@@ -1,0 +1,313 @@
+// C ABI of libtdc.so: plans, validation, weight re-layout bookkeeping and launch dispatch.
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "tdc_internal.h"
+
+struct tdc_plan {
+    tdc_shape shape;
+    TdcDims dims;
+    tdc_tuning tuning;
+    TdcFusedGeom geom;
+    int device;
+    float *z1, *z2;                    // intermediates (NAIVE, SPLIT)
+    float *uin_p, *core_p, *uout_p;    // re-laid-out weights (SPLIT, FUSED)
+    const float *packed_from[3];       // caller pointers the stored copy was made from, or NULLs
+    size_t ws_bytes;
+    char desc[320];
+};
+
+namespace {
+
+__global__ void tdc_null_kernel() {}
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard()
+    {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+bool same_shape(const tdc_shape &a, const tdc_shape &b)
+{
+    return a.batch == b.batch && a.C == b.C && a.N == b.N && a.H == b.H && a.W == b.W && a.R1 == b.R1 &&
+           a.R2 == b.R2 && a.K == b.K && a.stride == b.stride && a.pad == b.pad && a.layout == b.layout;
+}
+
+int validate(const tdc_shape &s)
+{
+    if (s.batch < 1 || s.C < 1 || s.N < 1 || s.H < 1 || s.W < 1 || s.R1 < 1 || s.R2 < 1 || s.K < 1) return TDC_ERR_BAD_SHAPE;
+    if (s.stride < 1 || s.pad < 0) return TDC_ERR_BAD_SHAPE;
+    if ((long)s.H + 2L * s.pad < s.K || (long)s.W + 2L * s.pad < s.K) return TDC_ERR_BAD_SHAPE;
+    if (s.layout != 0) return TDC_ERR_UNSUPPORTED;
+    if (s.K > 7 || s.stride > 4 || s.pad > s.K - 1) return TDC_ERR_UNSUPPORTED;
+    const long Ho = tdc_out_size(s.H, s.K, s.stride, s.pad), Wo = tdc_out_size(s.W, s.K, s.stride, s.pad);
+    const long lim = 0x7fffffffL;
+    const long r1p = (s.R1 + 15L) / 16 * 16, r2p = (s.R2 + 15L) / 16 * 16, np = (s.N + 15L) / 16 * 16;
+    const long cp = (s.C + 15L) / 16 * 16;
+    if ((double)s.batch * s.C * s.H * s.W >= lim || (double)s.batch * np * Ho * Wo >= lim) return TDC_ERR_UNSUPPORTED;
+    if ((double)s.batch * r1p * s.H * s.W >= lim || (double)s.batch * r2p * Ho * Wo >= lim) return TDC_ERR_UNSUPPORTED;
+    if ((double)cp * r1p >= lim || (double)r1p * r2p * s.K * s.K >= lim || (double)r2p * np >= lim) return TDC_ERR_UNSUPPORTED;
+    return TDC_OK;
+}
+
+TdcDims make_dims(const tdc_shape &s)
+{
+    TdcDims d;
+    d.B = s.batch; d.C = s.C; d.N = s.N; d.H = s.H; d.W = s.W; d.R1 = s.R1; d.R2 = s.R2; d.K = s.K;
+    d.stride = s.stride; d.pad = s.pad;
+    d.Ho = tdc_out_size(s.H, s.K, s.stride, s.pad);
+    d.Wo = tdc_out_size(s.W, s.K, s.stride, s.pad);
+    d.NB1 = (s.R1 + 15) / 16; d.NB2 = (s.R2 + 15) / 16; d.NB3 = (s.N + 15) / 16;
+    d.KG1 = (s.C + 15) / 16;
+    return d;
+}
+
+int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
+{
+    const tdc_tuning &t = p.tuning;
+    if (t.variant == TDC_VARIANT_NAIVE) return TDC_OK;
+    for (int i = 0; i < 3; ++i)
+        if (t.waves[i] < 1 || t.waves[i] > 8) return TDC_ERR_BAD_TUNING;
+    if (t.variant == TDC_VARIANT_SPLIT) {
+        for (int i = 0; i < 3; ++i) {
+            if (!tdc_gemm_unit_supported(t.mb[i], t.pb[i])) return TDC_ERR_BAD_TUNING;
+            if (t.waves[i] > 1 && (size_t)t.waves[i] * t.mb[i] * t.pb[i] * 1024 > 64 * 1024) return TDC_ERR_BAD_TUNING;
+        }
+        return TDC_OK;
+    }
+    if (t.variant == TDC_VARIANT_FUSED) {
+        if (t.tile_h < 1 || t.tile_w < 1 || t.tile_h * t.tile_w > 4096) return TDC_ERR_BAD_TUNING;
+        if (!tdc_fused_unit_supported(t.mb[0], t.mb[1], t.mb[2], t.pb[0])) return TDC_ERR_BAD_TUNING;
+        if ((long)p.geom.lds_bytes > dev.lds_per_wg) return TDC_ERR_BAD_TUNING;
+        return TDC_OK;
+    }
+    return TDC_ERR_BAD_TUNING;
+}
+
+void describe(tdc_plan &p)
+{
+    const tdc_tuning &t = p.tuning;
+    const char *names[] = {"auto", "naive", "split", "fused"};
+    if (t.variant == TDC_VARIANT_FUSED)
+        snprintf(p.desc, sizeof(p.desc),
+                 "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB",
+                 t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.mb[1], t.mb[2], t.pb[0],
+                 p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes);
+    else if (t.variant == TDC_VARIANT_SPLIT)
+        snprintf(p.desc, sizeof(p.desc), "split stage(mb,pb,waves)= s1(%d,%d,%d) s2(%d,%d,%d) s3(%d,%d,%d)",
+                 t.mb[0], t.pb[0], t.waves[0], t.mb[1], t.pb[1], t.waves[1], t.mb[2], t.pb[2], t.waves[2]);
+    else
+        snprintf(p.desc, sizeof(p.desc), "%s", names[t.variant & 3]);
+}
+
+}  // namespace
+
+extern "C" {
+
+int tdc_version(void) { return 100; }
+
+int tdc_out_size(int in, int K, int stride, int pad)
+{
+    if (in < 1 || K < 1 || stride < 1 || pad < 0 || in + 2 * pad < K) return 0;
+    return (in + 2 * pad - K) / stride + 1;
+}
+
+const char *tdc_status_string(int status)
+{
+    switch (status) {
+        case TDC_OK: return "ok";
+        case TDC_ERR_NULL: return "null pointer argument";
+        case TDC_ERR_BAD_SHAPE: return "invalid layer shape";
+        case TDC_ERR_SHAPE_MISMATCH: return "shape differs from the plan's shape";
+        case TDC_ERR_UNSUPPORTED: return "layer outside the supported domain";
+        case TDC_ERR_ALLOC: return "allocation failed";
+        case TDC_ERR_HIP: return "HIP runtime or kernel launch error";
+        case TDC_ERR_BAD_TUNING: return "forced tuning does not fit the shape or the device";
+        default: return "unknown status";
+    }
+}
+
+int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, const tdc_tuning *forced)
+{
+    if (!out || !shape) return TDC_ERR_NULL;
+    *out = nullptr;
+    int rc = validate(*shape);
+    if (rc != TDC_OK) return rc;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return TDC_ERR_HIP;
+    DeviceGuard guard(device);
+    if (!guard.ok) return TDC_ERR_HIP;
+
+    TdcDeviceInfo dev;
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return TDC_ERR_HIP;
+    dev.cus = v > 0 ? v : 256;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) return TDC_ERR_HIP;
+    dev.lds_per_wg = v > 0 ? v : 65536;
+
+    tdc_plan *p = new (std::nothrow) tdc_plan();
+    if (!p) return TDC_ERR_ALLOC;
+    memset(p, 0, sizeof(*p));
+    p->shape = *shape;
+    p->dims = make_dims(*shape);
+    p->device = device;
+    if (forced) p->tuning = *forced;
+    if (p->tuning.variant < TDC_VARIANT_AUTO || p->tuning.variant > TDC_VARIANT_FUSED) {
+        delete p;
+        return TDC_ERR_BAD_TUNING;
+    }
+    rc = tdc_select(p->dims, dev, &p->tuning);
+    if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)
+        p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w);
+    if (rc == TDC_OK) rc = check_tuning(*p, dev);
+    if (rc != TDC_OK) {
+        delete p;
+        return rc;
+    }
+
+    const TdcDims &d = p->dims;
+    const size_t n_z1 = (size_t)d.B * 16 * d.NB1 * d.H * d.W, n_z2 = (size_t)d.B * 16 * d.NB2 * d.Ho * d.Wo;
+    const size_t n_w1 = tdc_packed_floats_uin(d), n_w2 = tdc_packed_floats_core(d), n_w3 = tdc_packed_floats_uout(d);
+    bool ok = true;
+    if (p->tuning.variant != TDC_VARIANT_FUSED) {
+        ok = ok && hipMalloc((void **)&p->z1, n_z1 * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&p->z2, n_z2 * sizeof(float)) == hipSuccess;
+        p->ws_bytes += (n_z1 + n_z2) * sizeof(float);
+    }
+    if (p->tuning.variant != TDC_VARIANT_NAIVE) {
+        ok = ok && hipMalloc((void **)&p->uin_p, n_w1 * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&p->core_p, n_w2 * sizeof(float)) == hipSuccess;
+        ok = ok && hipMalloc((void **)&p->uout_p, n_w3 * sizeof(float)) == hipSuccess;
+        p->ws_bytes += (n_w1 + n_w2 + n_w3) * sizeof(float);
+    }
+    if (!ok) {
+        (void)hipGetLastError();
+        tdc_plan_destroy(p);
+        return TDC_ERR_ALLOC;
+    }
+    describe(*p);
+    *out = p;
+    return TDC_OK;
+}
+
+int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, tdc_tuning *inout)
+{
+    if (!shape || !inout) return TDC_ERR_NULL;
+    int rc = validate(*shape);
+    if (rc != TDC_OK) return rc;
+    if (compute_units < 1 || lds_bytes < 1024) return TDC_ERR_BAD_TUNING;
+    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_FUSED) return TDC_ERR_BAD_TUNING;
+    TdcDeviceInfo dev;
+    dev.cus = compute_units;
+    dev.lds_per_wg = lds_bytes;
+    tdc_plan tmp;
+    memset(&tmp, 0, sizeof(tmp));
+    tmp.dims = make_dims(*shape);
+    tmp.tuning = *inout;
+    rc = tdc_select(tmp.dims, dev, &tmp.tuning);
+    if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED)
+        tmp.geom = tdc_fused_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w);
+    if (rc == TDC_OK) rc = check_tuning(tmp, dev);
+    if (rc == TDC_OK) *inout = tmp.tuning;
+    return rc;
+}
+
+int tdc_plan_create(tdc_plan **out, const tdc_shape *shape, int device)
+{
+    return tdc_plan_create_tuned(out, shape, device, nullptr);
+}
+
+int tdc_plan_destroy(tdc_plan *p)
+{
+    if (!p) return TDC_OK;
+    DeviceGuard guard(p->device);
+    int rc = TDC_OK;
+    float *bufs[] = {p->z1, p->z2, p->uin_p, p->core_p, p->uout_p};
+    for (float *b : bufs)
+        if (b && hipFree(b) != hipSuccess) rc = TDC_ERR_HIP;
+    delete p;
+    return rc;
+}
+
+int tdc_plan_pack_weights(tdc_plan *p, void *hip_stream, const float *U_in, const float *core, const float *U_out)
+{
+    if (!p || !U_in || !core || !U_out) return TDC_ERR_NULL;
+    p->packed_from[0] = p->packed_from[1] = p->packed_from[2] = nullptr;
+    if (p->tuning.variant == TDC_VARIANT_NAIVE) {   // reads the caller's layouts directly
+        p->packed_from[0] = U_in; p->packed_from[1] = core; p->packed_from[2] = U_out;
+        return TDC_OK;
+    }
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return TDC_ERR_HIP;
+    if (tdc_launch_pack(p->dims, (hipStream_t)hip_stream, U_in, core, U_out, p->uin_p, p->core_p, p->uout_p) != hipSuccess)
+        return TDC_ERR_HIP;
+    p->packed_from[0] = U_in; p->packed_from[1] = core; p->packed_from[2] = U_out;
+    return TDC_OK;
+}
+
+int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float *U_in, const float *core,
+                     const float *U_out, float *y, const tdc_shape *shape)
+{
+    if (!p || !x || !U_in || !core || !U_out || !y || !shape) return TDC_ERR_NULL;
+    if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return TDC_ERR_HIP;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const TdcDims &d = p->dims;
+    hipError_t e;
+    if (p->tuning.variant == TDC_VARIANT_NAIVE) {
+        e = tdc_launch_naive(d, s, x, U_in, core, U_out, p->z1, p->z2, y);
+        return e == hipSuccess ? TDC_OK : TDC_ERR_HIP;
+    }
+    const bool packed = p->packed_from[0] == U_in && p->packed_from[1] == core && p->packed_from[2] == U_out;
+    if (!packed) {   // no stored copy for these pointers: re-lay out on the stream, remember nothing
+        p->packed_from[0] = p->packed_from[1] = p->packed_from[2] = nullptr;
+        e = tdc_launch_pack(d, s, U_in, core, U_out, p->uin_p, p->core_p, p->uout_p);
+        if (e != hipSuccess) return TDC_ERR_HIP;
+    }
+    if (p->tuning.variant == TDC_VARIANT_SPLIT)
+        e = tdc_launch_split(d, p->tuning, s, x, p->uin_p, p->core_p, p->uout_p, p->z1, p->z2, y);
+    else
+        e = tdc_launch_fused(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, p->uout_p, y);
+    return e == hipSuccess ? TDC_OK : TDC_ERR_HIP;
+}
+
+int tdc_plan_get_tuning(const tdc_plan *p, tdc_tuning *out)
+{
+    if (!p || !out) return TDC_ERR_NULL;
+    *out = p->tuning;
+    return TDC_OK;
+}
+
+int tdc_plan_describe(const tdc_plan *p, char *buf, size_t buf_len)
+{
+    if (!p || !buf || buf_len == 0) return TDC_ERR_NULL;
+    snprintf(buf, buf_len, "%s", p->desc);
+    return TDC_OK;
+}
+
+size_t tdc_plan_workspace_bytes(const tdc_plan *p) { return p ? p->ws_bytes : 0; }
+
+int tdc_plan_kernel_count(const tdc_plan *p)
+{
+    if (!p) return 0;
+    return p->tuning.variant == TDC_VARIANT_FUSED ? 1 : 3;
+}
+
+int tdc_launch_null(void *hip_stream)
+{
+    hipLaunchKernelGGL(tdc_null_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream);
+    return hipGetLastError() == hipSuccess ? TDC_OK : TDC_ERR_HIP;
+}
+
+}  // extern "C"

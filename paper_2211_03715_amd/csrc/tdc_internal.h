@@ -1,0 +1,71 @@
+// Internal declarations shared by the translation units of libtdc.so (not installed).
+//
+// Weight re-layout ("packed", frag-major) used by every MFMA kernel.  A weight matrix
+// Wt[k][m] (k = contraction index, m = output channel) is padded with zeros to
+// multiples of 16 in both directions and stored as
+//     Wp[mb][kg][lane][j],   mb = m/16, kg = k/16, lane = 0..63, j = 0..3
+//     Wp[mb][kg][lane][j] = Wt[16*kg + 4*j + lane/16][16*mb + lane%16]
+// so that one 16-byte load per lane yields the A operands of four consecutive
+// v_mfma_f32_16x16x4_f32 steps (A[m = lane%16][k = lane/16]) and a wavefront's load is
+// one contiguous 1 KiB run.  The matching B operand of step j is
+// B[k = 16*kg + 4*j + lane/16][p = lane%16].
+//   stage 1 (Eq. 2): k = c,                      m = d1   -> Uin_p  [NB1][KG1]
+//   stage 2 (Eq. 3): k = (r*K + s)*R1P + d1,     m = d2   -> core_p [NB2][K*K*NB1]
+//   stage 3 (Eq. 4): k = d2,                     m = n    -> Uout_p [NB3][NB2]
+// with R1P = 16*NB1 >= R1, R2P = 16*NB2 >= R2, NP = 16*NB3 >= N, KG1 = ceil(C/16).
+// Padded channels carry exact zeros through every stage, so the kernels need no
+// remainder handling on the rank dimensions.
+#ifndef TDC_INTERNAL_H
+#define TDC_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tdc.h"
+
+struct TdcDims {
+    int B, C, N, H, W, R1, R2, K, stride, pad, Ho, Wo;
+    int NB1, NB2, NB3;   // 16-blocks of the padded R1, R2, N
+    int KG1;             // ceil(C/16)
+};
+
+// ---- weight re-layout (tdc_pack.hip)
+hipError_t tdc_launch_pack(const TdcDims &d, hipStream_t s, const float *U_in, const float *core,
+                           const float *U_out, float *uin_p, float *core_p, float *uout_p);
+size_t tdc_packed_floats_uin(const TdcDims &d);
+size_t tdc_packed_floats_core(const TdcDims &d);
+size_t tdc_packed_floats_uout(const TdcDims &d);
+
+// ---- plain kernels (tdc_naive.hip): raw weights, z1 [B][R1][H*W], z2 [B][R2][Ho*Wo]
+hipError_t tdc_launch_naive(const TdcDims &d, hipStream_t s, const float *x, const float *U_in,
+                            const float *core, const float *U_out, float *z1, float *z2, float *y);
+
+// ---- three MFMA GEMM kernels (tdc_gemm.hip): packed weights, z1 [B][R1P][H*W], z2 [B][R2P][Ho*Wo]
+bool tdc_gemm_unit_supported(int mb, int pb);
+hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
+                            const float *uin_p, const float *core_p, const float *uout_p,
+                            float *z1, float *z2, float *y);
+
+// ---- fused MFMA kernel (tdc_fused.hip)
+struct TdcFusedGeom {
+    int TH, TW;          // output tile
+    int QH, QW, Q;       // input (halo'd) tile: QH = (TH-1)*stride + K, Q = QH*QW
+    int QB, PBk;         // 16-pixel blocks of the input tile / output tile
+    int tiles_x, tiles_y;
+    int pitch1, pitch2;  // LDS row pitches (floats) of the z1 and z2 tiles
+    size_t lds_bytes;
+};
+bool tdc_fused_unit_supported(int mb1, int mb2, int mb3, int pb);
+TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w);
+hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
+                            const float *x, const float *uin_p, const float *core_p,
+                            const float *uout_p, float *y);
+
+// ---- selector (tdc_select.cpp): fills every zero field of `t`
+struct TdcDeviceInfo {
+    int cus;             // compute units
+    int lds_per_wg;      // bytes of LDS one workgroup may use
+};
+int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t);
+
+#endif

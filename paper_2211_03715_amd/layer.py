@@ -1,0 +1,57 @@
+"""Convenience wrapper for callers that hold torch tensors: plan + packed weights + launch.
+
+Marshalling only; the arithmetic is in libtdc.so.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+from . import binding as B
+
+
+class TuckerConv2d:
+    """One Tucker-2 convolution layer (paper section 3, Eqs. 2-4) bound to a device plan."""
+
+    def __init__(self, layer, device: int = 0, tuning: Optional[B.tdc_tuning] = None):
+        """``layer`` has fields batch, C, N, H, W, R1, R2, K, stride, pad (e.g. workloads.Layer)."""
+        self.shape = B.make_shape(layer.batch, layer.C, layer.N, layer.H, layer.W, layer.R1, layer.R2,
+                                  layer.K, layer.stride, layer.pad)
+        self.Ho = B.tdc_out_size(layer.H, layer.K, layer.stride, layer.pad)
+        self.Wo = B.tdc_out_size(layer.W, layer.K, layer.stride, layer.pad)
+        self.plan = B.tdc_plan_create(self.shape, device, tuning)
+        self.device = device
+        self._weights = None
+
+    def describe(self) -> str:
+        return B.tdc_plan_describe(self.plan)
+
+    def tuning(self) -> dict:
+        return B.tdc_plan_get_tuning(self.plan).as_dict()
+
+    def kernel_count(self) -> int:
+        return B.tdc_plan_kernel_count(self.plan)
+
+    def pack(self, U_in, core, U_out, stream=None) -> None:
+        """Re-lay the weights out once; the tensors must stay alive and unchanged."""
+        self._weights = (U_in, core, U_out)
+        B.tdc_plan_pack_weights(self.plan, U_in, core, U_out, stream)
+
+    def __call__(self, x, y=None, weights=None, stream=None):
+        import torch
+        U_in, core, U_out = weights if weights is not None else self._weights
+        if y is None:
+            y = torch.empty((self.shape.batch, self.shape.N, self.Ho, self.Wo), device=x.device,
+                            dtype=torch.float32)
+        B.tdc_conv_tucker2(self.plan, x, U_in, core, U_out, y, self.shape, stream)
+        return y
+
+    def close(self) -> None:
+        if self.plan is not None:
+            B.tdc_plan_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,119 @@
+"""The C-ABI library without a GPU: it loads, exports what the header declares, and its host
+logic (validation, status strings, output-size rule, selector) behaves.  No compute calls."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2211_03715_amd import binding as B
+from paper_2211_03715_amd.workloads import config_layers
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "tdc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tdc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    lib = B.load()
+    names = _declared()
+    assert "tdc_conv_tucker2" in names and "tdc_plan_create" in names and "tdc_plan_destroy" in names
+    for n in names:
+        assert hasattr(lib, n), "libtdc.so does not export %s" % n
+    assert sorted(B.EXPORTS) == names, "binding.EXPORTS and include/tdc.h disagree"
+    for n in names:
+        assert hasattr(B, n), "binding has no wrapper named %s" % n
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(B.tdc_shape) == 11 * 4
+    assert ctypes.sizeof(B.tdc_tuning) == 12 * 4
+
+
+def test_status_strings_and_version():
+    assert B.tdc_version() >= 100
+    seen = set()
+    for code in range(0, -8, -1):
+        s = B.status_string(code)
+        assert s and s != "unknown status" and s not in seen
+        seen.add(s)
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_out_size_rule():
+    assert B.tdc_out_size(56, 3, 1, 1) == 56
+    assert B.tdc_out_size(56, 3, 2, 1) == 28
+    assert B.tdc_out_size(7, 3, 2, 1) == 4
+    assert B.tdc_out_size(5, 3, 1, 0) == 3
+    assert B.tdc_out_size(2, 3, 1, 0) == 0
+    assert B.tdc_out_size(0, 3, 1, 1) == 0
+
+
+def _create(shape, tuning=None):
+    lib = B.load()
+    plan = ctypes.c_void_p()
+    if tuning is None:
+        rc = lib.tdc_plan_create(ctypes.byref(plan), ctypes.byref(shape), 0)
+    else:
+        rc = lib.tdc_plan_create_tuned(ctypes.byref(plan), ctypes.byref(shape), 0, ctypes.byref(tuning))
+    return rc, plan
+
+
+def test_validation_happens_before_any_device_call():
+    lib = B.load()
+    assert lib.tdc_plan_create(None, None, 0) == B.TDC_ERR_NULL
+    bad = [B.make_shape(0, 4, 4, 8, 8, 2, 2), B.make_shape(1, 0, 4, 8, 8, 2, 2), B.make_shape(1, 4, 4, 8, 8, 0, 2),
+           B.make_shape(1, 4, 4, 8, 8, 2, 2, K=3, stride=0), B.make_shape(1, 4, 4, 8, 8, 2, 2, K=3, pad=-1),
+           B.make_shape(1, 4, 4, 2, 8, 2, 2, K=3, pad=0), B.make_shape(1, 4, 4, 8, 8, 2, 2, K=0)]
+    for s in bad:
+        rc, plan = _create(s)
+        assert rc == B.TDC_ERR_BAD_SHAPE and not plan.value
+    unsupported = [B.make_shape(1, 4, 4, 8, 8, 2, 2, layout=1), B.make_shape(1, 4, 4, 8, 8, 2, 2, K=9, pad=4),
+                   B.make_shape(1, 4, 4, 8, 8, 2, 2, stride=5), B.make_shape(1, 4, 4, 8, 8, 2, 2, K=3, pad=3),
+                   B.make_shape(4096, 1024, 4, 1024, 1024, 2, 2)]
+    for s in unsupported:
+        rc, plan = _create(s)
+        assert rc == B.TDC_ERR_UNSUPPORTED and not plan.value
+    # calls on a NULL plan
+    s = B.make_shape(1, 4, 4, 8, 8, 2, 2)
+    assert lib.tdc_conv_tucker2(None, None, None, None, None, None, None, ctypes.byref(s)) == B.TDC_ERR_NULL
+    assert lib.tdc_plan_pack_weights(None, None, None, None, None) == B.TDC_ERR_NULL
+    assert lib.tdc_plan_destroy(None) == B.TDC_OK
+    assert lib.tdc_plan_get_tuning(None, None) == B.TDC_ERR_NULL
+    assert lib.tdc_plan_workspace_bytes(None) == 0
+
+
+def test_selector_fills_a_launchable_tuning_for_every_workload():
+    for cfg in range(1, 6):
+        for L in config_layers(cfg):
+            t = B.tdc_select_tuning(B.make_shape(**L.asdict()))
+            d = t.as_dict()
+            assert d["variant"] in ("split", "fused"), d
+            assert all(1 <= w <= 8 for w in d["waves"]) and all(m in (1, 2, 4) for m in d["mb"])
+            if d["variant"] == "fused":
+                assert 1 <= d["tile_h"] <= L.Ho and 1 <= d["tile_w"] <= L.Wo
+
+
+def test_selector_respects_forced_fields_and_rejects_misfits():
+    L = config_layers(1)[0]
+    s = B.make_shape(**L.asdict())
+    t = B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_FUSED, tile_h=8, tile_w=8, waves=(4, 0, 0)))
+    assert (t.variant, t.tile_h, t.tile_w, t.waves[0]) == (B.VARIANT_FUSED, 8, 8, 4)
+    t = B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_SPLIT, mb=(2, 1, 4), pb=(2, 2, 1)))
+    assert t.variant == B.VARIANT_SPLIT and list(t.mb) == [2, 1, 4] and list(t.pb) == [2, 2, 1]
+    with pytest.raises(B.TdcError) as e:
+        B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_SPLIT, mb=(3, 1, 1)))
+    assert e.value.status == B.TDC_ERR_BAD_TUNING
+    with pytest.raises(B.TdcError):   # LDS budget too small for any fused tile
+        B.tdc_select_tuning(s, lds_bytes=2048, tuning=B.make_tuning(variant=B.VARIANT_FUSED))
+    with pytest.raises(B.TdcError):
+        B.tdc_select_tuning(s, tuning=B.make_tuning(variant=9))
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(RuntimeError):
+        B.load(str(tmp_path / "libtdc.so"))

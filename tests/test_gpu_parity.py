@@ -1,0 +1,191 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle, element by element.
+
+Every case prints its name before it touches the GPU, so that a fault names its case.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2211_03715_amd import binding as B
+from paper_2211_03715_amd.workloads import Layer, config_layers, layer_seed, make_inputs
+from parity_util import assert_parity, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = {"naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT, "fused": B.VARIANT_FUSED, "auto": B.VARIANT_AUTO}
+
+
+def _announce(*parts):
+    print("[case]", *parts, flush=True)
+    sys.stdout.flush()
+
+
+def _oracle(orc, layer, inputs):
+    y, _ = orc.conv_factored(orc.Shape(**layer.asdict()), **inputs)
+    return y
+
+
+# Small shapes that still span several 16-wide blocks and ragged tails in every dimension.
+SMALL = [
+    Layer(1, 5, 7, 6, 9, 3, 4),                 # nothing a multiple of anything
+    Layer(2, 20, 24, 19, 23, 17, 33),           # ranks just over a 16-block, odd image
+    Layer(1, 64, 64, 56, 56, 16, 16),           # the primary case
+    Layer(3, 33, 18, 12, 40, 8, 40, 3, 2, 1),   # stride 2, asymmetric ranks, batch 3
+    Layer(1, 16, 16, 9, 9, 16, 16, 3, 1, 0),    # no padding
+    Layer(2, 12, 10, 7, 5, 4, 6, 1, 1, 0),      # 1x1 core
+    Layer(1, 8, 8, 11, 13, 5, 3, 5, 1, 2),      # 5x5 core
+    Layer(1, 6, 9, 10, 10, 2, 2, 3, 3, 1),      # stride 3
+    Layer(1, 3, 2, 1, 1, 1, 1, 1, 1, 0),        # a single pixel
+    Layer(1, 4, 4, 3, 3, 2, 2, 3, 1, 1),        # image smaller than any tile
+    Layer(1, 40, 24, 16, 16, 32, 48, 3, 2, 1),
+]
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("layer", SMALL, ids=lambda l: l.name())
+def test_small_shapes(orc, variant, layer):
+    _announce("small", variant, layer.name())
+    inputs = make_inputs(layer, 1234)
+    want = _oracle(orc, layer, inputs)
+    got, desc = run_gpu(layer, inputs, B.make_tuning(variant=VARIANTS[variant]))
+    e = assert_parity(got, want, "%s %s [%s]" % (variant, layer.name(), desc))
+    print("   ", desc, "E_inf=%.2e E_el=%.2e" % e, flush=True)
+
+
+FORCED = [
+    ("fused_8x8_w4", dict(variant=B.VARIANT_FUSED, tile_h=8, tile_w=8, waves=(4, 4, 4), mb=(1, 1, 1), pb=(1, 1, 1))),
+    ("fused_4x16_w8", dict(variant=B.VARIANT_FUSED, tile_h=4, tile_w=16, waves=(8, 8, 8), mb=(2, 2, 4), pb=(1, 1, 1))),
+    ("fused_7x7_w2_pb2", dict(variant=B.VARIANT_FUSED, tile_h=7, tile_w=7, waves=(2, 2, 2), mb=(2, 2, 2), pb=(2, 2, 2))),
+    ("fused_3x5_w1", dict(variant=B.VARIANT_FUSED, tile_h=3, tile_w=5, waves=(1, 1, 1), mb=(4, 4, 4), pb=(2, 2, 2))),
+    ("fused_16x32_w4", dict(variant=B.VARIANT_FUSED, tile_h=16, tile_w=32, waves=(4, 4, 4), mb=(4, 4, 4), pb=(1, 1, 1))),
+    ("split_111_w1", dict(variant=B.VARIANT_SPLIT, waves=(1, 1, 1), mb=(1, 1, 1), pb=(1, 1, 1))),
+    ("split_w8", dict(variant=B.VARIANT_SPLIT, waves=(8, 8, 8), mb=(1, 2, 4), pb=(4, 2, 1))),
+    ("split_w3_44", dict(variant=B.VARIANT_SPLIT, waves=(3, 4, 2), mb=(4, 4, 4), pb=(4, 4, 4))),
+    ("split_w2_24", dict(variant=B.VARIANT_SPLIT, waves=(2, 4, 1), mb=(2, 4, 2), pb=(1, 1, 2))),
+]
+FORCED_LAYERS = [Layer(2, 20, 24, 19, 23, 17, 33), Layer(1, 64, 64, 56, 56, 16, 16),
+                 Layer(2, 33, 18, 12, 40, 8, 40, 3, 2, 1), Layer(1, 256, 256, 14, 14, 64, 64)]
+
+
+@pytest.mark.parametrize("name,tuning", FORCED, ids=[f[0] for f in FORCED])
+@pytest.mark.parametrize("layer", FORCED_LAYERS, ids=lambda l: l.name())
+def test_forced_tunings(orc, name, tuning, layer):
+    """Every register-tile shape, wave count and tile geometry the selector may pick."""
+    _announce("forced", name, layer.name())
+    inputs = make_inputs(layer, 77)
+    want = _oracle(orc, layer, inputs)
+    try:
+        got, desc = run_gpu(layer, inputs, B.make_tuning(**tuning))
+    except B.TdcError as e:
+        if e.status == B.TDC_ERR_BAD_TUNING and name == "fused_16x32_w4":
+            pytest.skip("tile does not fit the LDS budget for this layer")   # the library said so, nothing ran
+        raise
+    assert_parity(got, want, "%s %s [%s]" % (name, layer.name(), desc))
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_full_size_workloads(orc, cfg):
+    """Every layer of the five synthetic workloads at full size, in the launch configuration the
+    benchmark times (selector's choice, weights re-laid out once), compared element by element."""
+    worst = (0.0, 0.0)
+    for i, layer in enumerate(config_layers(cfg)):
+        _announce("config", cfg, "layer", i, layer.name())
+        inputs = make_inputs(layer, layer_seed(cfg, i))
+        want = _oracle(orc, layer, inputs)
+        got, desc = run_gpu(layer, inputs, None)
+        e = assert_parity(got, want, "config %d layer %d %s [%s]" % (cfg, i, layer.name(), desc))
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+        print("   ", desc, "E_inf=%.2e E_el=%.2e" % e, flush=True)
+    print("[config %d] worst E_inf=%.2e E_el=%.2e" % ((cfg,) + worst), flush=True)
+
+
+@pytest.mark.parametrize("variant", ["split", "fused"])
+def test_dense_path_agrees_too(orc, variant):
+    """The GPU result also matches the dense convolution with the kernel of Eq. 1."""
+    layer = Layer(1, 24, 20, 14, 14, 12, 9)
+    _announce("dense", variant, layer.name())
+    inputs = make_inputs(layer, 5)
+    want, _ = orc.conv_dense(orc.Shape(**layer.asdict()), **inputs)
+    got, desc = run_gpu(layer, inputs, B.make_tuning(variant=VARIANTS[variant]))
+    assert_parity(got, want, desc)
+
+
+@pytest.mark.parametrize("variant", ["naive", "split", "fused"])
+def test_unpacked_weights_path(orc, variant):
+    """Without tdc_plan_pack_weights the library re-lays the weights out on every call."""
+    layer = Layer(2, 20, 24, 19, 23, 17, 33)
+    _announce("unpacked", variant, layer.name())
+    inputs = make_inputs(layer, 9)
+    want = _oracle(orc, layer, inputs)
+    got, desc = run_gpu(layer, inputs, B.make_tuning(variant=VARIANTS[variant]), pack=False)
+    assert_parity(got, want, desc)
+
+
+def test_repacking_after_weight_change_and_determinism(orc):
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    layer = Layer(1, 64, 64, 28, 28, 16, 32)
+    _announce("repack+determinism", layer.name())
+    dev = torch.device("cuda:0")
+    for variant in (B.VARIANT_SPLIT, B.VARIANT_FUSED):
+        a = make_inputs(layer, 11)
+        b = make_inputs(layer, 12)
+        ta = {k: torch.from_numpy(v).to(dev) for k, v in a.items()}
+        conv = TuckerConv2d(layer, 0, B.make_tuning(variant=variant))
+        conv.pack(ta["U_in"], ta["core"], ta["U_out"])
+        y0 = conv(ta["x"]).clone()
+        for _ in range(10):   # no atomics anywhere: repeated runs are bit-identical
+            assert torch.equal(conv(ta["x"]), y0)
+        assert_parity(y0.cpu().numpy(), _oracle(orc, layer, a), conv.describe())
+        # new weight values in the same buffers, then pack again
+        for k in ("U_in", "core", "U_out"):
+            ta[k].copy_(torch.from_numpy(b[k]))
+        conv.pack(ta["U_in"], ta["core"], ta["U_out"])
+        y1 = conv(ta["x"])
+        torch.cuda.synchronize()
+        assert_parity(y1.cpu().numpy(), _oracle(orc, layer, dict(b, x=a["x"])), conv.describe())
+        conv.close()
+
+
+def test_linearity_and_batch_independence_on_gpu(orc):
+    layer = Layer(4, 32, 48, 14, 14, 16, 16)
+    _announce("linearity/batch", layer.name())
+    one = Layer(1, 32, 48, 14, 14, 16, 16)
+    inputs = make_inputs(layer, 21)
+    for variant in (B.VARIANT_SPLIT, B.VARIANT_FUSED):
+        yb, _ = run_gpu(layer, inputs, B.make_tuning(variant=variant))
+        for b in range(4):
+            y1, _ = run_gpu(one, dict(inputs, x=inputs["x"][b:b + 1].copy()), B.make_tuning(variant=variant))
+            assert_parity(y1[0], yb[b].astype(np.float64), "image %d" % b)
+        y2, _ = run_gpu(layer, dict(inputs, x=(2.0 * inputs["x"]).astype(np.float32)), B.make_tuning(variant=variant))
+        assert np.array_equal(y2, 2.0 * yb), "scaling x by 2 must scale y by exactly 2"
+
+
+def test_error_paths_on_device():
+    import ctypes
+    import torch
+    layer = Layer(1, 8, 8, 6, 6, 4, 4)
+    _announce("errors", layer.name())
+    lib = B.load()
+    s = B.make_shape(**layer.asdict())
+    plan = B.tdc_plan_create(s, 0)
+    t = {k: torch.from_numpy(v).cuda() for k, v in make_inputs(layer, 1).items()}
+    y = torch.empty((1, 8, 6, 6), device="cuda")
+    other = B.make_shape(1, 8, 8, 6, 7, 4, 4)
+    st = torch.cuda.current_stream().cuda_stream
+    args = [t["x"].data_ptr(), t["U_in"].data_ptr(), t["core"].data_ptr(), t["U_out"].data_ptr(), y.data_ptr()]
+    assert lib.tdc_conv_tucker2(plan, st, *args, ctypes.byref(other)) == B.TDC_ERR_SHAPE_MISMATCH
+    for i in range(5):
+        a = list(args)
+        a[i] = None
+        assert lib.tdc_conv_tucker2(plan, st, *a, ctypes.byref(s)) == B.TDC_ERR_NULL
+    assert lib.tdc_conv_tucker2(plan, st, *args, None) == B.TDC_ERR_NULL
+    assert lib.tdc_conv_tucker2(plan, st, *args, ctypes.byref(s)) == B.TDC_OK
+    assert B.tdc_plan_workspace_bytes(plan) > 0 and B.tdc_plan_kernel_count(plan) in (1, 3)
+    p2 = ctypes.c_void_p()
+    assert lib.tdc_plan_create(ctypes.byref(p2), ctypes.byref(s), 99) == B.TDC_ERR_HIP
+    with pytest.raises(B.TdcError):
+        B.tdc_plan_create(s, 0, B.make_tuning(variant=B.VARIANT_FUSED, tile_h=64, tile_w=64))
+    torch.cuda.synchronize()
+    B.tdc_plan_destroy(plan)
