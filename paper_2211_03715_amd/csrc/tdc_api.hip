@@ -57,6 +57,11 @@ int validate(const tdc_shape &s)
     if ((double)s.batch * s.C * s.H * s.W >= lim || (double)s.batch * np * Ho * Wo >= lim) return TDC_ERR_UNSUPPORTED;
     if ((double)s.batch * r1p * s.H * s.W >= lim || (double)s.batch * r2p * Ho * Wo >= lim) return TDC_ERR_UNSUPPORTED;
     if ((double)cp * r1p >= lim || (double)r1p * r2p * s.K * s.K >= lim || (double)r2p * np >= lim) return TDC_ERR_UNSUPPORTED;
+    // one image of any activation and each re-laid-out weight array must fit a 2 GiB buffer descriptor
+    const double lim4 = (double)lim / 4;
+    if ((double)s.C * s.H * s.W >= lim4 || (double)r1p * s.H * s.W >= lim4 || (double)r2p * Ho * Wo >= lim4) return TDC_ERR_UNSUPPORTED;
+    if ((double)cp * r1p >= lim4 || (double)r1p * r2p * s.K * s.K >= lim4 || (double)r2p * np >= lim4) return TDC_ERR_UNSUPPORTED;
+    if (s.batch > 65535) return TDC_ERR_UNSUPPORTED;   // images ride in the grid's y dimension
     return TDC_OK;
 }
 
@@ -78,6 +83,9 @@ int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
     if (t.variant == TDC_VARIANT_NAIVE) return TDC_OK;
     for (int i = 0; i < 3; ++i)
         if (t.waves[i] < 1 || t.waves[i] > 8) return TDC_ERR_BAD_TUNING;
+    const int nb[3] = {p.dims.NB1, p.dims.NB2, p.dims.NB3};
+    for (int i = 0; i < 3; ++i)
+        if (t.mb[i] < 1 || nb[i] % t.mb[i]) return TDC_ERR_BAD_TUNING;   // whole register tiles only
     if (t.variant == TDC_VARIANT_SPLIT) {
         for (int i = 0; i < 3; ++i) {
             if (!tdc_gemm_unit_supported(t.mb[i], t.pb[i])) return TDC_ERR_BAD_TUNING;
@@ -100,9 +108,9 @@ void describe(tdc_plan &p)
     const char *names[] = {"auto", "naive", "split", "fused"};
     if (t.variant == TDC_VARIANT_FUSED)
         snprintf(p.desc, sizeof(p.desc),
-                 "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB",
+                 "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB%s",
                  t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.mb[1], t.mb[2], t.pb[0],
-                 p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes);
+                 p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes, p.geom.weights_in_lds ? " wlds" : "");
     else if (t.variant == TDC_VARIANT_SPLIT)
         snprintf(p.desc, sizeof(p.desc), "split stage(mb,pb,waves)= s1(%d,%d,%d) s2(%d,%d,%d) s3(%d,%d,%d)",
                  t.mb[0], t.pb[0], t.waves[0], t.mb[1], t.pb[1], t.waves[1], t.mb[2], t.pb[2], t.waves[2]);
@@ -168,7 +176,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     }
     rc = tdc_select(p->dims, dev, &p->tuning);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)
-        p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w);
+        p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK) rc = check_tuning(*p, dev);
     if (rc != TDC_OK) {
         delete p;
@@ -216,7 +224,7 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     tmp.tuning = *inout;
     rc = tdc_select(tmp.dims, dev, &tmp.tuning);
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED)
-        tmp.geom = tdc_fused_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w);
+        tmp.geom = tdc_fused_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK) rc = check_tuning(tmp, dev);
     if (rc == TDC_OK) *inout = tmp.tuning;
     return rc;

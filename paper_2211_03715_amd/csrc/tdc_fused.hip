@@ -19,8 +19,36 @@
 //
 // Each stage's 16x16 output blocks are grouped into MB x PB register tiles ("units") and the
 // units are dealt round-robin to the wavefronts of the workgroup.
+//
+// Latency discipline (a batch-1 layer is a few hundred MFMAs per wavefront, so memory round
+// trips, not arithmetic, set the time): every wavefront first issues the loads of its first
+// stage-1 tile (x and U_in, straight from global memory), then the workgroup copies the core
+// and U_out weights into LDS while those loads are in flight (template flag WLDS; when the
+// weights do not fit, stages 2 and 3 stream them from L2 through the same register pipeline).
+// After that, stages 2 and 3 touch only LDS.
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
+
+// Phase timestamps for kernel bring-up: compiled in only with -DTDC_PHASE_TIMING (never in the
+// shipped library).  Slot s of wavefront w of workgroup b lands in tdc_probe_buf[((b*8+w)*8+s)*2 + {0,1}]
+// as (shader clock, 100 MHz wall clock).
+#ifdef TDC_PHASE_TIMING
+__device__ unsigned long long tdc_probe_buf[2 * 8 * 8 * 4096];
+#define TDC_PROBE(slot)                                                                             \
+    do {                                                                                            \
+        if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096 && blockIdx.y == 0) {                      \
+            const size_t o = (((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 8 + (slot)) * 2;      \
+            tdc_probe_buf[o] = clock64();                                                           \
+            tdc_probe_buf[o + 1] = wall_clock64();                                                  \
+        }                                                                                           \
+    } while (0)
+extern "C" int tdc_debug_read_probes(unsigned long long *host, size_t count)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(tdc_probe_buf), count * sizeof(unsigned long long)) == hipSuccess ? 0 : -1;
+}
+#else
+#define TDC_PROBE(slot) do { } while (0)
+#endif
 
 namespace {
 
@@ -31,136 +59,183 @@ struct FusedArgs {
     int NB1, NB2, NB3, KG1;
     int TH, TW, QW, Q, P, QB, PBk;
     int tiles_x;
-    int pitch1, pitch2;
+    int pitch1, pitch2;     // LDS row pitches of the z1 / z2 tiles, in 16-byte units
+    int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
 };
 
-template <int MB1, int MB2, int MB3, int PB>
+// LDS tiles hold 16-byte cells: cell (cb, g, col) = channels 16*cb + 4*g + {0,1,2,3} of pixel col,
+// i.e. exactly the four accumulator registers of lane (g, col%16) for channel block cb, and
+// exactly the B operand of the next stage for k-group cb (see tdc_mfma.h).
+__device__ __forceinline__ int tdc_cell(int cb, int g, int pitch, int col) { return (cb * 4 + g) * pitch + col; }
+
+template <int MB1, int MB2, int MB3, int PB, bool WLDS>
 __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
 {
-    extern __shared__ float lds[];
-    float *__restrict__ z1s = lds;                              // [16*NB1][pitch1]
-    float *__restrict__ z2s = lds + (size_t)16 * a.NB1 * a.pitch1;  // [16*NB2][pitch2]
+    extern __shared__ tdc_f4 lds4[];
+    tdc_f4 *__restrict__ z1s = lds4;                                  // [NB1][4][pitch1]
+    tdc_f4 *__restrict__ z2s = z1s + (size_t)4 * a.NB1 * a.pitch1;    // [NB2][4][pitch2]
+    tdc_f4 *__restrict__ wC = z2s + (size_t)4 * a.NB2 * a.pitch2;     // packed core   (WLDS)
+    tdc_f4 *__restrict__ wO = wC + a.w_core4;                         // packed U_out  (WLDS)
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int g = lane >> 4, l16 = lane & 15;
     const int ty = blockIdx.x / a.tiles_x, tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
     const int i0 = ty * a.TH, j0 = tx * a.TW;                   // first output pixel of the tile
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;  // first input pixel (may be < 0)
     const int HW = a.H * a.W;
 
+    TDC_PROBE(0);
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
-        const float *__restrict__ xb = a.x + (size_t)b * a.C * HW;
-        const int n_pg = (a.QB + PB - 1) / PB, n_mg = (a.NB1 + MB1 - 1) / MB1;
-        for (int u = wave; u < n_pg * n_mg; u += nw) {
-            const int pg = u % n_pg, mg = u / n_pg;
-            const int mvalid = min(MB1, a.NB1 - mg * MB1);
-            int xoff[PB];
-            bool ok[PB];
+        constexpr int U = 4;
+        const tdc_rsrc xrs = tdc_make_rsrc(a.x + (size_t)b * a.C * HW, (unsigned)a.C * HW * 4u);
+        const tdc_rsrc urs = tdc_make_rsrc(a.uin_p, (unsigned)a.NB1 * a.KG1 * 1024u);
+        const int n_pg = (a.QB + PB - 1) / PB, n_mg = a.NB1 / MB1;
+        const int n_units = n_pg * n_mg;
+        int pg = 0, mg = 0, kg = 0;
+        unsigned xoff[PB];       // byte offset of this lane's pixel in a channel row, or TDC_OOB
+        const auto setup = [&](int u) {
+            pg = u % n_pg;
+            mg = u / n_pg;
+            kg = 0;
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const int q = 16 * (pg * PB + pb) + l16;
                 const int qh = q / a.QW, qw = q - qh * a.QW;
                 const int h = h0 + qh, w = w0 + qw;
-                ok[pb] = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
-                xoff[pb] = h * a.W + w;
+                const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
+                xoff[pb] = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
+            }
+        };
+        auto next = [&](tdc_f4(&av)[MB1], tdc_f4(&bv)[PB]) {
+            const unsigned dead = kg < a.KG1 ? 0u : TDC_OOB;
+#pragma unroll
+            for (int mb = 0; mb < MB1; ++mb)
+                av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
+            // channels past C lie beyond the descriptor and read as 0 by themselves
+            const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) {
+                const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
+                bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
+                                  tdc_buf_load(xrs, o + 12u * HW)};
+            }
+            ++kg;
+        };
+        TdcPipe<MB1, PB, U> pipe;
+        int u = wave;
+        if (u < n_units) {
+            setup(u);
+            pipe.start(next);          // in flight while the weights are copied
+        }
+        TDC_PROBE(1);
+        if (WLDS) {
+            // core and U_out: global -> registers -> LDS, 8 x 16 bytes per thread and round
+            constexpr int CH = 8;
+            const tdc_f4 *__restrict__ src[2] = {reinterpret_cast<const tdc_f4 *>(a.core_p),
+                                                 reinterpret_cast<const tdc_f4 *>(a.uout_p)};
+            tdc_f4 *dst[2] = {wC, wO};
+            const int cnt[2] = {a.w_core4, a.w_uout4};
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                for (int base = threadIdx.x; base < cnt[t]; base += CH * blockDim.x) {
+                    tdc_f4 tmp[CH];
+#pragma unroll
+                    for (int c = 0; c < CH; ++c) tmp[c] = src[t][min(base + c * (int)blockDim.x, cnt[t] - 1)];
+#pragma unroll
+                    for (int c = 0; c < CH; ++c) {
+                        const int i = base + c * blockDim.x;
+                        if (i < cnt[t]) dst[t][i] = tmp[c];
+                    }
+                }
+        }
+        TDC_PROBE(2);
+        for (; u < n_units; u += nw) {
+            if (u != wave) {
+                setup(u);
+                pipe.start(next);
             }
             tdc_f4 acc[MB1][PB];
-#pragma unroll
-            for (int mb = 0; mb < MB1; ++mb)
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = (tdc_f4){0.f, 0.f, 0.f, 0.f};
-            for (int kg = 0; kg < a.KG1; ++kg) {
-                float bv[PB][4];
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int c = 16 * kg + 4 * j + g;
-                        bv[pb][j] = (ok[pb] && c < a.C) ? xb[(size_t)c * HW + xoff[pb]] : 0.f;
-                    }
-                tdc_f4 av[MB1];
-#pragma unroll
-                for (int mb = 0; mb < MB1; ++mb)
-                    av[mb] = (mb < mvalid) ? tdc_load_a4(a.uin_p, mg * MB1 + mb, a.KG1, kg, lane)
-                                           : (tdc_f4){0.f, 0.f, 0.f, 0.f};
-                tdc_mma_group<MB1, PB>(acc, av, bv, mvalid);
-            }
+            tdc_zero<MB1, PB>(acc);
+            pipe.run(acc, a.KG1, next);
 #pragma unroll
             for (int mb = 0; mb < MB1; ++mb)
 #pragma unroll
                 for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int row = 16 * (mg * MB1 + mb) + 4 * g + i;
-                        const int col = 16 * (pg * PB + pb) + l16;
-                        if (mb < mvalid && pg * PB + pb < a.QB) z1s[row * a.pitch1 + col] = acc[mb][pb][i];
-                    }
+                    if (pg * PB + pb < a.QB)
+                        z1s[tdc_cell(mg * MB1 + mb, g, a.pitch1, 16 * (pg * PB + pb) + l16)] = acc[mb][pb];
         }
     }
+    TDC_PROBE(3);
     __syncthreads();
+    TDC_PROBE(4);
 
     // ------------------------------------------------------------------ stage 2 (Eq. 3)
     {
-        const int n_pg = (a.PBk + PB - 1) / PB, n_mg = (a.NB2 + MB2 - 1) / MB2;
+        constexpr int U = WLDS ? 1 : 4;
+        const int n_pg = (a.PBk + PB - 1) / PB, n_mg = a.NB2 / MB2;
         const int KG2 = a.K * a.K * a.NB1;
+        const tdc_rsrc wrs = tdc_make_rsrc(a.core_p, (unsigned)a.w_core4 * 16u);
         for (int u = wave; u < n_pg * n_mg; u += nw) {
             const int pg = u % n_pg, mg = u / n_pg;
-            const int mvalid = min(MB2, a.NB2 - mg * MB2);
             int qbase[PB];
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const int p = 16 * (pg * PB + pb) + l16;
                 const int ph = p / a.TW, pw = p - ph * a.TW;
-                qbase[pb] = p < a.P ? ph * a.stride * a.QW + pw * a.stride : 0;
+                qbase[pb] = g * a.pitch1 + (p < a.P ? ph * a.stride * a.QW + pw * a.stride : 0);
             }
-            tdc_f4 acc[MB2][PB];
+            int kg = 0, dg = 0, s = 0, toff = 0;     // toff = r*QW + s
+            auto next = [&](tdc_f4(&av)[MB2], tdc_f4(&bv)[PB]) {
+                const bool live = kg < KG2;
 #pragma unroll
-            for (int mb = 0; mb < MB2; ++mb)
+                for (int mb = 0; mb < MB2; ++mb) {
+                    const int frag = (mg * MB2 + mb) * KG2 + kg;
+                    // WLDS: a dead fetch is never multiplied (one k-group per buffer), it only has to stay in range
+                    if (WLDS) av[mb] = wC[(live ? frag : 0) * 64 + lane];
+                    else av[mb] = tdc_buf_load4(wrs, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
+                }
+                const int cell = live ? dg * 4 * a.pitch1 + toff : 0;
 #pragma unroll
-                for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = (tdc_f4){0.f, 0.f, 0.f, 0.f};
-            for (int r = 0; r < a.K; ++r)
-                for (int s = 0; s < a.K; ++s) {
-                    const int toff = r * a.QW + s;
-                    const int kgt = (r * a.K + s) * a.NB1;
-                    for (int dg = 0; dg < a.NB1; ++dg) {
-                        float bv[PB][4];
-#pragma unroll
-                        for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                bv[pb][j] = z1s[(16 * dg + 4 * j + g) * a.pitch1 + qbase[pb] + toff];
-                        tdc_f4 av[MB2];
-#pragma unroll
-                        for (int mb = 0; mb < MB2; ++mb)
-                            av[mb] = (mb < mvalid) ? tdc_load_a4(a.core_p, mg * MB2 + mb, KG2, kgt + dg, lane)
-                                                   : (tdc_f4){0.f, 0.f, 0.f, 0.f};
-                        tdc_mma_group<MB2, PB>(acc, av, bv, mvalid);
+                for (int pb = 0; pb < PB; ++pb) bv[pb] = z1s[cell + qbase[pb]];
+                ++kg;
+                if (++dg == a.NB1) {
+                    dg = 0;
+                    ++toff;
+                    if (++s == a.K) {
+                        s = 0;
+                        toff += a.QW - a.K;
                     }
                 }
+            };
+            TdcPipe<MB2, PB, U> pipe;
+            tdc_f4 acc[MB2][PB];
+            tdc_zero<MB2, PB>(acc);
+            pipe.start(next);
+            pipe.run(acc, KG2, next);
 #pragma unroll
             for (int mb = 0; mb < MB2; ++mb)
 #pragma unroll
                 for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int row = 16 * (mg * MB2 + mb) + 4 * g + i;
-                        const int col = 16 * (pg * PB + pb) + l16;
-                        if (mb < mvalid && pg * PB + pb < a.PBk) z2s[row * a.pitch2 + col] = acc[mb][pb][i];
-                    }
+                    if (pg * PB + pb < a.PBk)
+                        z2s[tdc_cell(mg * MB2 + mb, g, a.pitch2, 16 * (pg * PB + pb) + l16)] = acc[mb][pb];
         }
     }
+    TDC_PROBE(5);
     __syncthreads();
+    TDC_PROBE(6);
 
     // ------------------------------------------------------------------ stage 3 (Eq. 4)
     {
-        const int n_pg = (a.PBk + PB - 1) / PB, n_mg = (a.NB3 + MB3 - 1) / MB3;
+        constexpr int U = WLDS ? 1 : 4;
+        const int n_pg = (a.PBk + PB - 1) / PB, n_mg = a.NB3 / MB3;
         const int P2 = a.Ho * a.Wo;
         float *__restrict__ yb = a.y + (size_t)b * a.N * P2;
+        const tdc_rsrc wrs = tdc_make_rsrc(a.uout_p, (unsigned)a.w_uout4 * 16u);
         for (int u = wave; u < n_pg * n_mg; u += nw) {
             const int pg = u % n_pg, mg = u / n_pg;
-            const int mvalid = min(MB3, a.NB3 - mg * MB3);
-            int yoff[PB];
+            int yoff[PB], col[PB];
             bool ok[PB];
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
@@ -169,28 +244,27 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
                 const int i = i0 + ph, j = j0 + pw;
                 ok[pb] = p < a.P && i < a.Ho && j < a.Wo;
                 yoff[pb] = i * a.Wo + j;
+                col[pb] = g * a.pitch2 + min(16 * (pg * PB + pb), 16 * (a.PBk - 1)) + l16;
             }
+            int kg = 0;
+            auto next = [&](tdc_f4(&av)[MB3], tdc_f4(&bv)[PB]) {
+                const bool live = kg < a.NB2;
+                const int kgc = live ? kg : 0;
+#pragma unroll
+                for (int mb = 0; mb < MB3; ++mb) {
+                    const int frag = (mg * MB3 + mb) * a.NB2 + kg;
+                    if (WLDS) av[mb] = wO[(live ? frag : 0) * 64 + lane];
+                    else av[mb] = tdc_buf_load4(wrs, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
+                }
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb) bv[pb] = z2s[kgc * 4 * a.pitch2 + col[pb]];
+                ++kg;
+            };
+            TdcPipe<MB3, PB, U> pipe;
             tdc_f4 acc[MB3][PB];
-#pragma unroll
-            for (int mb = 0; mb < MB3; ++mb)
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = (tdc_f4){0.f, 0.f, 0.f, 0.f};
-            for (int kg = 0; kg < a.NB2; ++kg) {
-                float bv[PB][4];
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int col = min(16 * (pg * PB + pb), 16 * (a.PBk - 1)) + l16;
-                        bv[pb][j] = z2s[(16 * kg + 4 * j + g) * a.pitch2 + col];
-                    }
-                tdc_f4 av[MB3];
-#pragma unroll
-                for (int mb = 0; mb < MB3; ++mb)
-                    av[mb] = (mb < mvalid) ? tdc_load_a4(a.uout_p, mg * MB3 + mb, a.NB2, kg, lane)
-                                           : (tdc_f4){0.f, 0.f, 0.f, 0.f};
-                tdc_mma_group<MB3, PB>(acc, av, bv, mvalid);
-            }
+            tdc_zero<MB3, PB>(acc);
+            pipe.start(next);
+            pipe.run(acc, a.NB2, next);
 #pragma unroll
             for (int mb = 0; mb < MB3; ++mb)
 #pragma unroll
@@ -198,10 +272,11 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int n = 16 * (mg * MB3 + mb) + 4 * g + i;
-                        if (mb < mvalid && ok[pb] && n < a.N) yb[(size_t)n * P2 + yoff[pb]] = acc[mb][pb][i];
+                        if (ok[pb] && n < a.N) yb[(size_t)n * P2 + yoff[pb]] = acc[mb][pb][i];
                     }
         }
     }
+    TDC_PROBE(7);
 }
 
 #define TDC_FUSED_MENU(X) X(1, 1, 1, 1) X(1, 1, 2, 1) X(2, 2, 2, 1) X(2, 2, 4, 1) X(4, 4, 4, 1) \
@@ -219,14 +294,12 @@ bool tdc_fused_unit_supported(int mb1, int mb2, int mb3, int pb)
 
 static int round_pitch(int cols)
 {
-    // smallest pitch >= cols with pitch % 32 == 16: the two 16-lane groups served in one LDS
-    // pass (rows k and k+1 of a B operand) then fall into disjoint banks
-    int p = (cols + 31) / 32 * 32 + 16;
-    if (p - 32 >= cols) p -= 32;
-    return p;
+    // row pitch of an LDS tile in 16-byte cells: the columns plus 4 cells (64 bytes), so that
+    // the four lane groups of one access start in different banks
+    return cols + 4;
 }
 
-TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w)
+TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit)
 {
     TdcFusedGeom g;
     g.TH = tile_h;
@@ -240,7 +313,10 @@ TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w)
     g.tiles_y = (d.Ho + tile_h - 1) / tile_h;
     g.pitch1 = round_pitch(16 * g.QB);
     g.pitch2 = round_pitch(16 * g.PBk);
-    g.lds_bytes = ((size_t)16 * d.NB1 * g.pitch1 + (size_t)16 * d.NB2 * g.pitch2) * sizeof(float);
+    const size_t tiles = ((size_t)16 * d.NB1 * g.pitch1 + (size_t)16 * d.NB2 * g.pitch2) * sizeof(float);
+    const size_t weights = (tdc_packed_floats_core(d) + tdc_packed_floats_uout(d)) * sizeof(float);
+    g.weights_in_lds = tiles + weights <= (size_t)lds_limit;
+    g.lds_bytes = tiles + (g.weights_in_lds ? weights : 0);
     return g;
 }
 
@@ -256,19 +332,26 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.TH = g.TH; a.TW = g.TW; a.QW = g.QW; a.Q = g.Q; a.P = g.TH * g.TW; a.QB = g.QB; a.PBk = g.PBk;
     a.tiles_x = g.tiles_x;
     a.pitch1 = g.pitch1; a.pitch2 = g.pitch2;
+    a.w_core4 = (int)(tdc_packed_floats_core(d) / 4);
+    a.w_uout4 = (int)(tdc_packed_floats_uout(d) / 4);
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
-#define TDC_X(A_, B_, C_, D_)                                                                          \
-    if (t.mb[0] == A_ && t.mb[1] == B_ && t.mb[2] == C_ && t.pb[0] == D_) {                            \
+#define TDC_LAUNCH(A_, B_, C_, D_, W_)                                                                 \
+    {                                                                                                  \
         if (g.lds_bytes > 48 * 1024) {                                                                 \
-            hipError_t e = hipFuncSetAttribute((const void *)tdc_fused_kernel<A_, B_, C_, D_>,         \
+            hipError_t e = hipFuncSetAttribute((const void *)tdc_fused_kernel<A_, B_, C_, D_, W_>,     \
                                                hipFuncAttributeMaxDynamicSharedMemorySize,             \
                                                (int)g.lds_bytes);                                      \
             if (e != hipSuccess) return e;                                                             \
         }                                                                                              \
-        hipLaunchKernelGGL((tdc_fused_kernel<A_, B_, C_, D_>), grid, block, g.lds_bytes, s, a);        \
+        hipLaunchKernelGGL((tdc_fused_kernel<A_, B_, C_, D_, W_>), grid, block, g.lds_bytes, s, a);    \
         return hipGetLastError();                                                                      \
+    }
+#define TDC_X(A_, B_, C_, D_)                                                                          \
+    if (t.mb[0] == A_ && t.mb[1] == B_ && t.mb[2] == C_ && t.pb[0] == D_) {                            \
+        if (g.weights_in_lds) TDC_LAUNCH(A_, B_, C_, D_, true) else TDC_LAUNCH(A_, B_, C_, D_, false)  \
     }
     TDC_FUSED_MENU(TDC_X)
 #undef TDC_X
+#undef TDC_LAUNCH
     return hipErrorInvalidValue;
 }

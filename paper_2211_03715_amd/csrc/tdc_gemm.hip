@@ -11,6 +11,14 @@
 // Splitting the contraction is what fills the chip on the small-image layers (14x14, 7x7),
 // where there are far fewer output blocks than SIMDs; the paper's kernel splits its input
 // channels across thread blocks for the same reason (section 5.2) but combines with atomics.
+//
+// At batch 1 a wavefront has only a handful of k-groups, so the kernel is bound by memory
+// latency, not by MFMA issue.  The inner loop is therefore branch-free (buffer loads whose
+// range check zeroes dead operands) and software-pipelined: operands are fetched U k-groups
+// at a time into two register buffers (TdcPipe), U chosen on the host so that 2*U covers the
+// wavefront's k-groups whenever they are at most eight -- one memory round trip per kernel.
+#include <algorithm>
+
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
 
@@ -25,79 +33,110 @@ struct GemmArgs {
     int act_pix;         // pixels per row in act
     int out_rows;        // channel rows per image in out (R1P, R2P, N)
     int out_pix;         // pixels per row in out
-    int NBm;             // 16-blocks of output channels
+    int NBm;             // 16-blocks of output channels (a multiple of MB)
     int KG;              // 16-wide k-groups of the contraction
     int NBk;             // stage 2: k-groups per tap (= NB1)
     int n_pgroups;
     int H, W, Wo, K, stride, pad;   // stage 2 geometry
 };
 
+// Stateful operand fetcher of one wavefront: each call returns the next k-group of its range.
 template <int MODE, int MB, int PB>
-__global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
-{
-    extern __shared__ float red[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    const int g = lane >> 4, l16 = lane & 15;
-    const int pg = blockIdx.x % a.n_pgroups, mg = blockIdx.x / a.n_pgroups, b = blockIdx.y;
-    const int mvalid = min(MB, a.NBm - mg * MB);
-
+struct GemmNext {
+    tdc_rsrc wrs, ars;                // packed weights of this tile's first m-block; activations of this image
+    unsigned wlane;                   // byte offset of this lane inside a 1 KiB weight fragment
+    unsigned wstride;                 // bytes between consecutive m-blocks (KG fragments)
+    int act_pix;
+    int kg, kg_end;                   // next k-group, end of range (wave-uniform)
+    int dg, r, s, NBk, K, H, W;       // stage 2: position of kg within (tap, d1-group)
+    int g;
     int poff[PB], ih0[PB], iw0[PB];
     bool pval[PB];
-#pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-        const int p = 16 * (pg * PB + pb) + l16;
-        pval[pb] = p < a.out_pix;
-        if (MODE == 2) {
-            const int i = p / a.Wo, j = p - i * a.Wo;
-            ih0[pb] = i * a.stride - a.pad;
-            iw0[pb] = j * a.stride - a.pad;
-            poff[pb] = ih0[pb] * a.W + iw0[pb];
-        } else {
-            ih0[pb] = iw0[pb] = 0;
-            poff[pb] = p;
-        }
-    }
-    const float *__restrict__ actb = a.act + (size_t)b * a.act_rows * a.act_pix;
 
-    tdc_f4 acc[MB][PB];
+    __device__ __forceinline__ void operator()(tdc_f4 (&av)[MB], tdc_f4 (&bv)[PB])
+    {
+        const unsigned dead = kg < kg_end ? 0u : TDC_OOB;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = (tdc_f4){0.f, 0.f, 0.f, 0.f};
-
-    const int kg0 = (int)(((long)a.KG * wave) / nw), kg1 = (int)(((long)a.KG * (wave + 1)) / nw);
-    for (int kg = kg0; kg < kg1; ++kg) {
-        float bv[PB][4];
+        for (int mb = 0; mb < MB; ++mb) av[mb] = tdc_buf_load4(wrs, (mb * wstride + (unsigned)kg * 1024u + wlane) | dead);
         if (MODE == 2) {
-            const int tap = kg / a.NBk, dg = kg - tap * a.NBk;
-            const int r = tap / a.K, s = tap - r * a.K;
-            const int toff = r * a.W + s;
+            const int toff = r * W + s;
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const int h = ih0[pb] + r, w = iw0[pb] + s;
-                const bool ok = pval[pb] && h >= 0 && h < a.H && w >= 0 && w < a.W;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int row = 16 * dg + 4 * j + g;
-                    bv[pb][j] = ok ? actb[(size_t)row * a.act_pix + poff[pb] + toff] : 0.f;
+                const bool ok = pval[pb] && h >= 0 && h < H && w >= 0 && w < W;
+                const unsigned base = (unsigned)((16 * dg + 4 * g) * act_pix + poff[pb] + toff) * 4u;
+                const unsigned bad = ok ? dead : TDC_OOB;
+                bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
+                                  tdc_buf_load(ars, (base + 8u * act_pix) | bad),
+                                  tdc_buf_load(ars, (base + 12u * act_pix) | bad)};
+            }
+            if (++dg == NBk) {
+                dg = 0;
+                if (++s == K) {
+                    s = 0;
+                    ++r;
                 }
             }
         } else {
+            // rows past the last channel lie beyond the descriptor and read as 0 by themselves
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int row = 16 * kg + 4 * j + g;
-                    const bool ok = pval[pb] && row < a.act_rows_valid;
-                    bv[pb][j] = ok ? actb[(size_t)row * a.act_pix + poff[pb]] : 0.f;
-                }
+            for (int pb = 0; pb < PB; ++pb) {
+                const unsigned base = (unsigned)((16 * kg + 4 * g) * act_pix + poff[pb]) * 4u;
+                const unsigned bad = pval[pb] ? dead : TDC_OOB;
+                bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
+                                  tdc_buf_load(ars, (base + 8u * act_pix) | bad),
+                                  tdc_buf_load(ars, (base + 12u * act_pix) | bad)};
+            }
         }
-        tdc_f4 av[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            av[mb] = (mb < mvalid) ? tdc_load_a4(a.wp, mg * MB + mb, a.KG, kg, lane) : (tdc_f4){0.f, 0.f, 0.f, 0.f};
-        tdc_mma_group<MB, PB>(acc, av, bv, mvalid);
+        ++kg;
     }
+};
+
+template <int MODE, int MB, int PB, int U>
+__global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
+{
+    extern __shared__ float red[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int g = lane >> 4, l16 = lane & 15;
+    const int pg = blockIdx.x % a.n_pgroups, mg = blockIdx.x / a.n_pgroups, b = blockIdx.y;
+
+    GemmNext<MODE, MB, PB> next;
+    next.wstride = (unsigned)a.KG * 1024u;
+    next.wrs = tdc_make_rsrc(a.wp + (size_t)mg * MB * a.KG * 256, MB * next.wstride);
+    next.ars = tdc_make_rsrc(a.act + (size_t)b * a.act_rows * a.act_pix, (unsigned)a.act_rows_valid * a.act_pix * 4u);
+    next.wlane = lane * 16u;
+    next.act_pix = a.act_pix;
+    next.NBk = a.NBk; next.K = a.K; next.H = a.H; next.W = a.W; next.g = g;
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+        const int p = 16 * (pg * PB + pb) + l16;
+        next.pval[pb] = p < a.out_pix;
+        if (MODE == 2) {
+            const int i = p / a.Wo, j = p - i * a.Wo;
+            next.ih0[pb] = i * a.stride - a.pad;
+            next.iw0[pb] = j * a.stride - a.pad;
+            next.poff[pb] = next.ih0[pb] * a.W + next.iw0[pb];
+        } else {
+            next.ih0[pb] = next.iw0[pb] = 0;
+            next.poff[pb] = p;
+        }
+    }
+    const int kg0 = (int)(((long)a.KG * wave) / nw);
+    next.kg = kg0;
+    next.kg_end = (int)(((long)a.KG * (wave + 1)) / nw);
+    {
+        const int tap = kg0 / a.NBk;
+        next.dg = kg0 - tap * a.NBk;
+        next.r = tap / a.K;
+        next.s = tap - next.r * a.K;
+    }
+
+    tdc_f4 acc[MB][PB];
+    tdc_zero<MB, PB>(acc);
+    TdcPipe<MB, PB, U> pipe;
+    pipe.start(next);
+    pipe.run(acc, next.kg_end - kg0, next);
 
     float *__restrict__ outb = a.out + (size_t)b * a.out_rows * a.out_pix;
     if (nw == 1) {
@@ -109,7 +148,7 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
                 for (int i = 0; i < 4; ++i) {
                     const int m = 16 * (mg * MB + mb) + 4 * g + i;
                     const int p = 16 * (pg * PB + pb) + l16;
-                    if (mb < mvalid && m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = acc[mb][pb][i];
+                    if (m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = acc[mb][pb][i];
                 }
         return;
     }
@@ -124,28 +163,52 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         float sum = red[e];
-        for (int w = 1; w < nw; ++w) sum += red[w * E + e];
+        for (int ww = 1; ww < nw; ++ww) sum += red[ww * E + e];
         const int ln = e & 63, i = (e >> 6) & 3, blk = e >> 8;
         const int pb = blk % PB, mb = blk / PB;
         const int m = 16 * (mg * MB + mb) + 4 * (ln >> 4) + i;
         const int p = 16 * (pg * PB + pb) + (ln & 15);
-        if (mb < mvalid && m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = sum;
+        if (m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = sum;
     }
+}
+
+// k-groups fetched per register buffer: 2*U covers up to eight k-groups per wavefront, beyond
+// that the choice among the compiled sizes minimises dead MFMA slots in the last buffer.
+int pick_u(int kg_per_wave, int umax)
+{
+    if (kg_per_wave <= 2 * umax) return std::min(umax, std::max(1, (kg_per_wave + 1) / 2));
+    int best = umax, waste = 1 << 30;
+    for (int u = umax; u >= std::max(1, umax - 1); --u) {
+        const int w = (kg_per_wave + u - 1) / u * u - kg_per_wave;
+        if (w < waste) {
+            waste = w;
+            best = u;
+        }
+    }
+    return best;
 }
 
 template <int MODE>
 hipError_t launch_stage(const GemmArgs &a, int mb, int pb, int waves, int batch, hipStream_t s)
 {
-    const int n_mgroups = (a.NBm + mb - 1) / mb;
+    const int n_mgroups = a.NBm / mb;
     dim3 grid((unsigned)(n_mgroups * a.n_pgroups), (unsigned)batch), block(64 * waves);
     const size_t lds = waves > 1 ? (size_t)waves * mb * pb * 256 * sizeof(float) : 0;
-#define TDC_CASE(M_, P_)                                                                          \
-    if (mb == M_ && pb == P_) {                                                                   \
-        hipLaunchKernelGGL((tdc_gemm_kernel<MODE, M_, P_>), grid, block, lds, s, a);              \
+    const int kg_per_wave = (a.KG + waves - 1) / waves;
+    const int umax = mb * pb <= 2 ? 4 : (mb * pb == 4 ? 4 : 2);
+    int u = pick_u(kg_per_wave, umax);
+    if (mb * pb == 4 && u != 4) u = 2;          // compiled sizes: {2,4} for four blocks, {2} beyond
+    if (mb * pb > 4) u = 2;
+#define TDC_CASE(M_, P_, U_)                                                                      \
+    if (mb == M_ && pb == P_ && u == U_) {                                                        \
+        hipLaunchKernelGGL((tdc_gemm_kernel<MODE, M_, P_, U_>), grid, block, lds, s, a);          \
         return hipGetLastError();                                                                 \
     }
-    TDC_CASE(1, 1) TDC_CASE(2, 1) TDC_CASE(1, 2) TDC_CASE(2, 2) TDC_CASE(4, 1)
-    TDC_CASE(1, 4) TDC_CASE(4, 2) TDC_CASE(2, 4) TDC_CASE(4, 4)
+    TDC_CASE(1, 1, 1) TDC_CASE(1, 1, 2) TDC_CASE(1, 1, 3) TDC_CASE(1, 1, 4)
+    TDC_CASE(2, 1, 1) TDC_CASE(2, 1, 2) TDC_CASE(2, 1, 3) TDC_CASE(2, 1, 4)
+    TDC_CASE(1, 2, 1) TDC_CASE(1, 2, 2) TDC_CASE(1, 2, 3) TDC_CASE(1, 2, 4)
+    TDC_CASE(2, 2, 2) TDC_CASE(2, 2, 4) TDC_CASE(4, 1, 2) TDC_CASE(4, 1, 4) TDC_CASE(1, 4, 2) TDC_CASE(1, 4, 4)
+    TDC_CASE(4, 2, 2) TDC_CASE(2, 4, 2) TDC_CASE(4, 4, 2)
 #undef TDC_CASE
     return hipErrorInvalidValue;
 }

@@ -4,11 +4,11 @@
 // Wt[k][m] (k = contraction index, m = output channel) is padded with zeros to
 // multiples of 16 in both directions and stored as
 //     Wp[mb][kg][lane][j],   mb = m/16, kg = k/16, lane = 0..63, j = 0..3
-//     Wp[mb][kg][lane][j] = Wt[16*kg + 4*j + lane/16][16*mb + lane%16]
+//     Wp[mb][kg][lane][j] = Wt[16*kg + 4*(lane/16) + j][16*mb + lane%16]
 // so that one 16-byte load per lane yields the A operands of four consecutive
 // v_mfma_f32_16x16x4_f32 steps (A[m = lane%16][k = lane/16]) and a wavefront's load is
 // one contiguous 1 KiB run.  The matching B operand of step j is
-// B[k = 16*kg + 4*j + lane/16][p = lane%16].
+// B[k = 16*kg + 4*(lane/16) + j][p = lane%16]  (see tdc_mfma.h for why this order).
 //   stage 1 (Eq. 2): k = c,                      m = d1   -> Uin_p  [NB1][KG1]
 //   stage 2 (Eq. 3): k = (r*K + s)*R1P + d1,     m = d2   -> core_p [NB2][K*K*NB1]
 //   stage 3 (Eq. 4): k = d2,                     m = n    -> Uout_p [NB3][NB2]
@@ -53,10 +53,11 @@ struct TdcFusedGeom {
     int QB, PBk;         // 16-pixel blocks of the input tile / output tile
     int tiles_x, tiles_y;
     int pitch1, pitch2;  // LDS row pitches (floats) of the z1 and z2 tiles
+    bool weights_in_lds; // core and U_out are copied into LDS by every workgroup
     size_t lds_bytes;
 };
 bool tdc_fused_unit_supported(int mb1, int mb2, int mb3, int pb);
-TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w);
+TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit);
 hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
                             const float *uout_p, float *y);

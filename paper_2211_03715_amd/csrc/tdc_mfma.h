@@ -6,6 +6,13 @@
 //   D : lane l holds D[m = 4*(l/16) + i][p = l%16] in register i = 0..3
 // Here m is an output channel, p a pixel and k the contraction index, so pixels run
 // along the lanes: activation loads and stores are contiguous in NCHW.
+//
+// A "k-group" is 16 consecutive contraction indices = four MFMA steps j = 0..3.  Within a
+// k-group, step j of lane group g = l/16 consumes contraction index 4*g + j.  With this
+// order the four accumulator registers a lane holds after one stage (channels 4*g + i of a
+// 16-channel block, i = 0..3) are exactly the four B operands the same lane position needs
+// for that block in the next stage, so an intermediate tile moves through LDS as one
+// 16-byte write and one 16-byte read per lane and k-group.
 #ifndef TDC_MFMA_H
 #define TDC_MFMA_H
 
@@ -18,27 +25,91 @@ __device__ __forceinline__ tdc_f4 tdc_mfma(float a, float b, tdc_f4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// Four A operands (k-steps 4*kg .. 4*kg+3 of 16-channel block mb) from a packed weight array.
-__device__ __forceinline__ tdc_f4 tdc_load_a4(const float *__restrict__ wp, int mb, int kgroups, int kg, int lane)
+__device__ __forceinline__ tdc_f4 tdc_f4_zero() { return (tdc_f4){0.f, 0.f, 0.f, 0.f}; }
+
+// Global operands are fetched with buffer loads: the hardware range check returns 0 for an
+// offset at or beyond the descriptor's size, so a lane that must read "nothing" (a pixel outside
+// the image or the tile, a channel past C, a k-group past the end of the range) just gets the
+// bit TDC_OOB set in its byte offset.  No branch and, unlike a select on the loaded value,
+// no wait for the load at the point of issue: loads can stay in flight across the MFMAs of the
+// other register buffer.  Descriptors cover less than 2 GiB.
+typedef __amdgpu_buffer_rsrc_t tdc_rsrc;
+constexpr unsigned TDC_OOB = 0x80000000u;
+
+__device__ __forceinline__ tdc_rsrc tdc_make_rsrc(const void *base, unsigned bytes)
 {
-    const tdc_f4 *p = reinterpret_cast<const tdc_f4 *>(wp);
-    return p[((size_t)mb * kgroups + kg) * 64 + lane];
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ float tdc_buf_load(tdc_rsrc r, unsigned byte_off)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
+}
+
+__device__ __forceinline__ tdc_f4 tdc_buf_load4(tdc_rsrc r, unsigned byte_off)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(tdc_f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
 }
 
 // acc[MB][PB] += A(mb, 4 steps) * B(pb, 4 steps); the step loop is outermost so that
 // consecutive MFMAs write different accumulators.
 template <int MB, int PB>
-__device__ __forceinline__ void tdc_mma_group(tdc_f4 (&acc)[MB][PB], const tdc_f4 (&a)[MB], const float (&b)[PB][4],
-                                              int mvalid)
+__device__ __forceinline__ void tdc_mma_group(tdc_f4 (&acc)[MB][PB], const tdc_f4 (&a)[MB], const tdc_f4 (&b)[PB])
 {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-            if (mb < mvalid) {
 #pragma unroll
-                for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = tdc_mfma(a[mb][j], b[pb][j], acc[mb][pb]);
+            for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = tdc_mfma(a[mb][j], b[pb][j], acc[mb][pb]);
+}
+
+// Software pipeline over the k-groups of one register tile.  `next(a, b)` fetches the operands
+// of the following k-group each time it is called; it is called more often than there are
+// k-groups and must then return A = 0 without touching memory out of bounds (by steering the
+// address, never by post-processing the loaded value), which keeps the loop body free of
+// branches and of waits.  Operands travel in two
+// register buffers of U k-groups; the loads of one buffer are issued before the MFMAs of the
+// other, so a tile with at most 2*U k-groups waits for memory once.  start() may be called
+// well ahead of run() to overlap the first fetch with other work.
+template <int MB, int PB, int U>
+struct TdcPipe {
+    tdc_f4 a0[U][MB], a1[U][MB];
+    tdc_f4 b0[U][PB], b1[U][PB];
+
+    template <class Next>
+    __device__ __forceinline__ void start(Next &next)
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) next(a0[u], b0[u]);
+    }
+
+    template <class Next>
+    __device__ __forceinline__ void run(tdc_f4 (&acc)[MB][PB], int nkg, Next &next)
+    {
+        for (int kg = 0; kg < nkg; kg += 2 * U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) next(a1[u], b1[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) tdc_mma_group<MB, PB>(acc, a0[u], b0[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) next(a0[u], b0[u]);
+            if (kg + U < nkg) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) tdc_mma_group<MB, PB>(acc, a1[u], b1[u]);
             }
+        }
+    }
+};
+
+template <int MB, int PB>
+__device__ __forceinline__ void tdc_zero(tdc_f4 (&acc)[MB][PB])
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = tdc_f4_zero();
 }
 
 #endif

@@ -9,7 +9,7 @@ size_t tdc_packed_floats_uout(const TdcDims &d) { return (size_t)d.NB3 * d.NB2 *
 
 namespace {
 
-// e = ((mb*KG + kg)*64 + lane)*4 + j  ->  k = 16*kg + 4*j + lane/16, m = 16*mb + lane%16
+// e = ((mb*KG + kg)*64 + lane)*4 + j  ->  k = 16*kg + 4*(lane/16) + j, m = 16*mb + lane%16
 __device__ __forceinline__ void unpack_index(size_t e, int kgroups, int &mb, int &kg, int &k16, int &m)
 {
     const int j = (int)(e & 3);
@@ -17,7 +17,7 @@ __device__ __forceinline__ void unpack_index(size_t e, int kgroups, int &mb, int
     const size_t blk = e >> 8;
     kg = (int)(blk % kgroups);
     mb = (int)(blk / kgroups);
-    k16 = 4 * j + (lane >> 4);
+    k16 = 4 * (lane >> 4) + j;
     m = 16 * mb + (lane & 15);
 }
 

@@ -52,7 +52,7 @@ const int kFusedMenu[][4] = {{1, 1, 1, 1}, {1, 1, 2, 1}, {2, 2, 2, 1}, {2, 2, 4,
 double fused_cycles(const Machine &m, const TdcDims &d, const TdcDeviceInfo &dev, int th, int tw, int nw,
                     const int *menu, size_t *lds_out)
 {
-    TdcFusedGeom g = tdc_fused_geometry(d, th, tw);
+    TdcFusedGeom g = tdc_fused_geometry(d, th, tw, dev.lds_per_wg);
     *lds_out = g.lds_bytes;
     if ((long)g.lds_bytes > dev.lds_per_wg) return 1e300;
     const int KG2 = d.K * d.K * d.NB1;
@@ -90,6 +90,7 @@ FusedChoice best_fused(const Machine &m, const TdcDims &d, const TdcDeviceInfo &
                     if (forced.mb[1] && menu[1] != forced.mb[1]) continue;
                     if (forced.mb[2] && menu[2] != forced.mb[2]) continue;
                     if (forced.pb[0] && menu[3] != forced.pb[0]) continue;
+                    if (d.NB1 % menu[0] || d.NB2 % menu[1] || d.NB3 % menu[2]) continue;   // whole register tiles only
                     size_t lds;
                     double c = fused_cycles(m, d, dev, th, tw, nw, menu, &lds);
                     if (c < best.cycles) {
@@ -119,6 +120,7 @@ StageChoice best_stage(const Machine &m, const TdcDeviceInfo &dev, int batch, in
                 if (fmb && mb != fmb) continue;
                 if (fpb && pb != fpb) continue;
                 if (fnw && nw != fnw) continue;
+                if (n_mblocks % mb) continue;         // whole register tiles only
                 if (!fnw && nw > kgroups) continue;   // idle wavefronts are legal, just never chosen
                 if ((size_t)nw * mb * pb * 1024 > 64 * 1024 && nw > 1) continue;
                 const long wgs = (long)cdiv(n_mblocks, mb) * cdiv(n_pblocks, pb) * batch;

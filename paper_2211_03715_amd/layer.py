@@ -4,6 +4,7 @@ Marshalling only; the arithmetic is in libtdc.so.
 """
 from __future__ import annotations
 
+import ctypes
 from typing import Optional
 
 from . import binding as B
@@ -44,6 +45,24 @@ class TuckerConv2d:
                             dtype=torch.float32)
         B.tdc_conv_tucker2(self.plan, x, U_in, core, U_out, y, self.shape, stream)
         return y
+
+    def bind(self, x, y, weights=None, stream=None):
+        """Marshal the arguments of tdc_conv_tucker2 once and return a zero-argument launcher.
+
+        For callers that enqueue the same buffers repeatedly: the per-call cost is one foreign
+        call.  The tensors and the stream must outlive the launcher."""
+        U_in, core, U_out = weights if weights is not None else self._weights
+        fn = B.load().tdc_conv_tucker2
+        vp = ctypes.c_void_p
+        args = (self.plan, vp(B._stream(stream)), vp(x.data_ptr()), vp(U_in.data_ptr()), vp(core.data_ptr()),
+                vp(U_out.data_ptr()), vp(y.data_ptr()), ctypes.byref(self.shape))
+
+        def launch():
+            rc = fn(*args)
+            if rc:
+                raise B.TdcError(rc, "tdc_conv_tucker2")
+
+        return launch
 
     def close(self) -> None:
         if self.plan is not None:

@@ -103,8 +103,10 @@ def test_selector_respects_forced_fields_and_rejects_misfits():
     s = B.make_shape(**L.asdict())
     t = B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_FUSED, tile_h=8, tile_w=8, waves=(4, 0, 0)))
     assert (t.variant, t.tile_h, t.tile_w, t.waves[0]) == (B.VARIANT_FUSED, 8, 8, 4)
-    t = B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_SPLIT, mb=(2, 1, 4), pb=(2, 2, 1)))
-    assert t.variant == B.VARIANT_SPLIT and list(t.mb) == [2, 1, 4] and list(t.pb) == [2, 2, 1]
+    t = B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_SPLIT, mb=(1, 1, 4), pb=(2, 2, 1)))
+    assert t.variant == B.VARIANT_SPLIT and list(t.mb) == [1, 1, 4] and list(t.pb) == [2, 2, 1]
+    with pytest.raises(B.TdcError):   # register tiles must divide the 16-channel blocks (R1 = 16 is one block)
+        B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_SPLIT, mb=(2, 1, 4)))
     with pytest.raises(B.TdcError) as e:
         B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_SPLIT, mb=(3, 1, 1)))
     assert e.value.status == B.TDC_ERR_BAD_TUNING

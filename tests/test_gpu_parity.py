@@ -64,8 +64,8 @@ FORCED = [
     ("split_w3_44", dict(variant=B.VARIANT_SPLIT, waves=(3, 4, 2), mb=(4, 4, 4), pb=(4, 4, 4))),
     ("split_w2_24", dict(variant=B.VARIANT_SPLIT, waves=(2, 4, 1), mb=(2, 4, 2), pb=(1, 1, 2))),
 ]
-FORCED_LAYERS = [Layer(2, 20, 24, 19, 23, 17, 33), Layer(1, 64, 64, 56, 56, 16, 16),
-                 Layer(2, 33, 18, 12, 40, 8, 40, 3, 2, 1), Layer(1, 256, 256, 14, 14, 64, 64)]
+FORCED_LAYERS = [Layer(2, 20, 60, 19, 23, 52, 64), Layer(1, 64, 64, 56, 56, 16, 16),
+                 Layer(2, 33, 128, 12, 40, 32, 57, 3, 2, 1), Layer(1, 256, 256, 14, 14, 64, 64)]
 
 
 @pytest.mark.parametrize("name,tuning", FORCED, ids=[f[0] for f in FORCED])
@@ -74,6 +74,13 @@ def test_forced_tunings(orc, name, tuning, layer):
     """Every register-tile shape, wave count and tile geometry the selector may pick."""
     _announce("forced", name, layer.name())
     inputs = make_inputs(layer, 77)
+    blocks = [(layer.R1 + 15) // 16, (layer.R2 + 15) // 16, (layer.N + 15) // 16]
+    if any(nb % mb for nb, mb in zip(blocks, tuning["mb"])):
+        # register tiles must divide the channel blocks: the library refuses, nothing runs
+        with pytest.raises(B.TdcError) as err:
+            run_gpu(layer, inputs, B.make_tuning(**tuning))
+        assert err.value.status == B.TDC_ERR_BAD_TUNING
+        return
     want = _oracle(orc, layer, inputs)
     try:
         got, desc = run_gpu(layer, inputs, B.make_tuning(**tuning))
