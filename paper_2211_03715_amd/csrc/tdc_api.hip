@@ -15,6 +15,7 @@ struct tdc_plan {
     float *uin_p, *core_p, *uout_p;    // re-laid-out weights (SPLIT, FUSED)
     const float *packed_from[3];       // caller pointers the stored copy was made from, or NULLs
     size_t ws_bytes;
+    double model_us;                   // the selector's latency estimate for this tuning
     char desc[320];
 };
 
@@ -108,12 +109,12 @@ void describe(tdc_plan &p)
     const char *names[] = {"auto", "naive", "split", "fused"};
     if (t.variant == TDC_VARIANT_FUSED)
         snprintf(p.desc, sizeof(p.desc),
-                 "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB%s",
+                 "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB%s model=%.1fus",
                  t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.mb[1], t.mb[2], t.pb[0],
-                 p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes, p.geom.weights_in_lds ? " wlds" : "");
+                 p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes, p.geom.weights_in_lds ? " wlds" : "", p.model_us);
     else if (t.variant == TDC_VARIANT_SPLIT)
-        snprintf(p.desc, sizeof(p.desc), "split stage(mb,pb,waves)= s1(%d,%d,%d) s2(%d,%d,%d) s3(%d,%d,%d)",
-                 t.mb[0], t.pb[0], t.waves[0], t.mb[1], t.pb[1], t.waves[1], t.mb[2], t.pb[2], t.waves[2]);
+        snprintf(p.desc, sizeof(p.desc), "split stage(mb,pb,waves)= s1(%d,%d,%d) s2(%d,%d,%d) s3(%d,%d,%d) model=%.1fus",
+                 t.mb[0], t.pb[0], t.waves[0], t.mb[1], t.pb[1], t.waves[1], t.mb[2], t.pb[2], t.waves[2], p.model_us);
     else
         snprintf(p.desc, sizeof(p.desc), "%s", names[t.variant & 3]);
 }
@@ -174,7 +175,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
         delete p;
         return TDC_ERR_BAD_TUNING;
     }
-    rc = tdc_select(p->dims, dev, &p->tuning);
+    rc = tdc_select(p->dims, dev, &p->tuning, &p->model_us);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)
         p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK) rc = check_tuning(*p, dev);
@@ -222,7 +223,7 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     memset(&tmp, 0, sizeof(tmp));
     tmp.dims = make_dims(*shape);
     tmp.tuning = *inout;
-    rc = tdc_select(tmp.dims, dev, &tmp.tuning);
+    rc = tdc_select(tmp.dims, dev, &tmp.tuning, nullptr);
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED)
         tmp.geom = tdc_fused_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK) rc = check_tuning(tmp, dev);

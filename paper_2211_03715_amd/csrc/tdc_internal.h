@@ -67,6 +67,7 @@ struct TdcDeviceInfo {
     int cus;             // compute units
     int lds_per_wg;      // bytes of LDS one workgroup may use
 };
-int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t);
+// `model_us`, when not null, receives the latency estimate of the chosen tuning (0 for NAIVE)
+int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double *model_us);
 
 #endif
