@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default: the ResNet-18-shaped sweep)")
     ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (the known-size kernel that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -170,6 +173,13 @@ def main():
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
+    if args.copy_mib > 0:
+        src = torch.empty(args.copy_mib * 262144, device=dev, dtype=torch.float32).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_mib"] = args.copy_mib
     for conv in convs:
         conv.close()
     print(json.dumps(out))

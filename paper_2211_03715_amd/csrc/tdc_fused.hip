@@ -29,32 +29,6 @@
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
 
-// Phase timestamps for kernel bring-up: compiled in only with -DTDC_PHASE_TIMING (never in the
-// shipped library).  Slot s of wavefront w of workgroup b lands in tdc_probe_buf[((b*8+w)*16+s)*2 + {0,1}]
-// as (shader clock, 100 MHz wall clock).
-#ifdef TDC_PHASE_TIMING
-__device__ unsigned long long tdc_probe_buf[2 * 8 * 16 * 4096];
-#define TDC_PROBE(slot)                                                                             \
-    do {                                                                                            \
-        if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096 && blockIdx.y == 0) {                      \
-            const size_t o = (((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (slot)) * 2;      \
-            tdc_probe_buf[o] = clock64();                                                           \
-            tdc_probe_buf[o + 1] = wall_clock64();                                                  \
-        }                                                                                           \
-    } while (0)
-extern "C" int tdc_debug_read_probes(unsigned long long *host, size_t count)
-{
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(tdc_probe_buf), count * sizeof(unsigned long long)) == hipSuccess ? 0 : -1;
-}
-// the whole body runs twice in the timing build; the probes keep the second pass (warm instruction cache)
-#define TDC_REPEAT_BEGIN for (int tdc_rep = 0; tdc_rep < 2; ++tdc_rep) {
-#define TDC_REPEAT_END __syncthreads(); }
-#else
-#define TDC_PROBE(slot) do { } while (0)
-#define TDC_REPEAT_BEGIN
-#define TDC_REPEAT_END
-#endif
-
 namespace {
 
 struct FusedArgs {
@@ -90,7 +64,6 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;  // first input pixel (may be < 0)
     const int HW = a.H * a.W;
 
-    TDC_REPEAT_BEGIN
     TDC_PROBE(0);
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
@@ -285,7 +258,6 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
         }
     }
     TDC_PROBE(7);
-    TDC_REPEAT_END
 }
 
 #define TDC_FUSED_MENU(X) X(1, 1, 1, 1) X(1, 1, 2, 1) X(2, 2, 2, 1) X(2, 2, 4, 1) X(4, 4, 4, 1) \

@@ -135,8 +135,11 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     tdc_f4 acc[MB][PB];
     tdc_zero<MB, PB>(acc);
     TdcPipe<MB, PB, U> pipe;
+    TDC_PROBE((MODE - 1) * 5 + 0);
     pipe.start(next);
+    TDC_PROBE((MODE - 1) * 5 + 1);
     pipe.run(acc, next.kg_end - kg0, next);
+    TDC_PROBE((MODE - 1) * 5 + 2);
 
     float *__restrict__ outb = a.out + (size_t)b * a.out_rows * a.out_pix;
     if (nw == 1) {
@@ -161,6 +164,7 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
 #pragma unroll
             for (int i = 0; i < 4; ++i) red[wave * E + ((mb * PB + pb) * 4 + i) * 64 + lane] = acc[mb][pb][i];
     __syncthreads();
+    TDC_PROBE((MODE - 1) * 5 + 3);
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         float sum = red[e];
         for (int ww = 1; ww < nw; ++ww) sum += red[ww * E + e];
@@ -170,6 +174,7 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
         const int p = 16 * (pg * PB + pb) + (ln & 15);
         if (m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = sum;
     }
+    TDC_PROBE((MODE - 1) * 5 + 4);
 }
 
 // k-groups fetched per register buffer: 2*U covers up to eight k-groups per wavefront, beyond

@@ -128,6 +128,28 @@ struct TdcPipe {
     }
 };
 
+// Phase timestamps for kernel bring-up: compiled in only with -DTDC_PHASE_TIMING, in a build that
+// includes every source into one translation unit (never in the shipped library).  Slot s of
+// wavefront w of workgroup b lands in tdc_probe_buf[((b*8+w)*16+s)*2 + {0,1}] as
+// (shader clock, 100 MHz wall clock).
+#ifdef TDC_PHASE_TIMING
+__device__ unsigned long long tdc_probe_buf[2 * 8 * 16 * 4096];
+#define TDC_PROBE(slot)                                                                             \
+    do {                                                                                            \
+        if ((threadIdx.x & 63) == 0 && blockIdx.x < 4096 && blockIdx.y == 0) {                      \
+            const size_t o = (((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (slot)) * 2;     \
+            tdc_probe_buf[o] = clock64();                                                           \
+            tdc_probe_buf[o + 1] = wall_clock64();                                                  \
+        }                                                                                           \
+    } while (0)
+extern "C" int tdc_debug_read_probes(unsigned long long *host, size_t count)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(tdc_probe_buf), count * sizeof(unsigned long long)) == hipSuccess ? 0 : -1;
+}
+#else
+#define TDC_PROBE(slot) do { } while (0)
+#endif
+
 template <int MB, int PB>
 __device__ __forceinline__ void tdc_zero(tdc_f4 (&acc)[MB][PB])
 {
