@@ -71,13 +71,16 @@ enum {
     TDC_VARIANT_AUTO = 0,   /* let the selector decide                                          */
     TDC_VARIANT_NAIVE = 1,  /* three plain fp32 kernels, one thread per output pixel            */
     TDC_VARIANT_SPLIT = 2,  /* three fp32-MFMA GEMM kernels, intermediates z1/z2 in workspace   */
-    TDC_VARIANT_FUSED = 3   /* one fp32-MFMA kernel per spatial tile, z1/z2 kept in LDS         */
+    TDC_VARIANT_FUSED = 3,  /* one fp32-MFMA kernel per spatial tile, z1/z2 kept in LDS         */
+    TDC_VARIANT_CHAIN = 4   /* fused; each wavefront keeps its z2 columns in registers and feeds
+                               them straight into stage 3 (throughput regime)                   */
 };
 
 /* Launch parameters.  Zero in any field means "selector's choice".
- *   tile_h, tile_w : output tile of one workgroup            (FUSED)
- *   waves          : wavefronts (of 64 lanes) per workgroup  (SPLIT: per stage, FUSED: waves[0])
- *   mb, pb         : 16-channel and 16-pixel blocks per wavefront register tile, per stage */
+ *   tile_h, tile_w : output tile of one workgroup            (FUSED, CHAIN)
+ *   waves          : wavefronts (of 64 lanes) per workgroup  (SPLIT: per stage; FUSED, CHAIN: waves[0])
+ *   mb, pb         : 16-channel and 16-pixel blocks per wavefront register tile, per stage
+ *                    (CHAIN uses mb[0] and pb[0]; its stage-2 tile is all of R2 by construction) */
 typedef struct tdc_tuning {
     int32_t variant;
     int32_t tile_h, tile_w;

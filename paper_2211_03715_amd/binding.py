@@ -22,8 +22,8 @@ TDC_ERR_ALLOC = -5
 TDC_ERR_HIP = -6
 TDC_ERR_BAD_TUNING = -7
 
-VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
-VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused"}
+VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN = 0, 1, 2, 3, 4
+VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain"}
 
 # every symbol include/tdc.h declares
 EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", "tdc_conv_tucker2",

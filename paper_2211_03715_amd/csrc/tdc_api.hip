@@ -100,6 +100,12 @@ int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
         if ((long)p.geom.lds_bytes > dev.lds_per_wg) return TDC_ERR_BAD_TUNING;
         return TDC_OK;
     }
+    if (t.variant == TDC_VARIANT_CHAIN) {
+        if (t.tile_h < 1 || t.tile_w < 1 || t.tile_h * t.tile_w > 4096) return TDC_ERR_BAD_TUNING;
+        if (!tdc_chain_supported(p.dims.NB2, t.mb[0], t.pb[0])) return TDC_ERR_BAD_TUNING;
+        if ((long)p.geom.lds_bytes > dev.lds_per_wg) return TDC_ERR_BAD_TUNING;
+        return TDC_OK;
+    }
     return TDC_ERR_BAD_TUNING;
 }
 
@@ -107,7 +113,12 @@ void describe(tdc_plan &p)
 {
     const tdc_tuning &t = p.tuning;
     const char *names[] = {"auto", "naive", "split", "fused"};
-    if (t.variant == TDC_VARIANT_FUSED)
+    if (t.variant == TDC_VARIANT_CHAIN)
+        snprintf(p.desc, sizeof(p.desc),
+                 "chain tile=%dx%d in=%dx%d waves=%d units(mb1,pb)=(%d,%d) grid=%dx%d lds=%zuB%s model=%.1fus",
+                 t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.pb[0],
+                 p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes, p.geom.weights_in_lds ? " wlds" : "", p.model_us);
+    else if (t.variant == TDC_VARIANT_FUSED)
         snprintf(p.desc, sizeof(p.desc),
                  "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB%s model=%.1fus",
                  t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.mb[1], t.mb[2], t.pb[0],
@@ -171,13 +182,15 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     p->dims = make_dims(*shape);
     p->device = device;
     if (forced) p->tuning = *forced;
-    if (p->tuning.variant < TDC_VARIANT_AUTO || p->tuning.variant > TDC_VARIANT_FUSED) {
+    if (p->tuning.variant < TDC_VARIANT_AUTO || p->tuning.variant > TDC_VARIANT_CHAIN) {
         delete p;
         return TDC_ERR_BAD_TUNING;
     }
     rc = tdc_select(p->dims, dev, &p->tuning, &p->model_us);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)
         p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
+    if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_CHAIN)
+        p->geom = tdc_chain_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK) rc = check_tuning(*p, dev);
     if (rc != TDC_OK) {
         delete p;
@@ -188,7 +201,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     const size_t n_z1 = (size_t)d.B * 16 * d.NB1 * d.H * d.W, n_z2 = (size_t)d.B * 16 * d.NB2 * d.Ho * d.Wo;
     const size_t n_w1 = tdc_packed_floats_uin(d), n_w2 = tdc_packed_floats_core(d), n_w3 = tdc_packed_floats_uout(d);
     bool ok = true;
-    if (p->tuning.variant != TDC_VARIANT_FUSED) {
+    if (p->tuning.variant != TDC_VARIANT_FUSED && p->tuning.variant != TDC_VARIANT_CHAIN) {
         ok = ok && hipMalloc((void **)&p->z1, n_z1 * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->z2, n_z2 * sizeof(float)) == hipSuccess;
         p->ws_bytes += (n_z1 + n_z2) * sizeof(float);
@@ -215,7 +228,7 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
     if (compute_units < 1 || lds_bytes < 1024) return TDC_ERR_BAD_TUNING;
-    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_FUSED) return TDC_ERR_BAD_TUNING;
+    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_CHAIN) return TDC_ERR_BAD_TUNING;
     TdcDeviceInfo dev;
     dev.cus = compute_units;
     dev.lds_per_wg = lds_bytes;
@@ -226,6 +239,8 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     rc = tdc_select(tmp.dims, dev, &tmp.tuning, nullptr);
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED)
         tmp.geom = tdc_fused_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
+    if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_CHAIN)
+        tmp.geom = tdc_chain_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK) rc = check_tuning(tmp, dev);
     if (rc == TDC_OK) *inout = tmp.tuning;
     return rc;
@@ -286,6 +301,8 @@ int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float 
     }
     if (p->tuning.variant == TDC_VARIANT_SPLIT)
         e = tdc_launch_split(d, p->tuning, s, x, p->uin_p, p->core_p, p->uout_p, p->z1, p->z2, y);
+    else if (p->tuning.variant == TDC_VARIANT_CHAIN)
+        e = tdc_launch_chain(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, p->uout_p, y);
     else
         e = tdc_launch_fused(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, p->uout_p, y);
     return e == hipSuccess ? TDC_OK : TDC_ERR_HIP;
@@ -310,7 +327,7 @@ size_t tdc_plan_workspace_bytes(const tdc_plan *p) { return p ? p->ws_bytes : 0;
 int tdc_plan_kernel_count(const tdc_plan *p)
 {
     if (!p) return 0;
-    return p->tuning.variant == TDC_VARIANT_FUSED ? 1 : 3;
+    return (p->tuning.variant == TDC_VARIANT_FUSED || p->tuning.variant == TDC_VARIANT_CHAIN) ? 1 : 3;
 }
 
 int tdc_launch_null(void *hip_stream)

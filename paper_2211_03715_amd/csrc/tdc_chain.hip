@@ -1,0 +1,346 @@
+// CHAIN variant: the fused kernel for the throughput regime.  Like FUSED, one workgroup evaluates
+// all three stages (Eqs. 2, 3, 4) for one TH x TW output tile of one image with the z1 tile and
+// its halo in LDS.  Unlike FUSED, stages 2 and 3 are chained inside a wavefront:
+//
+//   - a wavefront owns whole groups of 16-pixel blocks of the output tile and computes ALL R2
+//     channels of z2 for them (NB2 = R2P/16 is a template parameter so that the NB2 x PB
+//     accumulator blocks live in registers; every z1 operand read from LDS is used NB2 times);
+//   - with the k-order of tdc_mfma.h those accumulator registers are, as they stand, the operand
+//     of stage 3, so z2 never goes through LDS and there is no barrier between stages 2 and 3;
+//   - stage 3 runs with the MFMA operands swapped, D = z2^T U_out, which leaves each lane with
+//     four consecutive PIXELS of one output channel: y is written with one 16-byte buffer store
+//     per lane instead of four 4-byte stores of four channels (scalar stores when the tile or
+//     image width is not a multiple of 4).
+//
+// The paper's kernel keeps one output channel per thread and the R x S weights of the current
+// input channel in registers (section 5.2); here the register-resident object is the whole
+// R2-channel column of z2 for 16 or 32 pixels, which is what lets the 1x1 expansion ride along.
+#include "tdc_internal.h"
+#include "tdc_mfma.h"
+
+namespace {
+
+struct ChainArgs {
+    const float *x, *uin_p, *core_p, *uout_p;
+    float *y;
+    int C, N, H, W, Ho, Wo, K, stride, pad;
+    int NB1, NB3, KG1;
+    int TH, TW, QW, Q, P, QB, PBk;
+    int tiles_x;
+    int pitch1;             // LDS row pitch of the z1 tile, in 16-byte cells
+    int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
+    int mb1;                // stage-1 register tile height (1, 2 or 4 channel blocks)
+    int vec;                // 1: tile width, image width and tile origin are multiples of 4 -> 16-byte stores
+};
+
+__device__ __forceinline__ void tdc_buf_store(tdc_rsrc r, unsigned byte_off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)byte_off, 0, 0);
+}
+
+__device__ __forceinline__ void tdc_buf_store4(tdc_rsrc r, unsigned byte_off, tdc_f4 v)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), r, (int)byte_off, 0, 0);
+}
+
+// Stage 1 (Eq. 2) for the whole workgroup: z1 tile = U_in^T x into LDS cells.  `prefetched`
+// says that `pipe` already holds the first buffer of unit `wave` (issued before the weight copy).
+template <int MB1, int PB>
+struct ChainStage1 {
+    const ChainArgs &a;
+    tdc_rsrc xrs, urs;
+    int lane, g, l16, h0, w0, HW, n_pg;
+    int pg, mg, kg;
+    unsigned xoff[PB];
+
+    __device__ __forceinline__ void setup(int u)
+    {
+        pg = u % n_pg;
+        mg = u / n_pg;
+        kg = 0;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            const int q = 16 * (pg * PB + pb) + l16;
+            const int qh = q / a.QW, qw = q - qh * a.QW;
+            const int h = h0 + qh, w = w0 + qw;
+            const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
+            xoff[pb] = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
+        }
+    }
+    __device__ __forceinline__ void operator()(tdc_f4 (&av)[MB1], tdc_f4 (&bv)[PB])
+    {
+        const unsigned dead = kg < a.KG1 ? 0u : TDC_OOB;
+#pragma unroll
+        for (int mb = 0; mb < MB1; ++mb)
+            av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
+        // channels past C lie beyond the descriptor and read as 0 by themselves
+        const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
+            bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
+                              tdc_buf_load(xrs, o + 12u * HW)};
+        }
+        ++kg;
+    }
+};
+
+template <int MB1, int PB>
+__device__ __forceinline__ void chain_stage1(const ChainArgs &a, tdc_f4 *__restrict__ z1s, int lane, int wave, int nw,
+                                             int b, int h0, int w0, const tdc_f4 *__restrict__ wsrc_core,
+                                             tdc_f4 *__restrict__ wC, tdc_f4 *__restrict__ wO, bool copy_weights)
+{
+    constexpr int U = 4;
+    const int HW = a.H * a.W;
+    ChainStage1<MB1, PB> next{a};
+    next.xrs = tdc_make_rsrc(a.x + (size_t)b * a.C * HW, (unsigned)a.C * HW * 4u);
+    next.urs = tdc_make_rsrc(a.uin_p, (unsigned)a.NB1 * a.KG1 * 1024u);
+    next.lane = lane; next.g = lane >> 4; next.l16 = lane & 15;
+    next.h0 = h0; next.w0 = w0; next.HW = HW;
+    next.n_pg = (a.QB + PB - 1) / PB;
+    const int n_units = next.n_pg * (a.NB1 / MB1);
+    TdcPipe<MB1, PB, U> pipe;
+    int u = wave;
+    if (u < n_units) {
+        next.setup(u);
+        pipe.start(next);          // in flight while the weights are copied
+    }
+    if (copy_weights) {
+        // core and U_out: global -> registers -> LDS, 8 x 16 bytes per thread and round
+        constexpr int CH = 8;
+        const tdc_f4 *__restrict__ src[2] = {wsrc_core, reinterpret_cast<const tdc_f4 *>(a.uout_p)};
+        tdc_f4 *dst[2] = {wC, wO};
+        const int cnt[2] = {a.w_core4, a.w_uout4};
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+            for (int base = threadIdx.x; base < cnt[t]; base += CH * blockDim.x) {
+                tdc_f4 tmp[CH];
+#pragma unroll
+                for (int c = 0; c < CH; ++c) tmp[c] = src[t][min(base + c * (int)blockDim.x, cnt[t] - 1)];
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const int i = base + c * blockDim.x;
+                    if (i < cnt[t]) dst[t][i] = tmp[c];
+                }
+            }
+    }
+    for (; u < n_units; u += nw) {
+        if (u != wave) {
+            next.setup(u);
+            pipe.start(next);
+        }
+        tdc_f4 acc[MB1][PB];
+        pipe.run(acc, a.KG1, next);
+#pragma unroll
+        for (int mb = 0; mb < MB1; ++mb)
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb)
+                if (next.pg * PB + pb < a.QB)
+                    z1s[((next.mg * MB1 + mb) * 4 + next.g) * a.pitch1 + 16 * (next.pg * PB + pb) + next.l16] = acc[mb][pb];
+    }
+}
+
+template <int NB2, int PB, bool WLDS>
+__global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
+{
+    extern __shared__ tdc_f4 lds4[];
+    tdc_f4 *__restrict__ z1s = lds4;                                  // [NB1][4][pitch1]
+    tdc_f4 *__restrict__ wC = z1s + (size_t)4 * a.NB1 * a.pitch1;     // packed core   (WLDS)
+    tdc_f4 *__restrict__ wO = wC + a.w_core4;                         // packed U_out  (WLDS)
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int g = lane >> 4, l16 = lane & 15;
+    const int ty = blockIdx.x / a.tiles_x, tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
+    const int i0 = ty * a.TH, j0 = tx * a.TW;                   // first output pixel of the tile
+    const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;  // first input pixel (may be < 0)
+
+    TDC_PROBE(0);
+    // ------------------------------------------------------------------ stage 1 (Eq. 2)
+    {
+        const tdc_f4 *core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
+        if (a.mb1 == 4) chain_stage1<4, PB>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
+        else if (a.mb1 == 2) chain_stage1<2, PB>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
+        else chain_stage1<1, PB>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
+    }
+    TDC_PROBE(3);
+    __syncthreads();
+    TDC_PROBE(4);
+
+    // ------------------------------------------------- stages 2 and 3 (Eqs. 3, 4), per wavefront
+    const int KG2 = a.K * a.K * a.NB1;
+    const int P2 = a.Ho * a.Wo;
+    const tdc_rsrc crs = tdc_make_rsrc(a.core_p, (unsigned)a.w_core4 * 16u);
+    const tdc_rsrc ors = tdc_make_rsrc(a.uout_p, (unsigned)a.w_uout4 * 16u);
+    const tdc_rsrc yrs = tdc_make_rsrc(a.y + (size_t)b * a.N * P2, (unsigned)a.N * P2 * 4u);
+    const int n_pg = (a.PBk + PB - 1) / PB;
+    for (int pg = wave; pg < n_pg; pg += nw) {
+        // ---- stage 2: acc2[kg2][pb] = z2 channels 16*kg2 + 4*g + {0..3} of pixel l16 of block pb
+        int qbase[PB];
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            const int p = 16 * (pg * PB + pb) + l16;
+            const int ph = p / a.TW, pw = p - ph * a.TW;
+            qbase[pb] = g * a.pitch1 + (p < a.P ? ph * a.stride * a.QW + pw * a.stride : 0);
+        }
+        tdc_f4 acc2[NB2][PB];
+        {
+            constexpr int U = 1;
+            int kg = 0, dg = 0, s = 0, toff = 0;     // toff = r*QW + s
+            auto next = [&](tdc_f4(&av)[NB2], tdc_f4(&bv)[PB]) {
+                const bool live = kg < KG2;
+#pragma unroll
+                for (int mb = 0; mb < NB2; ++mb) {
+                    const int frag = mb * KG2 + kg;
+                    // a dead fetch is never multiplied (one k-group per buffer); it only has to stay in range
+                    if (WLDS) av[mb] = wC[(live ? frag : 0) * 64 + lane];
+                    else av[mb] = tdc_buf_load4(crs, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
+                }
+                const int cell = live ? dg * 4 * a.pitch1 + toff : 0;
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb) bv[pb] = z1s[cell + qbase[pb]];
+                ++kg;
+                // position of the next k-group inside (tap, 16-channel group of z1), without branches
+                const int nd = dg + 1;
+                const bool w1 = nd == a.NB1;
+                dg = w1 ? 0 : nd;
+                const int ns = s + (w1 ? 1 : 0);
+                const bool w2 = ns == a.K;
+                s = w2 ? 0 : ns;
+                toff += (w1 ? 1 : 0) + (w2 ? a.QW - a.K : 0);
+            };
+            TdcPipe<NB2, PB, U> pipe;
+            pipe.start(next);
+            pipe.run(acc2, KG2, next);
+        }
+        // ---- stage 3: D[pixel 4*g + i][channel l16] = sum_d2 z2[d2][pixel] * U_out[d2][channel]
+        unsigned yq[PB][4];      // byte offset of pixel 4*g + i of block pb in one channel plane, or TDC_OOB
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int p = 16 * (pg * PB + pb) + 4 * g + i;
+                const int ph = p / a.TW, pw = p - ph * a.TW;
+                const int oi = i0 + ph, oj = j0 + pw;
+                yq[pb][i] = (p < a.P && oi < a.Ho && oj < a.Wo) ? (unsigned)(oi * a.Wo + oj) * 4u : TDC_OOB;
+            }
+        tdc_f4 ua[2][NB2];
+        const auto fetch = [&](int nb, tdc_f4(&u)[NB2]) {
+            const bool live = nb < a.NB3;
+#pragma unroll
+            for (int kg = 0; kg < NB2; ++kg) {
+                const int frag = nb * NB2 + kg;
+                if (WLDS) u[kg] = wO[(live ? frag : 0) * 64 + lane];
+                else u[kg] = tdc_buf_load4(ors, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
+            }
+        };
+        const auto emit = [&](int nb, const tdc_f4(&u)[NB2]) {
+            tdc_f4 acc3[PB];
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) acc3[pb] = tdc_f4_zero();
+#pragma unroll
+            for (int kg = 0; kg < NB2; ++kg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int pb = 0; pb < PB; ++pb) acc3[pb] = tdc_mfma(acc2[kg][pb][j], u[kg][j], acc3[pb]);
+            // channels past N lie beyond the descriptor: the hardware drops those stores
+            const unsigned plane = (unsigned)(16 * nb + l16) * P2 * 4u;
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) {
+                if (a.vec) {
+                    tdc_buf_store4(yrs, (plane + yq[pb][0]) | (yq[pb][0] & TDC_OOB), acc3[pb]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        tdc_buf_store(yrs, (plane + yq[pb][i]) | (yq[pb][i] & TDC_OOB), acc3[pb][i]);
+                }
+            }
+        };
+        fetch(0, ua[0]);
+        for (int nb = 0; nb < a.NB3; nb += 2) {
+            fetch(nb + 1, ua[1]);
+            emit(nb, ua[0]);
+            fetch(nb + 2, ua[0]);
+            if (nb + 1 < a.NB3) emit(nb + 1, ua[1]);
+        }
+    }
+    TDC_PROBE(7);
+}
+
+#define TDC_CHAIN_NB2(X) X(1) X(2) X(3) X(4) X(5) X(6) X(8) X(10)
+
+}  // namespace
+
+bool tdc_chain_supported(int nb2, int mb1, int pb)
+{
+    if (!(mb1 == 1 || mb1 == 2 || mb1 == 4) || !(pb == 1 || pb == 2)) return false;
+#define TDC_X(N_) if (nb2 == N_) return true;
+    TDC_CHAIN_NB2(TDC_X)
+#undef TDC_X
+    return false;
+}
+
+TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit)
+{
+    TdcFusedGeom g;
+    g.TH = tile_h;
+    g.TW = tile_w;
+    g.QH = (tile_h - 1) * d.stride + d.K;
+    g.QW = (tile_w - 1) * d.stride + d.K;
+    g.Q = g.QH * g.QW;
+    g.QB = (g.Q + 15) / 16;
+    g.PBk = (tile_h * tile_w + 15) / 16;
+    g.tiles_x = (d.Wo + tile_w - 1) / tile_w;
+    g.tiles_y = (d.Ho + tile_h - 1) / tile_h;
+    g.pitch1 = 16 * g.QB + 4;
+    g.pitch2 = 0;
+    const size_t tiles = (size_t)16 * d.NB1 * g.pitch1 * sizeof(float);
+    const size_t weights = (tdc_packed_floats_core(d) + tdc_packed_floats_uout(d)) * sizeof(float);
+    g.weights_in_lds = tiles + weights <= (size_t)lds_limit;
+    g.lds_bytes = tiles + (g.weights_in_lds ? weights : 0);
+    return g;
+}
+
+hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
+                            const float *x, const float *uin_p, const float *core_p,
+                            const float *uout_p, float *y)
+{
+    ChainArgs a;
+    a.x = x; a.uin_p = uin_p; a.core_p = core_p; a.uout_p = uout_p; a.y = y;
+    a.C = d.C; a.N = d.N; a.H = d.H; a.W = d.W; a.Ho = d.Ho; a.Wo = d.Wo;
+    a.K = d.K; a.stride = d.stride; a.pad = d.pad;
+    a.NB1 = d.NB1; a.NB3 = d.NB3; a.KG1 = d.KG1;
+    a.TH = g.TH; a.TW = g.TW; a.QW = g.QW; a.Q = g.Q; a.P = g.TH * g.TW; a.QB = g.QB; a.PBk = g.PBk;
+    a.tiles_x = g.tiles_x;
+    a.pitch1 = g.pitch1;
+    a.w_core4 = (int)(tdc_packed_floats_core(d) / 4);
+    a.w_uout4 = (int)(tdc_packed_floats_uout(d) / 4);
+    a.mb1 = t.mb[0];
+    a.vec = (g.TW % 4 == 0 && d.Wo % 4 == 0) ? 1 : 0;
+    dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
+#define TDC_LAUNCH(N_, P_, W_)                                                                         \
+    {                                                                                                  \
+        if (g.lds_bytes > 48 * 1024) {                                                                 \
+            hipError_t e = hipFuncSetAttribute((const void *)tdc_chain_kernel<N_, P_, W_>,             \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,             \
+                                               (int)g.lds_bytes);                                      \
+            if (e != hipSuccess) return e;                                                             \
+        }                                                                                              \
+        hipLaunchKernelGGL((tdc_chain_kernel<N_, P_, W_>), grid, block, g.lds_bytes, s, a);            \
+        return hipGetLastError();                                                                      \
+    }
+#define TDC_X(N_)                                                                                      \
+    if (d.NB2 == N_) {                                                                                 \
+        if (t.pb[0] == 1) {                                                                            \
+            if (g.weights_in_lds) TDC_LAUNCH(N_, 1, true) else TDC_LAUNCH(N_, 1, false)                \
+        } else {                                                                                       \
+            if (g.weights_in_lds) TDC_LAUNCH(N_, 2, true) else TDC_LAUNCH(N_, 2, false)                \
+        }                                                                                              \
+    }
+    TDC_CHAIN_NB2(TDC_X)
+#undef TDC_X
+#undef TDC_LAUNCH
+    return hipErrorInvalidValue;
+}

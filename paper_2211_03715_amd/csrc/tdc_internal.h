@@ -62,6 +62,13 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
                             const float *x, const float *uin_p, const float *core_p,
                             const float *uout_p, float *y);
 
+// ---- fused MFMA kernel with stages 2 and 3 chained in registers (tdc_chain.hip)
+bool tdc_chain_supported(int nb2, int mb1, int pb);
+TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit);
+hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
+                            const float *x, const float *uin_p, const float *core_p,
+                            const float *uout_p, float *y);
+
 // ---- selector (tdc_select.cpp): fills every zero field of `t`
 struct TdcDeviceInfo {
     int cus;             // compute units

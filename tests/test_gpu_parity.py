@@ -13,7 +13,8 @@ from parity_util import assert_parity, run_gpu
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = {"naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT, "fused": B.VARIANT_FUSED, "auto": B.VARIANT_AUTO}
+VARIANTS = {"naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT, "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN,
+            "auto": B.VARIANT_AUTO}
 
 
 def _announce(*parts):
@@ -59,6 +60,10 @@ FORCED = [
     ("fused_7x7_w2_pb2", dict(variant=B.VARIANT_FUSED, tile_h=7, tile_w=7, waves=(2, 2, 2), mb=(2, 2, 2), pb=(2, 2, 2))),
     ("fused_3x5_w1", dict(variant=B.VARIANT_FUSED, tile_h=3, tile_w=5, waves=(1, 1, 1), mb=(4, 4, 4), pb=(2, 2, 2))),
     ("fused_16x32_w4", dict(variant=B.VARIANT_FUSED, tile_h=16, tile_w=32, waves=(4, 4, 4), mb=(4, 4, 4), pb=(1, 1, 1))),
+    ("chain_8x8_w4", dict(variant=B.VARIANT_CHAIN, tile_h=8, tile_w=8, waves=(4, 4, 4), mb=(1, 1, 1), pb=(1, 1, 1))),
+    ("chain_4x28_w8_pb2", dict(variant=B.VARIANT_CHAIN, tile_h=4, tile_w=28, waves=(8, 8, 8), mb=(2, 1, 1), pb=(2, 2, 2))),
+    ("chain_3x5_w1", dict(variant=B.VARIANT_CHAIN, tile_h=3, tile_w=5, waves=(1, 1, 1), mb=(4, 1, 1), pb=(2, 2, 2))),
+    ("chain_7x7_w2", dict(variant=B.VARIANT_CHAIN, tile_h=7, tile_w=7, waves=(2, 2, 2), mb=(1, 1, 1), pb=(1, 1, 1))),
     ("split_111_w1", dict(variant=B.VARIANT_SPLIT, waves=(1, 1, 1), mb=(1, 1, 1), pb=(1, 1, 1))),
     ("split_w8", dict(variant=B.VARIANT_SPLIT, waves=(8, 8, 8), mb=(1, 2, 4), pb=(4, 2, 1))),
     ("split_w3_44", dict(variant=B.VARIANT_SPLIT, waves=(3, 4, 2), mb=(4, 4, 4), pb=(4, 4, 4))),
@@ -107,7 +112,7 @@ def test_full_size_workloads(orc, cfg):
     print("[config %d] worst E_inf=%.2e E_el=%.2e" % ((cfg,) + worst), flush=True)
 
 
-@pytest.mark.parametrize("variant", ["split", "fused"])
+@pytest.mark.parametrize("variant", ["split", "fused", "chain"])
 def test_dense_path_agrees_too(orc, variant):
     """The GPU result also matches the dense convolution with the kernel of Eq. 1."""
     layer = Layer(1, 24, 20, 14, 14, 12, 9)
@@ -118,7 +123,7 @@ def test_dense_path_agrees_too(orc, variant):
     assert_parity(got, want, desc)
 
 
-@pytest.mark.parametrize("variant", ["naive", "split", "fused"])
+@pytest.mark.parametrize("variant", ["naive", "split", "fused", "chain"])
 def test_unpacked_weights_path(orc, variant):
     """Without tdc_plan_pack_weights the library re-lays the weights out on every call."""
     layer = Layer(2, 20, 24, 19, 23, 17, 33)
@@ -135,7 +140,7 @@ def test_repacking_after_weight_change_and_determinism(orc):
     layer = Layer(1, 64, 64, 28, 28, 16, 32)
     _announce("repack+determinism", layer.name())
     dev = torch.device("cuda:0")
-    for variant in (B.VARIANT_SPLIT, B.VARIANT_FUSED):
+    for variant in (B.VARIANT_SPLIT, B.VARIANT_FUSED, B.VARIANT_CHAIN):
         a = make_inputs(layer, 11)
         b = make_inputs(layer, 12)
         ta = {k: torch.from_numpy(v).to(dev) for k, v in a.items()}
@@ -160,7 +165,7 @@ def test_linearity_and_batch_independence_on_gpu(orc):
     _announce("linearity/batch", layer.name())
     one = Layer(1, 32, 48, 14, 14, 16, 16)
     inputs = make_inputs(layer, 21)
-    for variant in (B.VARIANT_SPLIT, B.VARIANT_FUSED):
+    for variant in (B.VARIANT_SPLIT, B.VARIANT_FUSED, B.VARIANT_CHAIN):
         yb, _ = run_gpu(layer, inputs, B.make_tuning(variant=variant))
         for b in range(4):
             y1, _ = run_gpu(one, dict(inputs, x=inputs["x"][b:b + 1].copy()), B.make_tuning(variant=variant))
