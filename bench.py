@@ -9,8 +9,13 @@ fp32), each layer one tdc_conv_tucker2 call on the current stream with inputs an
 weights already resident in HBM.  Prints ONE JSON line.
 
   value        effective GFLOP/s of the sweep: algorithmic FLOPs of the four layers / step time
-  layers       per-layer latency (us, event-timed over back-to-back launches), GFLOP/s and the
-               fraction of that layer's roofline max(bytes/8 TB/s, flops/157.3 TFLOP/s)
+  layers       per layer: latency_us (event-timed over back-to-back launches on one stream, the
+               primary figure), sync_latency_us (one launch + host synchronise, median),
+               cold_latency_us (back-to-back launches that cycle through more than 512 MB of distinct
+               x / y buffers, so no activation is found in a cache), GFLOP/s, the fraction of the
+               layer's roofline max(bytes/8 TB/s, flops/157.3 TFLOP/s), dense_conv_us (this
+               library's kernel for the undecomposed K x K layer, timed the same way) and oracle_us
+               (the CPU oracle's three-stage and dense paths, all host threads and one thread)
   roofline     the same for the dominant (slowest) layer's kernel
   null_launch_us  an empty kernel timed the same way: the floor any batch-1 layer sits on
   cpu_baseline the CPU oracle (three-stage, fp64) timed on the host cores on the same sweep
@@ -43,6 +48,65 @@ def _time_events(fn, iters, torch):
     return start.elapsed_time(stop) * 1e-3 / iters   # seconds per call
 
 
+def _time_sync(fn, iters, torch):
+    """Median wall time of one launch followed by a host synchronise."""
+    ts = []
+    for _ in range(iters):
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        ts.append(time.perf_counter() - t0)
+    ts.sort()
+    return ts[len(ts) // 2]
+
+
+def _time_cold(conv, L, x, torch, min_bytes=512 << 20, max_sets=2048):
+    """Seconds per call when every call reads and writes buffers no earlier call of the pass touched."""
+    y_shape = (L.batch, L.N, conv.Ho, conv.Wo)
+    per_set = 4 * (x.numel() + L.batch * L.N * conv.Ho * conv.Wo)
+    n_sets = max(2, min(max_sets, -(-min_bytes // per_set)))
+    xs = [x.clone() for _ in range(n_sets)]
+    ys = [torch.empty(y_shape, device=x.device, dtype=torch.float32) for _ in range(n_sets)]
+    launchers = [conv.bind(a, b) for a, b in zip(xs, ys)]
+    for launch in launchers:                       # one untimed pass: page tables, code
+        launch()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for launch in launchers:
+        launch()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) * 1e-3 / n_sets, n_sets
+
+
+def oracle_layer_times(L, inp, budget_s=1.5):
+    """CPU oracle on one image of the layer: three-stage and dense paths, all threads and one thread (us)."""
+    from oracle import tdc_oracle as orc
+    orc.load()
+    d = L.asdict()
+    d["batch"] = 1
+    sh = orc.Shape(**d)
+    one = dict(inp, x=inp["x"][:1])
+    Wd, _ = orc.reconstruct(sh, one["U_in"], one["core"], one["U_out"])
+    out = {"images": 1}
+    nmax = orc.max_threads()
+    for label, nthr in (("all", nmax), ("1t", 1)):
+        orc.set_threads(nthr)
+        for name, fn in (("factored", lambda: orc.conv_factored(sh, **one)),
+                         ("dense", lambda: orc.conv_dense_with(sh, one["x"], Wd))):
+            fn()
+            best, t_begin = 1e30, time.perf_counter()
+            for _ in range(5):
+                t0 = time.perf_counter()
+                fn()
+                best = min(best, time.perf_counter() - t0)
+                if time.perf_counter() - t_begin > budget_s / 4:
+                    break
+            out["%s_%s" % (name, label)] = best * 1e6
+    orc.set_threads(nmax)
+    return out
+
+
 def cpu_baseline(layers, inputs, budget_s=12.0, max_sweeps=400):
     """The oracle as it stands (three-stage, Eqs. 2-4, fp64 accumulation, OpenMP over output channels)."""
     from oracle import tdc_oracle as orc
@@ -60,7 +124,7 @@ def cpu_baseline(layers, inputs, budget_s=12.0, max_sweeps=400):
         sweeps += 1
     dt = time.perf_counter() - t0
     return {"value": fl * sweeps / dt / 1e9, "unit": "GFLOP/s", "cores": orc.max_threads(), "kind": "oracle",
-            "sample": "%d passes of the same 4-layer sweep, three-stage path, %.1f s wall" % (sweeps, dt),
+            "sample": "%d passes over the same %d layer(s), three-stage path, %.1f s wall" % (sweeps, len(layers), dt),
             "us_per_sweep": dt / sweeps * 1e6}
 
 
@@ -70,8 +134,10 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default: the ResNet-18-shaped sweep)")
-    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused"])
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the per-layer oracle times")
+    ap.add_argument("--brief", action="store_true",
+                    help="only the queued latency per layer (no sync / cold-cache / dense-kernel columns)")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by)")
@@ -82,8 +148,8 @@ def main():
     import torch
     from paper_2211_03715_amd import binding as B
     from paper_2211_03715_amd import roofline as R
-    from paper_2211_03715_amd.layer import TuckerConv2d
-    from paper_2211_03715_amd.workloads import config_layers, layer_seed, make_inputs
+    from paper_2211_03715_amd.layer import DenseConv2d, TuckerConv2d
+    from paper_2211_03715_amd.workloads import config_layers, layer_seed, make_dense_inputs, make_inputs
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
@@ -91,7 +157,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     variant = {"auto": B.VARIANT_AUTO, "naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT,
-               "fused": B.VARIANT_FUSED}[args.variant]
+               "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN}[args.variant]
 
     layers = config_layers(args.config)
     host_inputs = [make_inputs(L, layer_seed(args.config, i)) for i, L in enumerate(layers)]
@@ -126,20 +192,39 @@ def main():
     # per-layer: events around back-to-back launches of that layer alone, on the launch stream
     iters = max(200, min(2000, args.steps))
     per_layer = []
-    for L, conv, launch in zip(layers, convs, launchers):
+    for i, (L, conv, launch) in enumerate(zip(layers, convs, launchers)):
         for _ in range(20):
             launch()
         sec = _time_events(launch, iters, torch)
         bound, t_roof, t_hbm, t_mfma = R.roofline(L)
-        per_layer.append({
+        row = {
             "layer": L.name(), "plan": conv.describe(), "kernels": conv.kernel_count(),
             "latency_us": sec * 1e6, "gflops": R.flops(L) / sec / 1e9,
             "dense_equiv_gflops": R.dense_flops(L) / sec / 1e9,
             "bound": bound, "roofline_us": t_roof * 1e6, "roofline_frac": t_roof / sec,
-        })
+        }
+        if not args.brief:
+            row["sync_latency_us"] = _time_sync(launch, 200, torch) * 1e6
+            cold, n_sets = _time_cold(conv, L, xs[i], torch)
+            row["cold_latency_us"], row["cold_buffer_sets"] = cold * 1e6, n_sets
+            # the undecomposed layer on this library's own dense kernel (the t2 of the paper's threshold test)
+            dense = DenseConv2d(L, 0)
+            W = torch.from_numpy(make_dense_inputs(L, layer_seed(args.config, i) + 500)["W"]).to(dev)
+            dense.pack(W)
+            dl = dense.bind(xs[i], ys[i])
+            for _ in range(20):
+                dl()
+            row["dense_conv_us"] = _time_events(dl, max(50, iters // 4), torch) * 1e6
+            row["dense_conv_plan"] = dense.describe()
+            row["speedup_vs_dense_conv"] = row["dense_conv_us"] / row["latency_us"]
+            torch.cuda.synchronize()
+            dense.close()
+            launch()                              # ys[i] holds the Tucker layer's output again
+        per_layer.append(row)
     import ctypes
     null_fn, null_stream = B.load().tdc_launch_null, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     null_us = _time_events(lambda: null_fn(null_stream), 2000, torch) * 1e6
+    null_sync_us = _time_sync(lambda: null_fn(null_stream), 200, torch) * 1e6
 
     dom = max(range(len(layers)), key=lambda i: per_layer[i]["latency_us"])
     Ld, pd = layers[dom], per_layer[dom]
@@ -169,10 +254,14 @@ def main():
         "roofline": roof,
         "layers": per_layer,
         "null_launch_us": null_us,
+        "null_sync_us": null_sync_us,
         "sum_layer_latency_us": sum(p["latency_us"] for p in per_layer),
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
+        if not args.brief:
+            for row, L, inp in zip(per_layer, layers, host_inputs):
+                row["oracle_us"] = oracle_layer_times(L, inp)
     if args.copy_mib > 0:
         src = torch.empty(args.copy_mib * 262144, device=dev, dtype=torch.float32).normal_()
         dst = torch.empty_like(src)

@@ -72,8 +72,11 @@ enum {
     TDC_VARIANT_NAIVE = 1,  /* three plain fp32 kernels, one thread per output pixel            */
     TDC_VARIANT_SPLIT = 2,  /* three fp32-MFMA GEMM kernels, intermediates z1/z2 in workspace   */
     TDC_VARIANT_FUSED = 3,  /* one fp32-MFMA kernel per spatial tile, z1/z2 kept in LDS         */
-    TDC_VARIANT_CHAIN = 4   /* fused; each wavefront keeps its z2 columns in registers and feeds
+    TDC_VARIANT_CHAIN = 4,  /* fused; each wavefront keeps its z2 columns in registers and feeds
                                them straight into stage 3 (throughput regime)                   */
+    TDC_VARIANT_DENSE = 5   /* not a Tucker kernel: the undecomposed K x K layer as one implicit-GEMM
+                               MFMA kernel, for tdc_conv_dense only.  Never chosen by AUTO; a plan
+                               made with it ignores R1 and R2                                   */
 };
 
 /* Launch parameters.  Zero in any field means "selector's choice".
@@ -108,6 +111,20 @@ int tdc_plan_pack_weights(tdc_plan *plan, void *hip_stream,
 int tdc_conv_tucker2(tdc_plan *plan, void *hip_stream,
                      const float *x, const float *U_in, const float *core, const float *U_out,
                      float *y, const tdc_shape *shape);
+
+/* The undecomposed layer, y = K (*) x with the dense kernel W[C][N][K][K] = K(c,n,r,s) of Eq. 1
+ * (same index order as `core`, same padding / stride / cross-correlation rule, x and y as above).
+ * This is the "original convolution" of the paper's rank selection (section 6): a layer is only
+ * decomposed if its Tucker latency t1 beats the original layer's latency t2 by the threshold
+ * theta, so a caller building the latency table needs both from the same library.
+ * `plan` must have been created by tdc_plan_create_tuned with variant TDC_VARIANT_DENSE (fields
+ * mb[1], pb[1], waves[1] may be forced; R1 and R2 of the shape must be positive and are otherwise
+ * ignored); on such a plan tdc_conv_tucker2 and tdc_plan_pack_weights return TDC_ERR_BAD_TUNING, and
+ * so do the two calls below on any other plan.  tdc_plan_pack_dense stores the re-laid-out copy of W
+ * exactly as tdc_plan_pack_weights does for the factors; without it every call re-lays W out first. */
+int tdc_plan_pack_dense(tdc_plan *plan, void *hip_stream, const float *W);
+int tdc_conv_dense(tdc_plan *plan, void *hip_stream, const float *x, const float *W, float *y,
+                   const tdc_shape *shape);
 
 /* Release the plan and its workspace.  NULL is accepted. */
 int tdc_plan_destroy(tdc_plan *plan);

@@ -22,14 +22,14 @@ TDC_ERR_ALLOC = -5
 TDC_ERR_HIP = -6
 TDC_ERR_BAD_TUNING = -7
 
-VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN = 0, 1, 2, 3, 4
-VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain"}
+VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN, VARIANT_DENSE = 0, 1, 2, 3, 4, 5
+VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense"}
 
 # every symbol include/tdc.h declares
 EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", "tdc_conv_tucker2",
            "tdc_plan_destroy", "tdc_plan_get_tuning", "tdc_plan_describe", "tdc_plan_workspace_bytes",
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
-           "tdc_select_tuning", "tdc_launch_null"]
+           "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -75,6 +75,10 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_plan_pack_weights.restype = ip
     lib.tdc_conv_tucker2.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp]
     lib.tdc_conv_tucker2.restype = ip
+    lib.tdc_plan_pack_dense.argtypes = [vp, vp, vp]
+    lib.tdc_plan_pack_dense.restype = ip
+    lib.tdc_conv_dense.argtypes = [vp, vp, vp, vp, vp, sp]
+    lib.tdc_conv_dense.restype = ip
     lib.tdc_plan_destroy.argtypes = [vp]
     lib.tdc_plan_destroy.restype = ip
     lib.tdc_plan_get_tuning.argtypes = [vp, tp]
@@ -187,6 +191,18 @@ def tdc_conv_tucker2(plan, x, U_in, core, U_out, y, shape: tdc_shape, stream=Non
                                  _ptr(y), ctypes.byref(shape))
     if rc != TDC_OK:
         raise TdcError(rc, "tdc_conv_tucker2")
+
+
+def tdc_plan_pack_dense(plan, W, stream=None) -> None:
+    rc = load().tdc_plan_pack_dense(plan, _stream(stream), _ptr(W))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_pack_dense")
+
+
+def tdc_conv_dense(plan, x, W, y, shape: tdc_shape, stream=None) -> None:
+    rc = load().tdc_conv_dense(plan, _stream(stream), _ptr(x), _ptr(W), _ptr(y), ctypes.byref(shape))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_conv_dense")
 
 
 def tdc_plan_get_tuning(plan) -> tdc_tuning:

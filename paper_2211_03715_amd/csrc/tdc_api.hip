@@ -60,10 +60,22 @@ int validate(const tdc_shape &s)
     if ((double)cp * r1p >= lim || (double)r1p * r2p * s.K * s.K >= lim || (double)r2p * np >= lim) return TDC_ERR_UNSUPPORTED;
     // one image of any activation and each re-laid-out weight array must fit a 2 GiB buffer descriptor
     const double lim4 = (double)lim / 4;
-    if ((double)s.C * s.H * s.W >= lim4 || (double)r1p * s.H * s.W >= lim4 || (double)r2p * Ho * Wo >= lim4) return TDC_ERR_UNSUPPORTED;
+    if ((double)cp * s.H * s.W >= lim4 || (double)r1p * s.H * s.W >= lim4 || (double)r2p * Ho * Wo >= lim4) return TDC_ERR_UNSUPPORTED;
     if ((double)cp * r1p >= lim4 || (double)r1p * r2p * s.K * s.K >= lim4 || (double)r2p * np >= lim4) return TDC_ERR_UNSUPPORTED;
     if (s.batch > 65535) return TDC_ERR_UNSUPPORTED;   // images ride in the grid's y dimension
     return TDC_OK;
+}
+
+// The shape the kernels see: a DENSE plan runs the stage-2 kernel with the layer's own channel
+// counts standing in for the ranks.
+tdc_shape kernel_shape(const tdc_shape &s, int variant)
+{
+    tdc_shape k = s;
+    if (variant == TDC_VARIANT_DENSE) {
+        k.R1 = s.C;
+        k.R2 = s.N;
+    }
+    return k;
 }
 
 TdcDims make_dims(const tdc_shape &s)
@@ -84,9 +96,15 @@ int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
     if (t.variant == TDC_VARIANT_NAIVE) return TDC_OK;
     for (int i = 0; i < 3; ++i)
         if (t.waves[i] < 1 || t.waves[i] > 8) return TDC_ERR_BAD_TUNING;
-    const int nb[3] = {p.dims.NB1, p.dims.NB2, p.dims.NB3};
+    const bool dense = t.variant == TDC_VARIANT_DENSE;   // one kernel, tiled over the blocks of N
+    const int nb[3] = {dense ? p.dims.NB2 : p.dims.NB1, p.dims.NB2, dense ? p.dims.NB2 : p.dims.NB3};
     for (int i = 0; i < 3; ++i)
         if (t.mb[i] < 1 || nb[i] % t.mb[i]) return TDC_ERR_BAD_TUNING;   // whole register tiles only
+    if (t.variant == TDC_VARIANT_DENSE) {
+        if (!tdc_gemm_unit_supported(t.mb[1], t.pb[1])) return TDC_ERR_BAD_TUNING;
+        if (t.waves[1] > 1 && (size_t)t.waves[1] * t.mb[1] * t.pb[1] * 1024 > 64 * 1024) return TDC_ERR_BAD_TUNING;
+        return TDC_OK;
+    }
     if (t.variant == TDC_VARIANT_SPLIT) {
         for (int i = 0; i < 3; ++i) {
             if (!tdc_gemm_unit_supported(t.mb[i], t.pb[i])) return TDC_ERR_BAD_TUNING;
@@ -123,6 +141,9 @@ void describe(tdc_plan &p)
                  "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB%s model=%.1fus",
                  t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.mb[1], t.mb[2], t.pb[0],
                  p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes, p.geom.weights_in_lds ? " wlds" : "", p.model_us);
+    else if (t.variant == TDC_VARIANT_DENSE)
+        snprintf(p.desc, sizeof(p.desc), "dense %dx%d conv (mb,pb,waves)=(%d,%d,%d) model=%.1fus", p.dims.K, p.dims.K,
+                 t.mb[1], t.pb[1], t.waves[1], p.model_us);
     else if (t.variant == TDC_VARIANT_SPLIT)
         snprintf(p.desc, sizeof(p.desc), "split stage(mb,pb,waves)= s1(%d,%d,%d) s2(%d,%d,%d) s3(%d,%d,%d) model=%.1fus",
                  t.mb[0], t.pb[0], t.waves[0], t.mb[1], t.pb[1], t.waves[1], t.mb[2], t.pb[2], t.waves[2], p.model_us);
@@ -163,6 +184,11 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     *out = nullptr;
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
+    const int want = forced ? forced->variant : TDC_VARIANT_AUTO;
+    if (want < TDC_VARIANT_AUTO || want > TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
+    const tdc_shape kshape = kernel_shape(*shape, want);
+    rc = validate(kshape);
+    if (rc != TDC_OK) return rc;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return TDC_ERR_HIP;
     DeviceGuard guard(device);
@@ -179,13 +205,9 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     if (!p) return TDC_ERR_ALLOC;
     memset(p, 0, sizeof(*p));
     p->shape = *shape;
-    p->dims = make_dims(*shape);
+    p->dims = make_dims(kshape);
     p->device = device;
     if (forced) p->tuning = *forced;
-    if (p->tuning.variant < TDC_VARIANT_AUTO || p->tuning.variant > TDC_VARIANT_CHAIN) {
-        delete p;
-        return TDC_ERR_BAD_TUNING;
-    }
     rc = tdc_select(p->dims, dev, &p->tuning, &p->model_us);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)
         p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
@@ -201,12 +223,17 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     const size_t n_z1 = (size_t)d.B * 16 * d.NB1 * d.H * d.W, n_z2 = (size_t)d.B * 16 * d.NB2 * d.Ho * d.Wo;
     const size_t n_w1 = tdc_packed_floats_uin(d), n_w2 = tdc_packed_floats_core(d), n_w3 = tdc_packed_floats_uout(d);
     bool ok = true;
-    if (p->tuning.variant != TDC_VARIANT_FUSED && p->tuning.variant != TDC_VARIANT_CHAIN) {
+    const bool dense = p->tuning.variant == TDC_VARIANT_DENSE;
+    if (dense) {
+        ok = ok && hipMalloc((void **)&p->core_p, n_w2 * sizeof(float)) == hipSuccess;
+        p->ws_bytes += n_w2 * sizeof(float);
+    }
+    if (!dense && p->tuning.variant != TDC_VARIANT_FUSED && p->tuning.variant != TDC_VARIANT_CHAIN) {
         ok = ok && hipMalloc((void **)&p->z1, n_z1 * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->z2, n_z2 * sizeof(float)) == hipSuccess;
         p->ws_bytes += (n_z1 + n_z2) * sizeof(float);
     }
-    if (p->tuning.variant != TDC_VARIANT_NAIVE) {
+    if (!dense && p->tuning.variant != TDC_VARIANT_NAIVE) {
         ok = ok && hipMalloc((void **)&p->uin_p, n_w1 * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->core_p, n_w2 * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->uout_p, n_w3 * sizeof(float)) == hipSuccess;
@@ -228,13 +255,16 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
     if (compute_units < 1 || lds_bytes < 1024) return TDC_ERR_BAD_TUNING;
-    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_CHAIN) return TDC_ERR_BAD_TUNING;
+    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
+    const tdc_shape kshape = kernel_shape(*shape, inout->variant);
+    rc = validate(kshape);
+    if (rc != TDC_OK) return rc;
     TdcDeviceInfo dev;
     dev.cus = compute_units;
     dev.lds_per_wg = lds_bytes;
     tdc_plan tmp;
     memset(&tmp, 0, sizeof(tmp));
-    tmp.dims = make_dims(*shape);
+    tmp.dims = make_dims(kshape);
     tmp.tuning = *inout;
     rc = tdc_select(tmp.dims, dev, &tmp.tuning, nullptr);
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED)
@@ -266,6 +296,7 @@ int tdc_plan_destroy(tdc_plan *p)
 int tdc_plan_pack_weights(tdc_plan *p, void *hip_stream, const float *U_in, const float *core, const float *U_out)
 {
     if (!p || !U_in || !core || !U_out) return TDC_ERR_NULL;
+    if (p->tuning.variant == TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
     p->packed_from[0] = p->packed_from[1] = p->packed_from[2] = nullptr;
     if (p->tuning.variant == TDC_VARIANT_NAIVE) {   // reads the caller's layouts directly
         p->packed_from[0] = U_in; p->packed_from[1] = core; p->packed_from[2] = U_out;
@@ -284,6 +315,7 @@ int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float 
 {
     if (!p || !x || !U_in || !core || !U_out || !y || !shape) return TDC_ERR_NULL;
     if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
+    if (p->tuning.variant == TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
     DeviceGuard guard(p->device);
     if (!guard.ok) return TDC_ERR_HIP;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -308,6 +340,33 @@ int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float 
     return e == hipSuccess ? TDC_OK : TDC_ERR_HIP;
 }
 
+int tdc_plan_pack_dense(tdc_plan *p, void *hip_stream, const float *W)
+{
+    if (!p || !W) return TDC_ERR_NULL;
+    if (p->tuning.variant != TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
+    p->packed_from[1] = nullptr;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return TDC_ERR_HIP;
+    if (tdc_launch_pack_core(p->dims, (hipStream_t)hip_stream, W, p->core_p) != hipSuccess) return TDC_ERR_HIP;
+    p->packed_from[1] = W;
+    return TDC_OK;
+}
+
+int tdc_conv_dense(tdc_plan *p, void *hip_stream, const float *x, const float *W, float *y, const tdc_shape *shape)
+{
+    if (!p || !x || !W || !y || !shape) return TDC_ERR_NULL;
+    if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
+    if (p->tuning.variant != TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return TDC_ERR_HIP;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (p->packed_from[1] != W) {   // no stored copy for this pointer: re-lay out on the stream, remember nothing
+        p->packed_from[1] = nullptr;
+        if (tdc_launch_pack_core(p->dims, s, W, p->core_p) != hipSuccess) return TDC_ERR_HIP;
+    }
+    return tdc_launch_dense(p->dims, p->tuning, s, x, p->core_p, y) == hipSuccess ? TDC_OK : TDC_ERR_HIP;
+}
+
 int tdc_plan_get_tuning(const tdc_plan *p, tdc_tuning *out)
 {
     if (!p || !out) return TDC_ERR_NULL;
@@ -327,7 +386,8 @@ size_t tdc_plan_workspace_bytes(const tdc_plan *p) { return p ? p->ws_bytes : 0;
 int tdc_plan_kernel_count(const tdc_plan *p)
 {
     if (!p) return 0;
-    return (p->tuning.variant == TDC_VARIANT_FUSED || p->tuning.variant == TDC_VARIANT_CHAIN) ? 1 : 3;
+    const int v = p->tuning.variant;
+    return (v == TDC_VARIANT_FUSED || v == TDC_VARIANT_CHAIN || v == TDC_VARIANT_DENSE) ? 1 : 3;
 }
 
 int tdc_launch_null(void *hip_stream)

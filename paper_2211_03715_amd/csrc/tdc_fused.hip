@@ -136,7 +136,6 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
                 pipe.start(next);
             }
             tdc_f4 acc[MB1][PB];
-            tdc_zero<MB1, PB>(acc);
             pipe.run(acc, a.KG1, next);
 #pragma unroll
             for (int mb = 0; mb < MB1; ++mb)
@@ -190,7 +189,6 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
             };
             TdcPipe<MB2, PB, U> pipe;
             tdc_f4 acc[MB2][PB];
-            tdc_zero<MB2, PB>(acc);
             TDC_PROBE(8);
             pipe.start(next);
             pipe.run(acc, KG2, next);
@@ -243,7 +241,6 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
             };
             TdcPipe<MB3, PB, U> pipe;
             tdc_f4 acc[MB3][PB];
-            tdc_zero<MB3, PB>(acc);
             pipe.start(next);
             pipe.run(acc, a.NB2, next);
 #pragma unroll

@@ -133,7 +133,6 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     }
 
     tdc_f4 acc[MB][PB];
-    tdc_zero<MB, PB>(acc);
     TdcPipe<MB, PB, U> pipe;
     TDC_PROBE((MODE - 1) * 5 + 0);
     pipe.start(next);
@@ -255,4 +254,22 @@ hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s
     a.NBm = d.NB3; a.KG = d.NB2; a.NBk = 1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[2] - 1) / t.pb[2];
     return launch_stage<3>(a, t.mb[2], t.pb[2], t.waves[2], d.B, s);
+}
+
+// The undecomposed layer (Eq. 1's kernel applied directly): the stage-2 implicit GEMM with the
+// layer's own channels in place of the ranks.  `d` carries R1 = C and R2 = N, so NB1 counts the
+// 16-blocks of C and NB2 those of N; x has exactly C rows (rows of the last, partial block lie
+// beyond the buffer descriptor and read as zero) and y exactly N.
+hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
+                            const float *w_p, float *y)
+{
+    const int HW = d.H * d.W, P = d.Ho * d.Wo;
+    GemmArgs a;
+    a.act = x; a.wp = w_p; a.out = y;
+    a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
+    a.out_rows = d.N; a.out_pix = P;
+    a.NBm = d.NB2; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
+    a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
+    a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
+    return launch_stage<2>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
 }

@@ -32,6 +32,7 @@ struct TdcDims {
 // ---- weight re-layout (tdc_pack.hip)
 hipError_t tdc_launch_pack(const TdcDims &d, hipStream_t s, const float *U_in, const float *core,
                            const float *U_out, float *uin_p, float *core_p, float *uout_p);
+hipError_t tdc_launch_pack_core(const TdcDims &d, hipStream_t s, const float *core, float *core_p);
 size_t tdc_packed_floats_uin(const TdcDims &d);
 size_t tdc_packed_floats_core(const TdcDims &d);
 size_t tdc_packed_floats_uout(const TdcDims &d);
@@ -45,6 +46,10 @@ bool tdc_gemm_unit_supported(int mb, int pb);
 hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
                             const float *uin_p, const float *core_p, const float *uout_p,
                             float *z1, float *z2, float *y);
+
+// the dense K x K layer through the stage-2 kernel; `d` has R1 = C, R2 = N
+hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
+                            const float *w_p, float *y);
 
 // ---- fused MFMA kernel (tdc_fused.hip)
 struct TdcFusedGeom {

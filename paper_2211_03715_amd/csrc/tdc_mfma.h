@@ -52,25 +52,18 @@ __device__ __forceinline__ tdc_f4 tdc_buf_load4(tdc_rsrc r, unsigned byte_off)
     return __builtin_bit_cast(tdc_f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
 }
 
-// Independent accumulation chains per 16x16 block.  A v_mfma whose SrcC is the result of the
-// MFMA issued just before it stalls for that result, so a register tile with fewer than four
-// blocks splits its k-steps over several accumulators (summed once at the end) to keep four
-// MFMAs in flight.
+// acc[mb][pb] += A(mb, step j) * B(pb, step j) for the four steps of one k-group.  Successive
+// MFMAs may target the same accumulator: v_mfma_f32_16x16x4_f32 issues every 32 cycles even in a
+// dependent chain (measured), so no extra accumulators are needed to keep the pipe busy.
 template <int MB, int PB>
-struct TdcChains {
-    static constexpr int N = MB * PB >= 4 ? 1 : (MB * PB == 2 ? 2 : 4);
-};
-
-// ch[j % NC][mb][pb] += A(mb, step j) * B(pb, step j) for the four steps of one k-group.
-template <int MB, int PB, int NC>
-__device__ __forceinline__ void tdc_mma_group(tdc_f4 (&ch)[NC][MB][PB], const tdc_f4 (&a)[MB], const tdc_f4 (&b)[PB])
+__device__ __forceinline__ void tdc_mma_group(tdc_f4 (&acc)[MB][PB], const tdc_f4 (&a)[MB], const tdc_f4 (&b)[PB])
 {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb) ch[j % NC][mb][pb] = tdc_mfma(a[mb][j], b[pb][j], ch[j % NC][mb][pb]);
+            for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = tdc_mfma(a[mb][j], b[pb][j], acc[mb][pb]);
 }
 
 // Software pipeline over the k-groups of one register tile.  `next(a, b)` fetches the operands
@@ -96,35 +89,22 @@ struct TdcPipe {
     template <class Next>
     __device__ __forceinline__ void run(tdc_f4 (&acc)[MB][PB], int nkg, Next &next)
     {
-        constexpr int NC = TdcChains<MB, PB>::N;
-        tdc_f4 ch[NC][MB][PB];
 #pragma unroll
-        for (int c = 0; c < NC; ++c)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb) ch[c][mb][pb] = tdc_f4_zero();
+            for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = tdc_f4_zero();
         for (int kg = 0; kg < nkg; kg += 2 * U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) next(a1[u], b1[u]);
 #pragma unroll
-            for (int u = 0; u < U; ++u) tdc_mma_group<MB, PB, NC>(ch, a0[u], b0[u]);
+            for (int u = 0; u < U; ++u) tdc_mma_group<MB, PB>(acc, a0[u], b0[u]);
 #pragma unroll
             for (int u = 0; u < U; ++u) next(a0[u], b0[u]);
             if (kg + U < nkg) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) tdc_mma_group<MB, PB, NC>(ch, a1[u], b1[u]);
+                for (int u = 0; u < U; ++u) tdc_mma_group<MB, PB>(acc, a1[u], b1[u]);
             }
         }
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                tdc_f4 sum = ch[0][mb][pb];
-#pragma unroll
-                for (int c = 1; c < NC; ++c) sum += ch[c][mb][pb];
-                acc[mb][pb] = sum;
-            }
     }
 };
 
@@ -149,14 +129,5 @@ extern "C" int tdc_debug_read_probes(unsigned long long *host, size_t count)
 #else
 #define TDC_PROBE(slot) do { } while (0)
 #endif
-
-template <int MB, int PB>
-__device__ __forceinline__ void tdc_zero(tdc_f4 (&acc)[MB][PB])
-{
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) acc[mb][pb] = tdc_f4_zero();
-}
 
 #endif

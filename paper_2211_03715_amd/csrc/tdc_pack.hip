@@ -65,3 +65,11 @@ hipError_t tdc_launch_pack(const TdcDims &d, hipStream_t s, const float *U_in, c
     hipLaunchKernelGGL(pack_uout_kernel, dim3((unsigned)((n3 + T - 1) / T)), dim3(T), 0, s, d, U_out, uout_p, n3);
     return hipGetLastError();
 }
+
+hipError_t tdc_launch_pack_core(const TdcDims &d, hipStream_t s, const float *core, float *core_p)
+{
+    const int T = 256;
+    const size_t n2 = tdc_packed_floats_core(d);
+    hipLaunchKernelGGL(pack_core_kernel, dim3((unsigned)((n2 + T - 1) / T)), dim3(T), 0, s, d, core, core_p, n2);
+    return hipGetLastError();
+}

@@ -220,6 +220,18 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     if (model_us) *model_us = 0.0;
     const tdc_tuning forced = *t;
     if (forced.variant == TDC_VARIANT_NAIVE) return TDC_OK;
+    if (forced.variant == TDC_VARIANT_DENSE) {
+        // the stage-2 kernel on the layer's own channels: `d` has R1 = C and R2 = N
+        const StageChoice c = best_stage(dev, d.B, d.NB2, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1],
+                                         forced.pb[1], forced.waves[1]);
+        if (c.us >= 1e299) return TDC_ERR_BAD_TUNING;
+        t->tile_h = t->tile_w = 0;
+        for (int i = 0; i < 3; ++i) {
+            t->mb[i] = c.mb; t->pb[i] = c.pb; t->waves[i] = c.nw;
+        }
+        if (model_us) *model_us = c.us;
+        return TDC_OK;
+    }
     if (forced.variant == TDC_VARIANT_CHAIN) {
         const FusedChoice c = best_chain(d, dev, forced);
         if (c.us >= 1e299) return TDC_ERR_BAD_TUNING;

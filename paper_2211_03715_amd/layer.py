@@ -74,3 +74,64 @@ class TuckerConv2d:
             self.close()
         except Exception:
             pass
+
+
+class DenseConv2d:
+    """The undecomposed K x K layer with the kernel W[C][N][K][K] of Eq. 1, on the same library: the
+    "original convolution" the rank-selection threshold test (paper section 6) compares against."""
+
+    def __init__(self, layer, device: int = 0, tuning: Optional[B.tdc_tuning] = None):
+        self.shape = B.make_shape(layer.batch, layer.C, layer.N, layer.H, layer.W, layer.R1, layer.R2,
+                                  layer.K, layer.stride, layer.pad)
+        self.Ho = B.tdc_out_size(layer.H, layer.K, layer.stride, layer.pad)
+        self.Wo = B.tdc_out_size(layer.W, layer.K, layer.stride, layer.pad)
+        t = tuning if tuning is not None else B.make_tuning()
+        t.variant = B.VARIANT_DENSE
+        self.plan = B.tdc_plan_create(self.shape, device, t)
+        self.device = device
+        self._W = None
+
+    def describe(self) -> str:
+        return B.tdc_plan_describe(self.plan)
+
+    def tuning(self) -> dict:
+        return B.tdc_plan_get_tuning(self.plan).as_dict()
+
+    def pack(self, W, stream=None) -> None:
+        self._W = W
+        B.tdc_plan_pack_dense(self.plan, W, stream)
+
+    def __call__(self, x, y=None, W=None, stream=None):
+        import torch
+        W = W if W is not None else self._W
+        if y is None:
+            y = torch.empty((self.shape.batch, self.shape.N, self.Ho, self.Wo), device=x.device,
+                            dtype=torch.float32)
+        B.tdc_conv_dense(self.plan, x, W, y, self.shape, stream)
+        return y
+
+    def bind(self, x, y, W=None, stream=None):
+        """Zero-argument launcher with the arguments of tdc_conv_dense marshalled once."""
+        W = W if W is not None else self._W
+        fn = B.load().tdc_conv_dense
+        vp = ctypes.c_void_p
+        args = (self.plan, vp(B._stream(stream)), vp(x.data_ptr()), vp(W.data_ptr()), vp(y.data_ptr()),
+                ctypes.byref(self.shape))
+
+        def launch():
+            rc = fn(*args)
+            if rc:
+                raise B.TdcError(rc, "tdc_conv_dense")
+
+        return launch
+
+    def close(self) -> None:
+        if self.plan is not None:
+            B.tdc_plan_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -104,3 +104,13 @@ def make_inputs(layer: Layer, seed: int) -> Dict[str, np.ndarray]:
     core *= np.float32((L.R1 * L.K * L.K) ** -0.5)
     U_out *= np.float32(L.R2 ** -0.5)
     return {"x": x, "U_in": U_in, "core": core, "U_out": U_out}
+
+
+def make_dense_inputs(layer: Layer, seed: int) -> Dict[str, np.ndarray]:
+    """Inputs of the undecomposed layer: x ~ N(0,1) and a dense kernel W[C][N][K][K] ~ N(0, 1/(C*K*K))."""
+    rng = np.random.default_rng(seed)
+    L = layer
+    x = rng.standard_normal((L.batch, L.C, L.H, L.W), dtype=np.float32)
+    W = rng.standard_normal((L.C, L.N, L.K, L.K), dtype=np.float32)
+    W *= np.float32((L.C * L.K * L.K) ** -0.5)
+    return {"x": x, "W": W}

@@ -116,6 +116,21 @@ def test_selector_respects_forced_fields_and_rejects_misfits():
         B.tdc_select_tuning(s, tuning=B.make_tuning(variant=9))
 
 
+def test_selector_handles_the_dense_layer():
+    lib = B.load()
+    for cfg in (2, 4):
+        for L in config_layers(cfg):
+            t = B.tdc_select_tuning(B.make_shape(**L.asdict()), tuning=B.make_tuning(variant=B.VARIANT_DENSE))
+            d = t.as_dict()
+            assert d["variant"] == "dense" and d["mb"][1] in (1, 2, 4) and 1 <= d["waves"][1] <= 8, d
+            assert ((L.N + 15) // 16) % d["mb"][1] == 0
+    s = B.make_shape(1, 40, 24, 9, 9, 1, 1)           # N = 24 is two 16-blocks: a tile of four cannot divide it
+    with pytest.raises(B.TdcError):
+        B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_DENSE, mb=(0, 4, 0)))
+    assert lib.tdc_conv_dense(None, None, None, None, None, ctypes.byref(s)) == B.TDC_ERR_NULL
+    assert lib.tdc_plan_pack_dense(None, None, None) == B.TDC_ERR_NULL
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError):
         B.load(str(tmp_path / "libtdc.so"))
