@@ -134,7 +134,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default: the ResNet-18-shaped sweep)")
-    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the per-layer oracle times")
     ap.add_argument("--brief", action="store_true",
                     help="only the queued latency per layer (no sync / cold-cache / dense-kernel columns)")
@@ -157,7 +157,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     variant = {"auto": B.VARIANT_AUTO, "naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT,
-               "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN}[args.variant]
+               "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN, "merged": B.VARIANT_MERGED}[args.variant]
 
     layers = config_layers(args.config)
     host_inputs = [make_inputs(L, layer_seed(args.config, i)) for i, L in enumerate(layers)]

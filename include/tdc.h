@@ -74,6 +74,11 @@ enum {
     TDC_VARIANT_FUSED = 3,  /* one fp32-MFMA kernel per spatial tile, z1/z2 kept in LDS         */
     TDC_VARIANT_CHAIN = 4,  /* fused; each wavefront keeps its z2 columns in registers and feeds
                                them straight into stage 3 (throughput regime)                   */
+    TDC_VARIANT_MERGED = 6, /* two kernels: stage 1, then ONE K x K implicit GEMM R1 -> N whose kernel
+                               core x_2 U_out is formed when the weights are re-laid out.  More MACs
+                               than Eqs. 3+4 (K*K*R1*N against K*K*R1*R2 + R2*N per pixel), same
+                               result; its output-channel blocks run in parallel, which pays on
+                               small images at batch 1 where launches, not FLOPs, set the latency */
     TDC_VARIANT_DENSE = 5   /* not a Tucker kernel: the undecomposed K x K layer as one implicit-GEMM
                                MFMA kernel, for tdc_conv_dense only.  Never chosen by AUTO; a plan
                                made with it ignores R1 and R2                                   */
@@ -81,7 +86,8 @@ enum {
 
 /* Launch parameters.  Zero in any field means "selector's choice".
  *   tile_h, tile_w : output tile of one workgroup            (FUSED, CHAIN)
- *   waves          : wavefronts (of 64 lanes) per workgroup  (SPLIT: per stage; FUSED, CHAIN: waves[0])
+ *   waves          : wavefronts (of 64 lanes) per workgroup  (SPLIT: per stage; FUSED, CHAIN: waves[0];
+ *                    MERGED: [0] for stage 1, [1] for the merged convolution, likewise mb and pb)
  *   mb, pb         : 16-channel and 16-pixel blocks per wavefront register tile, per stage
  *                    (CHAIN uses mb[0] and pb[0]; its stage-2 tile is all of R2 by construction) */
 typedef struct tdc_tuning {
@@ -147,6 +153,43 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
  * are of the same order (the paper, section 6, also notes that launch time of the extra 1x1
  * kernels can outweigh the saved FLOPs). */
 int tdc_launch_null(void *hip_stream);
+
+/* Hardware-aware rank selection, host only (paper section 6; first step of Algorithm 1).
+ * For each layer, in the order given: among the entries of its measured latency table whose Tucker
+ * MACs  P = H*W*C*R1 + Ho*Wo*K*K*R1*R2 + Ho*Wo*N*R2  (section 3; batch included) respect the FLOPs
+ * budget, take those of minimal latency -- within the relative tolerance `tie_tol`, 0 for exact
+ * ties only -- and among these the largest ranks (largest R1*R2, then R1+R2, then R1).  The layer
+ * is decomposed only if that latency t1 < (1 - theta) * t2, t2 = dense_latency_us of its original
+ * convolution (the paper uses theta = 0.15).
+ * `budget` in [0,1) is the target MAC reduction ratio over all listed layers.  Layer l may keep at
+ * most (1 - b_l) * F_l MACs, F_l = Ho*Wo*K*K*C*N, with
+ *     b_l = max(0, (budget * sum_k F_k - MACs removed by layers before l) / sum_{k >= l} F_k),
+ * so the share of a layer that stays dense passes to the layers after it.
+ * R1, R2 and layout of `shape` are ignored.  Table entries of one layer must have distinct
+ * (R1, R2), positive ranks and latencies.  out[l] receives the choice for layer l: decomposed = 1
+ * with the ranks, their table latency and P, or decomposed = 0, R1 = R2 = 0, t2 and F_l.
+ * Returns TDC_ERR_NULL or TDC_ERR_BAD_SHAPE on invalid arguments; never touches a device. */
+typedef struct tdc_rank_entry {
+    int32_t R1, R2;
+    double latency_us;
+} tdc_rank_entry;
+
+typedef struct tdc_rank_layer {
+    tdc_shape shape;
+    const tdc_rank_entry *table;   /* host pointer, n_entries elements, caller-owned */
+    int32_t n_entries;
+    double dense_latency_us;
+} tdc_rank_layer;
+
+typedef struct tdc_rank_choice {
+    int32_t decomposed;
+    int32_t R1, R2;
+    double latency_us;
+    double macs;
+} tdc_rank_choice;
+
+int tdc_select_ranks(const tdc_rank_layer *layers, int n_layers, double budget, double theta,
+                     double tie_tol, tdc_rank_choice *out);
 
 /* Output size rule used everywhere: floor((in + 2*pad - K)/stride) + 1; returns 0 on bad input. */
 int tdc_out_size(int in, int K, int stride, int pad);

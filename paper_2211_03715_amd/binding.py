@@ -22,14 +22,14 @@ TDC_ERR_ALLOC = -5
 TDC_ERR_HIP = -6
 TDC_ERR_BAD_TUNING = -7
 
-VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN, VARIANT_DENSE = 0, 1, 2, 3, 4, 5
-VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense"}
+VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN, VARIANT_DENSE, VARIANT_MERGED = 0, 1, 2, 3, 4, 5, 6
+VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense", 6: "merged"}
 
 # every symbol include/tdc.h declares
 EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", "tdc_conv_tucker2",
            "tdc_plan_destroy", "tdc_plan_get_tuning", "tdc_plan_describe", "tdc_plan_workspace_bytes",
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
-           "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense"]
+           "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -44,6 +44,20 @@ class tdc_tuning(ctypes.Structure):
     def as_dict(self):
         return {"variant": VARIANT_NAMES.get(self.variant, self.variant), "tile_h": self.tile_h,
                 "tile_w": self.tile_w, "waves": list(self.waves), "mb": list(self.mb), "pb": list(self.pb)}
+
+
+class tdc_rank_entry(ctypes.Structure):
+    _fields_ = [("R1", ctypes.c_int32), ("R2", ctypes.c_int32), ("latency_us", ctypes.c_double)]
+
+
+class tdc_rank_layer(ctypes.Structure):
+    _fields_ = [("shape", tdc_shape), ("table", ctypes.POINTER(tdc_rank_entry)), ("n_entries", ctypes.c_int32),
+                ("dense_latency_us", ctypes.c_double)]
+
+
+class tdc_rank_choice(ctypes.Structure):
+    _fields_ = [("decomposed", ctypes.c_int32), ("R1", ctypes.c_int32), ("R2", ctypes.c_int32),
+                ("latency_us", ctypes.c_double), ("macs", ctypes.c_double)]
 
 
 class TdcError(RuntimeError):
@@ -99,6 +113,9 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_select_tuning.restype = ip
     lib.tdc_launch_null.argtypes = [vp]
     lib.tdc_launch_null.restype = ip
+    lib.tdc_select_ranks.argtypes = [ctypes.POINTER(tdc_rank_layer), ip, ctypes.c_double, ctypes.c_double,
+                                     ctypes.c_double, ctypes.POINTER(tdc_rank_choice)]
+    lib.tdc_select_ranks.restype = ip
     if path is None:
         _lib = lib
     return lib
@@ -233,3 +250,30 @@ def tdc_launch_null(stream=None) -> None:
     rc = load().tdc_launch_null(_stream(stream))
     if rc != TDC_OK:
         raise TdcError(rc, "tdc_launch_null")
+
+
+def tdc_select_ranks(layers, tables, dense_latency, budget: float, theta: float = 0.15, tie_tol: float = 0.0):
+    """``layers``: objects or dicts with batch, C, N, H, W, K, stride, pad; ``tables``: per layer a list of
+    (R1, R2, latency_us); ``dense_latency``: per layer the original convolution's latency.
+    Returns one dict per layer: decomposed, R1, R2, latency_us, macs."""
+    n = len(layers)
+    if not (n == len(tables) == len(dense_latency)):
+        raise ValueError("layers, tables and dense_latency must have the same length")
+    arr = (tdc_rank_layer * n)()
+    keep = []
+    for i, (L, tab, t2) in enumerate(zip(layers, tables, dense_latency)):
+        g = (lambda k: L[k]) if isinstance(L, dict) else (lambda k: getattr(L, k))
+        arr[i].shape = make_shape(g("batch"), g("C"), g("N"), g("H"), g("W"), 1, 1, g("K"), g("stride"), g("pad"))
+        ent = (tdc_rank_entry * max(1, len(tab)))()
+        for j, (r1, r2, t) in enumerate(tab):
+            ent[j].R1, ent[j].R2, ent[j].latency_us = int(r1), int(r2), float(t)
+        keep.append(ent)
+        arr[i].table = ctypes.cast(ent, ctypes.POINTER(tdc_rank_entry))
+        arr[i].n_entries = len(tab)
+        arr[i].dense_latency_us = float(t2)
+    out = (tdc_rank_choice * n)()
+    rc = load().tdc_select_ranks(arr, n, float(budget), float(theta), float(tie_tol), out)
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_select_ranks")
+    return [{"decomposed": bool(o.decomposed), "R1": o.R1, "R2": o.R2, "latency_us": o.latency_us, "macs": o.macs}
+            for o in out]

@@ -273,3 +273,28 @@ hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
     return launch_stage<2>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
 }
+
+// MERGED variant: two launches.  Stage 1 as in SPLIT; then one implicit GEMM R1 -> N with the
+// kernel Wm = core x_2 U_out (stage 3 folded into the core when the weights are re-laid out).  It
+// spends K*K*R1*N instead of K*K*R1*R2 + R2*N MACs per output pixel, but its output-channel
+// blocks are independent workgroups, which is what a small image lacks, and a launch is saved.
+hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
+                             const float *uin_p, const float *wm_p, float *z1, float *y)
+{
+    const int HW = d.H * d.W, P = d.Ho * d.Wo;
+    GemmArgs a;
+    a.act = x; a.wp = uin_p; a.out = z1;
+    a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
+    a.out_rows = 16 * d.NB1; a.out_pix = HW;
+    a.NBm = d.NB1; a.KG = d.KG1; a.NBk = 1;
+    a.n_pgroups = ((HW + 15) / 16 + t.pb[0] - 1) / t.pb[0];
+    a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
+    hipError_t e = launch_stage<1>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
+    if (e != hipSuccess) return e;
+    a.act = z1; a.wp = wm_p; a.out = y;
+    a.act_rows = 16 * d.NB1; a.act_rows_valid = 16 * d.NB1; a.act_pix = HW;
+    a.out_rows = d.N; a.out_pix = P;
+    a.NBm = d.NB3; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
+    a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
+    return launch_stage<2>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+}

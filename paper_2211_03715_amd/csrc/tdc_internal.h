@@ -33,6 +33,9 @@ struct TdcDims {
 hipError_t tdc_launch_pack(const TdcDims &d, hipStream_t s, const float *U_in, const float *core,
                            const float *U_out, float *uin_p, float *core_p, float *uout_p);
 hipError_t tdc_launch_pack_core(const TdcDims &d, hipStream_t s, const float *core, float *core_p);
+// U_in as usual; Wm[R1][N][K][K] = core x_2 U_out into `wm`, then re-laid out into `wm_p` [NB3][K*K*NB1]
+hipError_t tdc_launch_pack_merged(const TdcDims &d, hipStream_t s, const float *U_in, const float *core,
+                                  const float *U_out, float *uin_p, float *wm, float *wm_p);
 size_t tdc_packed_floats_uin(const TdcDims &d);
 size_t tdc_packed_floats_core(const TdcDims &d);
 size_t tdc_packed_floats_uout(const TdcDims &d);
@@ -50,6 +53,10 @@ hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s
 // the dense K x K layer through the stage-2 kernel; `d` has R1 = C, R2 = N
 hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
                             const float *w_p, float *y);
+
+// stage 1, then stages 2 and 3 as one implicit GEMM with the merged kernel
+hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
+                             const float *uin_p, const float *wm_p, float *z1, float *y);
 
 // ---- fused MFMA kernel (tdc_fused.hip)
 struct TdcFusedGeom {

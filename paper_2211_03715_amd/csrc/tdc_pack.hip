@@ -53,7 +53,37 @@ __global__ void pack_uout_kernel(TdcDims d, const float *__restrict__ U_out, flo
     out[e] = (d2 < d.R2 && m < d.N) ? U_out[(size_t)d2 * d.N + m] : 0.f;
 }
 
+// Wm[d1][n][r][s] = sum_d2 core[d1][d2][r][s] * U_out[d2][n]: stage 3 folded into the core.
+__global__ void merge_core_uout_kernel(TdcDims d, const float *__restrict__ core, const float *__restrict__ U_out,
+                                       float *__restrict__ wm, size_t total)
+{
+    size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    const int KK = d.K * d.K;
+    const int tap = (int)(e % KK);
+    const int n = (int)((e / KK) % d.N);
+    const int d1 = (int)(e / ((size_t)KK * d.N));
+    float acc = 0.f;
+    for (int d2 = 0; d2 < d.R2; ++d2) acc += core[((size_t)d1 * d.R2 + d2) * KK + tap] * U_out[(size_t)d2 * d.N + n];
+    wm[e] = acc;
+}
+
 }  // namespace
+
+hipError_t tdc_launch_pack_merged(const TdcDims &d, hipStream_t s, const float *U_in, const float *core,
+                                  const float *U_out, float *uin_p, float *wm, float *wm_p)
+{
+    const int T = 256;
+    const size_t n1 = tdc_packed_floats_uin(d), nm = (size_t)d.R1 * d.N * d.K * d.K;
+    hipLaunchKernelGGL(pack_uin_kernel, dim3((unsigned)((n1 + T - 1) / T)), dim3(T), 0, s, d, U_in, uin_p, n1);
+    hipLaunchKernelGGL(merge_core_uout_kernel, dim3((unsigned)((nm + T - 1) / T)), dim3(T), 0, s, d, core, U_out, wm, nm);
+    TdcDims m = d;          // the merged kernel is a core tensor with R2 = N
+    m.R2 = d.N;
+    m.NB2 = d.NB3;
+    const size_t n2 = tdc_packed_floats_core(m);
+    hipLaunchKernelGGL(pack_core_kernel, dim3((unsigned)((n2 + T - 1) / T)), dim3(T), 0, s, m, wm, wm_p, n2);
+    return hipGetLastError();
+}
 
 hipError_t tdc_launch_pack(const TdcDims &d, hipStream_t s, const float *U_in, const float *core,
                            const float *U_out, float *uin_p, float *core_p, float *uout_p)

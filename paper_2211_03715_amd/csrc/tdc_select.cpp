@@ -12,9 +12,9 @@
 // per tile, and share >= 1 is the number of wavefronts that time-share one of the CU's four
 // MFMA pipes.  A workgroup round over the chip repeats ceil(WGs / (CUs * resident)) times and
 // one dependent launch adds a constant.  The coefficients (microseconds) were fitted by
-// non-negative least squares to an exhaustive sweep on MI355X (about 6000 fused and 200 split
-// tunings over the batch-1 ResNet-18-shaped layers and the batch-8/32 variants; median
-// relative error 10%); they read as: a launch ~3.6 us when timed back to back, one memory
+// non-negative least squares to exhaustive sweeps on MI355X (about 6000 fused, 4700 chain and
+// 2500 single-GEMM tunings over the batch-1 layers and the batch-8/32 variants; median relative
+// error 5-12%); they read as: a launch ~2.6-3.6 us when timed back to back, one memory
 // round trip ~1.26 us (the unit cost of stage 1, whose operands come from HBM/L2), ~0.02-0.08 us
 // per k-group of issue overhead, and a store-bound stage 3.
 #include <algorithm>
@@ -37,11 +37,20 @@ struct FusedCoef {
     double w_kb = 0.0340;         // per KiB of weights copied into LDS, per co-resident workgroup
 };
 
-struct SplitCoef {
-    double launch = 1.2310;       // per stage
-    double wg = 1.7233;           // per round of workgroups over the chip
-    double kg = 0.0351, mfma = 0.1017;
-    double reduce = 0.2965;       // cross-wavefront sum through LDS, per 16x16 block of the tile
+// One GEMM launch of SPLIT, MERGED or DENSE.  Fitted to ~2500 stage tunings of the batch-1 layers
+// (median relative error 5%, the picked tuning within 10% of the best one timed): a launch
+// costs ~2.6 us however small; a k-group ~0.065 us of issue per wavefront plus its MFMAs; the K x K
+// stage pays for its gathered activation loads per pixel block; and the activation operand is
+// re-read by every output-channel group, which is what makes taller register tiles (mb > 1) pay
+// once there are many channel blocks -- charged as k-group loads per CU over the whole launch,
+// more per load for a strided gather.
+struct StageCoef {
+    double launch = 2.5930;
+    double kg = 0.0649, mfma = 0.0785;
+    double conv_b = 0.0255;       // K x K stage: per k-group and pixel block of the register tile
+    double reduce = 0.3158;       // cross-wavefront sum through LDS, per 16x16 block of the tile
+    double act_1x1 = 0.0653;      // per activation k-group load per CU, 1x1 stages
+    double act_conv = 0.0246;     // same for the K x K stage, times its stride
 };
 
 const int kMb[3] = {1, 2, 4};
@@ -182,11 +191,12 @@ struct StageChoice {
     int mb = 1, pb = 1, nw = 1;
 };
 
-// one SPLIT stage: n_mblocks x n_pblocks output blocks per image, `kgroups` k-groups
+// one GEMM launch: n_mblocks x n_pblocks output blocks per image, `kgroups` k-groups;
+// conv_stride = 0 for a 1x1 stage, the stride for the K x K stage
 StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n_pblocks, int kgroups, int fmb,
-                       int fpb, int fnw)
+                       int fpb, int fnw, int conv_stride)
 {
-    const SplitCoef c;
+    const StageCoef c;
     StageChoice best;
     for (int mb : kMb)
         for (int pb : kMb)
@@ -203,8 +213,11 @@ StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n
                 const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
                 const double share = std::max(1.0, per_cu * nw / 4.0);
                 const int kgw = cdiv(kgroups, nw);
-                const double us = c.launch + rounds * (c.wg + kgw * (c.kg + c.mfma * mb * pb * share) +
-                                                       (nw > 1 ? c.reduce * mb * pb : 0.0));
+                const double act_loads = (double)batch * (n_mblocks / mb) * n_pblocks * kgroups / dev.cus;
+                const double us = c.launch +
+                                  rounds * (kgw * (c.kg + c.mfma * mb * pb * share + (conv_stride ? c.conv_b * pb : 0.0)) +
+                                            (nw > 1 ? c.reduce * mb * pb : 0.0)) +
+                                  act_loads * (conv_stride ? c.act_conv * conv_stride : c.act_1x1);
                 if (us < best.us) {
                     best.us = us;
                     best.mb = mb; best.pb = pb; best.nw = nw;
@@ -223,13 +236,24 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     if (forced.variant == TDC_VARIANT_DENSE) {
         // the stage-2 kernel on the layer's own channels: `d` has R1 = C and R2 = N
         const StageChoice c = best_stage(dev, d.B, d.NB2, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1],
-                                         forced.pb[1], forced.waves[1]);
+                                         forced.pb[1], forced.waves[1], d.stride);
         if (c.us >= 1e299) return TDC_ERR_BAD_TUNING;
         t->tile_h = t->tile_w = 0;
         for (int i = 0; i < 3; ++i) {
             t->mb[i] = c.mb; t->pb[i] = c.pb; t->waves[i] = c.nw;
         }
         if (model_us) *model_us = c.us;
+        return TDC_OK;
+    }
+    if (forced.variant == TDC_VARIANT_MERGED) {
+        const StageChoice a = best_stage(dev, d.B, d.NB1, cdiv(d.H * d.W, 16), d.KG1, forced.mb[0], forced.pb[0], forced.waves[0], 0);
+        const StageChoice b = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1], forced.pb[1],
+                                         forced.waves[1], d.stride);
+        if (a.us >= 1e299 || b.us >= 1e299) return TDC_ERR_BAD_TUNING;
+        t->tile_h = t->tile_w = 0;
+        t->mb[0] = a.mb; t->pb[0] = a.pb; t->waves[0] = a.nw;
+        t->mb[1] = t->mb[2] = b.mb; t->pb[1] = t->pb[2] = b.pb; t->waves[1] = t->waves[2] = b.nw;
+        if (model_us) *model_us = a.us + b.us;
         return TDC_OK;
     }
     if (forced.variant == TDC_VARIANT_CHAIN) {
@@ -265,10 +289,26 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     double split_us = 1e300;
     if (forced.variant == TDC_VARIANT_AUTO || forced.variant == TDC_VARIANT_SPLIT) {
         const int pb_in = cdiv(d.H * d.W, 16), pb_out = cdiv(d.Ho * d.Wo, 16);
-        s[0] = best_stage(dev, d.B, d.NB1, pb_in, d.KG1, forced.mb[0], forced.pb[0], forced.waves[0]);
-        s[1] = best_stage(dev, d.B, d.NB2, pb_out, d.K * d.K * d.NB1, forced.mb[1], forced.pb[1], forced.waves[1]);
-        s[2] = best_stage(dev, d.B, d.NB3, pb_out, d.NB2, forced.mb[2], forced.pb[2], forced.waves[2]);
+        s[0] = best_stage(dev, d.B, d.NB1, pb_in, d.KG1, forced.mb[0], forced.pb[0], forced.waves[0], 0);
+        s[1] = best_stage(dev, d.B, d.NB2, pb_out, d.K * d.K * d.NB1, forced.mb[1], forced.pb[1], forced.waves[1], d.stride);
+        s[2] = best_stage(dev, d.B, d.NB3, pb_out, d.NB2, forced.mb[2], forced.pb[2], forced.waves[2], 0);
         split_us = s[0].us + s[1].us + s[2].us;
+    }
+
+    // MERGED (stage 1, then stages 2+3 as one convolution R1 -> N) against the others: only below
+    // the throughput regime, where its extra MACs cost nothing and its saved launch counts.
+    if (forced.variant == TDC_VARIANT_AUTO && !pixels_fill_chip) {
+        const StageChoice m = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1], forced.pb[1],
+                                         forced.waves[1], d.stride);
+        const double merged_us = s[0].us + m.us;
+        if (merged_us < f.us && merged_us < split_us) {
+            t->variant = TDC_VARIANT_MERGED;
+            t->tile_h = t->tile_w = 0;
+            t->mb[0] = s[0].mb; t->pb[0] = s[0].pb; t->waves[0] = s[0].nw;
+            t->mb[1] = t->mb[2] = m.mb; t->pb[1] = t->pb[2] = m.pb; t->waves[1] = t->waves[2] = m.nw;
+            if (model_us) *model_us = merged_us;
+            return TDC_OK;
+        }
     }
 
     int variant = forced.variant;

@@ -14,7 +14,7 @@ from parity_util import assert_parity, run_gpu
 pytestmark = pytest.mark.gpu
 
 VARIANTS = {"naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT, "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN,
-            "auto": B.VARIANT_AUTO}
+            "merged": B.VARIANT_MERGED, "auto": B.VARIANT_AUTO}
 
 
 def _announce(*parts):
@@ -96,6 +96,23 @@ def test_forced_tunings(orc, name, tuning, layer):
     assert_parity(got, want, "%s %s [%s]" % (name, layer.name(), desc))
 
 
+MERGED_FORCED = [dict(waves=(1, 1, 1), mb=(1, 1, 1), pb=(1, 1, 1)), dict(waves=(8, 8, 8), mb=(1, 2, 2), pb=(4, 2, 2)),
+                 dict(waves=(3, 4, 4), mb=(2, 4, 4), pb=(1, 1, 1)), dict(waves=(2, 6, 6), mb=(1, 1, 1), pb=(2, 4, 4))]
+
+
+@pytest.mark.parametrize("tuning", MERGED_FORCED, ids=lambda t: "w%d-%d_mb%d-%d_pb%d-%d" % (
+    t["waves"][0], t["waves"][1], t["mb"][0], t["mb"][1], t["pb"][0], t["pb"][1]))
+@pytest.mark.parametrize("layer", [Layer(2, 20, 64, 19, 23, 32, 57), Layer(1, 256, 256, 14, 14, 64, 64),
+                                   Layer(2, 33, 128, 12, 40, 32, 57, 3, 2, 1)], ids=lambda l: l.name())
+def test_forced_merged_tunings(orc, tuning, layer):
+    """Stage 1 and the merged stage-2/3 convolution with every register-tile shape."""
+    _announce("forced merged", tuning, layer.name())
+    inputs = make_inputs(layer, 78)
+    want = _oracle(orc, layer, inputs)
+    got, desc = run_gpu(layer, inputs, B.make_tuning(variant=B.VARIANT_MERGED, **tuning))
+    assert_parity(got, want, "%s [%s]" % (layer.name(), desc))
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_full_size_workloads(orc, cfg):
     """Every layer of the five synthetic workloads at full size, in the launch configuration the
@@ -112,7 +129,7 @@ def test_full_size_workloads(orc, cfg):
     print("[config %d] worst E_inf=%.2e E_el=%.2e" % ((cfg,) + worst), flush=True)
 
 
-@pytest.mark.parametrize("variant", ["split", "fused", "chain"])
+@pytest.mark.parametrize("variant", ["split", "fused", "chain", "merged"])
 def test_dense_path_agrees_too(orc, variant):
     """The GPU result also matches the dense convolution with the kernel of Eq. 1."""
     layer = Layer(1, 24, 20, 14, 14, 12, 9)
@@ -123,7 +140,7 @@ def test_dense_path_agrees_too(orc, variant):
     assert_parity(got, want, desc)
 
 
-@pytest.mark.parametrize("variant", ["naive", "split", "fused", "chain"])
+@pytest.mark.parametrize("variant", ["naive", "split", "fused", "chain", "merged"])
 def test_unpacked_weights_path(orc, variant):
     """Without tdc_plan_pack_weights the library re-lays the weights out on every call."""
     layer = Layer(2, 20, 24, 19, 23, 17, 33)
