@@ -211,7 +211,7 @@ def test_error_paths_on_device():
         assert lib.tdc_conv_tucker2(plan, st, *a, ctypes.byref(s)) == B.TDC_ERR_NULL
     assert lib.tdc_conv_tucker2(plan, st, *args, None) == B.TDC_ERR_NULL
     assert lib.tdc_conv_tucker2(plan, st, *args, ctypes.byref(s)) == B.TDC_OK
-    assert B.tdc_plan_workspace_bytes(plan) > 0 and B.tdc_plan_kernel_count(plan) in (1, 3)
+    assert B.tdc_plan_workspace_bytes(plan) > 0 and B.tdc_plan_kernel_count(plan) in (1, 2, 3)
     p2 = ctypes.c_void_p()
     assert lib.tdc_plan_create(ctypes.byref(p2), ctypes.byref(s), 99) == B.TDC_ERR_HIP
     with pytest.raises(B.TdcError):
