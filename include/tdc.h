@@ -79,6 +79,11 @@ enum {
                                than Eqs. 3+4 (K*K*R1*N against K*K*R1*R2 + R2*N per pixel), same
                                result; its output-channel blocks run in parallel, which pays on
                                small images at batch 1 where launches, not FLOPs, set the latency */
+    TDC_VARIANT_FUSED_MERGED = 7, /* one kernel: a workgroup computes stage 1 for its pixel tile into LDS
+                               and then the merged stage-2/3 convolution for its own group of output
+                               channels; workgroups that share a tile recompute stage 1.  Tuning:
+                               tile_h, tile_w (at most 64 pixels), waves[0], mb[0] (stage 1), mb[1] =
+                               16-channel output blocks per workgroup (must divide waves[0])       */
     TDC_VARIANT_DENSE = 5   /* not a Tucker kernel: the undecomposed K x K layer as one implicit-GEMM
                                MFMA kernel, for tdc_conv_dense only.  Never chosen by AUTO; a plan
                                made with it ignores R1 and R2                                   */

@@ -36,7 +36,7 @@ def _tiles(L: Layer):
     return sorted({(min(th, L.Ho), min(tw, L.Wo)) for th in TILE_H for tw in TILE_W if min(th, L.Ho) * min(tw, L.Wo) <= 512})
 
 
-def candidates(L: Layer, variants: Iterable[str] = ("fused", "chain", "split", "merged")) -> List[Dict]:
+def candidates(L: Layer, variants: Iterable[str] = ("fused", "chain", "split", "merged", "fused_merged")) -> List[Dict]:
     """Keyword sets for binding.make_tuning; the library refuses those that do not fit the layer."""
     out: List[Dict] = []
     if "fused" in variants:
@@ -45,6 +45,12 @@ def candidates(L: Layer, variants: Iterable[str] = ("fused", "chain", "split", "
     if "chain" in variants:
         for (th, tw), nw, mb1, pb in itertools.product(_tiles(L), (1, 2, 4, 8), (1, 2, 4), (1, 2)):
             out.append(dict(variant=B.VARIANT_CHAIN, tile_h=th, tile_w=tw, waves=(nw,) * 3, mb=(mb1, 1, 1), pb=(pb,) * 3))
+    if "fused_merged" in variants:
+        small = sorted({(min(th, L.Ho), min(tw, L.Wo)) for th in (1, 2, 3, 4) for tw in (4, 7, 8, 14, 16, 28, 32)
+                        if min(th, L.Ho) * min(tw, L.Wo) <= 64})
+        for (th, tw), nbg, mb1 in itertools.product(small, (1, 2, 4, 8), (1, 2, 4)):
+            for nw in range(nbg, 9, nbg):
+                out.append(dict(variant=B.VARIANT_FUSED_MERGED, tile_h=th, tile_w=tw, waves=(nw, 0, 0), mb=(mb1, nbg, 0)))
     for name, var, stages in (("split", B.VARIANT_SPLIT, 3), ("merged", B.VARIANT_MERGED, 2)):
         if name not in variants:
             continue
@@ -77,7 +83,7 @@ def _time(launch, iters: int) -> float:
     return a.elapsed_time(b) * 1e3 / iters
 
 
-def autotune(L: Layer, device: int = 0, iters: int = 200, variants=("fused", "chain", "split", "merged"),
+def autotune(L: Layer, device: int = 0, iters: int = 200, variants=("fused", "chain", "split", "merged", "fused_merged"),
              seed: int = 1, progress=None) -> Dict:
     """Times the selector's pick and every candidate.  Returns {"auto": row, "best": row, "by_variant":
     {name: best row}, "rows": all rows sorted by latency}; a row is {us, plan, tuning}."""
@@ -148,7 +154,7 @@ def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--config", type=int, nargs="*", default=[2])
     ap.add_argument("--iters", type=int, default=200)
-    ap.add_argument("--variants", nargs="*", default=["fused", "chain", "split", "merged"])
+    ap.add_argument("--variants", nargs="*", default=["fused", "chain", "split", "merged", "fused_merged"])
     ap.add_argument("--out", default=None, help="JSON with every timed tuning")
     args = ap.parse_args(argv)
     import torch

@@ -23,7 +23,8 @@ TDC_ERR_HIP = -6
 TDC_ERR_BAD_TUNING = -7
 
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN, VARIANT_DENSE, VARIANT_MERGED = 0, 1, 2, 3, 4, 5, 6
-VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense", 6: "merged"}
+VARIANT_FUSED_MERGED = 7
+VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense", 6: "merged", 7: "fused_merged"}
 
 # every symbol include/tdc.h declares
 EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", "tdc_conv_tucker2",

@@ -98,13 +98,20 @@ int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
     for (int i = 0; i < 3; ++i)
         if (t.waves[i] < 1 || t.waves[i] > 8) return TDC_ERR_BAD_TUNING;
     const bool dense = t.variant == TDC_VARIANT_DENSE;   // one kernel, tiled over the blocks of N
-    const bool merged = t.variant == TDC_VARIANT_MERGED; // stage 1, then a kernel tiled over the blocks of N
+    // MERGED, FUSED_MERGED: the second field tiles the blocks of N
+    const bool merged = t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_FUSED_MERGED;
     const int nb[3] = {dense ? p.dims.NB2 : p.dims.NB1, merged ? p.dims.NB3 : p.dims.NB2, dense ? p.dims.NB2 : p.dims.NB3};
     for (int i = 0; i < 3; ++i)
         if (t.mb[i] < 1 || nb[i] % t.mb[i]) return TDC_ERR_BAD_TUNING;   // whole register tiles only
     if (t.variant == TDC_VARIANT_DENSE) {
         if (!tdc_gemm_unit_supported(t.mb[1], t.pb[1])) return TDC_ERR_BAD_TUNING;
         if (t.waves[1] > 1 && (size_t)t.waves[1] * t.mb[1] * t.pb[1] * 1024 > 64 * 1024) return TDC_ERR_BAD_TUNING;
+        return TDC_OK;
+    }
+    if (t.variant == TDC_VARIANT_FUSED_MERGED) {
+        if (t.tile_h < 1 || t.tile_w < 1 || t.tile_h * t.tile_w > 64) return TDC_ERR_BAD_TUNING;
+        if (!tdc_fm_supported(p.dims, t.tile_h, t.tile_w, t.waves[0], t.mb[0], t.mb[1])) return TDC_ERR_BAD_TUNING;
+        if ((long)p.geom.lds_bytes > dev.lds_per_wg) return TDC_ERR_BAD_TUNING;
         return TDC_OK;
     }
     if (t.variant == TDC_VARIANT_MERGED) {
@@ -150,6 +157,11 @@ void describe(tdc_plan &p)
                  "fused tile=%dx%d in=%dx%d waves=%d units(mb1,mb2,mb3,pb)=(%d,%d,%d,%d) grid=%dx%d lds=%zuB%s model=%.1fus",
                  t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.mb[1], t.mb[2], t.pb[0],
                  p.geom.tiles_x * p.geom.tiles_y, p.dims.B, p.geom.lds_bytes, p.geom.weights_in_lds ? " wlds" : "", p.model_us);
+    else if (t.variant == TDC_VARIANT_FUSED_MERGED)
+        snprintf(p.desc, sizeof(p.desc),
+                 "fused-merged tile=%dx%d in=%dx%d waves=%d mb1=%d n-blocks/wg=%d k-slices=%d grid=%dx%d lds=%zuB model=%.1fus",
+                 t.tile_h, t.tile_w, p.geom.QH, p.geom.QW, t.waves[0], t.mb[0], t.mb[1], t.waves[0] / t.mb[1],
+                 p.geom.tiles_x * p.geom.tiles_y * (p.dims.NB3 / t.mb[1]), p.dims.B, p.geom.lds_bytes, p.model_us);
     else if (t.variant == TDC_VARIANT_MERGED)
         snprintf(p.desc, sizeof(p.desc), "merged stage(mb,pb,waves)= s1(%d,%d,%d) s23(%d,%d,%d) model=%.1fus", t.mb[0], t.pb[0],
                  t.waves[0], t.mb[1], t.pb[1], t.waves[1], p.model_us);
@@ -197,7 +209,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
     const int want = forced ? forced->variant : TDC_VARIANT_AUTO;
-    if (want < TDC_VARIANT_AUTO || want > TDC_VARIANT_MERGED) return TDC_ERR_BAD_TUNING;
+    if (want < TDC_VARIANT_AUTO || want > TDC_VARIANT_FUSED_MERGED) return TDC_ERR_BAD_TUNING;
     const tdc_shape kshape = kernel_shape(*shape, want);
     rc = validate(kshape);
     if (rc != TDC_OK) return rc;
@@ -225,6 +237,8 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
         p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_CHAIN)
         p->geom = tdc_chain_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
+    if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
+        p->geom = tdc_fm_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, p->tuning.waves[0], p->tuning.mb[1]);
     if (rc == TDC_OK) rc = check_tuning(*p, dev);
     if (rc != TDC_OK) {
         delete p;
@@ -236,14 +250,18 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     const size_t n_w1 = tdc_packed_floats_uin(d), n_w2 = tdc_packed_floats_core(d), n_w3 = tdc_packed_floats_uout(d);
     bool ok = true;
     const bool dense = p->tuning.variant == TDC_VARIANT_DENSE;
-    const bool merged = p->tuning.variant == TDC_VARIANT_MERGED;
+    const bool fm = p->tuning.variant == TDC_VARIANT_FUSED_MERGED;
+    const bool merged = p->tuning.variant == TDC_VARIANT_MERGED || fm;
     if (merged) {
         const size_t n_wm = (size_t)d.R1 * d.N * d.K * d.K, n_wmp = (size_t)d.NB3 * d.K * d.K * d.NB1 * 256;
-        ok = ok && hipMalloc((void **)&p->z1, n_z1 * sizeof(float)) == hipSuccess;
+        if (!fm) {
+            ok = ok && hipMalloc((void **)&p->z1, n_z1 * sizeof(float)) == hipSuccess;
+            p->ws_bytes += n_z1 * sizeof(float);
+        }
         ok = ok && hipMalloc((void **)&p->uin_p, n_w1 * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->wm, n_wm * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->core_p, n_wmp * sizeof(float)) == hipSuccess;
-        p->ws_bytes += (n_z1 + n_w1 + n_wm + n_wmp) * sizeof(float);
+        p->ws_bytes += (n_w1 + n_wm + n_wmp) * sizeof(float);
     }
     if (dense) {
         ok = ok && hipMalloc((void **)&p->core_p, n_w2 * sizeof(float)) == hipSuccess;
@@ -276,7 +294,7 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
     if (compute_units < 1 || lds_bytes < 1024) return TDC_ERR_BAD_TUNING;
-    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_MERGED) return TDC_ERR_BAD_TUNING;
+    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_FUSED_MERGED) return TDC_ERR_BAD_TUNING;
     const tdc_shape kshape = kernel_shape(*shape, inout->variant);
     rc = validate(kshape);
     if (rc != TDC_OK) return rc;
@@ -292,6 +310,8 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
         tmp.geom = tdc_fused_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_CHAIN)
         tmp.geom = tdc_chain_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
+    if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED_MERGED)
+        tmp.geom = tdc_fm_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, tmp.tuning.waves[0], tmp.tuning.mb[1]);
     if (rc == TDC_OK) rc = check_tuning(tmp, dev);
     if (rc == TDC_OK) *inout = tmp.tuning;
     return rc;
@@ -325,7 +345,8 @@ int tdc_plan_pack_weights(tdc_plan *p, void *hip_stream, const float *U_in, cons
     }
     DeviceGuard guard(p->device);
     if (!guard.ok) return TDC_ERR_HIP;
-    const hipError_t e = p->tuning.variant == TDC_VARIANT_MERGED
+    const bool merged_weights = p->tuning.variant == TDC_VARIANT_MERGED || p->tuning.variant == TDC_VARIANT_FUSED_MERGED;
+    const hipError_t e = merged_weights
                              ? tdc_launch_pack_merged(p->dims, (hipStream_t)hip_stream, U_in, core, U_out, p->uin_p, p->wm, p->core_p)
                              : tdc_launch_pack(p->dims, (hipStream_t)hip_stream, U_in, core, U_out, p->uin_p, p->core_p, p->uout_p);
     if (e != hipSuccess) return TDC_ERR_HIP;
@@ -351,12 +372,14 @@ int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float 
     const bool packed = p->packed_from[0] == U_in && p->packed_from[1] == core && p->packed_from[2] == U_out;
     if (!packed) {   // no stored copy for these pointers: re-lay out on the stream, remember nothing
         p->packed_from[0] = p->packed_from[1] = p->packed_from[2] = nullptr;
-        e = p->tuning.variant == TDC_VARIANT_MERGED
+        e = (p->tuning.variant == TDC_VARIANT_MERGED || p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
                 ? tdc_launch_pack_merged(d, s, U_in, core, U_out, p->uin_p, p->wm, p->core_p)
                 : tdc_launch_pack(d, s, U_in, core, U_out, p->uin_p, p->core_p, p->uout_p);
         if (e != hipSuccess) return TDC_ERR_HIP;
     }
-    if (p->tuning.variant == TDC_VARIANT_MERGED)
+    if (p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
+        e = tdc_launch_fm(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, y);
+    else if (p->tuning.variant == TDC_VARIANT_MERGED)
         e = tdc_launch_merged(d, p->tuning, s, x, p->uin_p, p->core_p, p->z1, y);
     else if (p->tuning.variant == TDC_VARIANT_SPLIT)
         e = tdc_launch_split(d, p->tuning, s, x, p->uin_p, p->core_p, p->uout_p, p->z1, p->z2, y);
@@ -415,7 +438,7 @@ int tdc_plan_kernel_count(const tdc_plan *p)
     if (!p) return 0;
     const int v = p->tuning.variant;
     if (v == TDC_VARIANT_MERGED) return 2;
-    return (v == TDC_VARIANT_FUSED || v == TDC_VARIANT_CHAIN || v == TDC_VARIANT_DENSE) ? 1 : 3;
+    return (v == TDC_VARIANT_FUSED || v == TDC_VARIANT_CHAIN || v == TDC_VARIANT_DENSE || v == TDC_VARIANT_FUSED_MERGED) ? 1 : 3;
 }
 
 int tdc_launch_null(void *hip_stream)

@@ -1,0 +1,256 @@
+// FUSED_MERGED variant: one launch for the whole layer in the latency regime (batch 1, small ranks).
+//
+// A workgroup owns one TH x TW tile of output pixels of one image AND one group of NBG 16-channel
+// blocks of the output.  It runs
+//   stage 1    z1 tile (all R1P channels x the input tile incl. halo) = U_in^T x  (Eq. 2), to LDS,
+//              exactly as the FUSED kernel does;
+//   stage 2+3  y(n-block, tile) = Wm (*) z1 with Wm = core x_2 U_out (Eqs. 3 and 4 folded into one
+//              K x K convolution R1 -> N when the weights were re-laid out), straight to HBM.
+// Workgroups that share a tile but own different output-channel groups each recompute stage 1:
+// at batch 1 most CUs are idle anyway, and the recomputation buys what the three-stage form cannot
+// give on a small image -- parallelism over output channels inside ONE launch, with a single
+// barrier between the stages.
+//
+// Every wavefront owns one output-channel block and one slice of the contraction range
+// (k = (tap, d1-block), KG2 = K*K*NB1 k-groups split KS ways; wave = ks*NBG + block), at most FR
+// k-groups.  Its FR weight fragments are fetched into registers as the kernel's very first
+// instructions, so they travel in the same memory round trip as the first stage-1 operands and
+// stage 2+3 touches only LDS (z1 cells) and registers.  Partial sums of the KS slices are added
+// through LDS in a fixed order.
+#include "tdc_internal.h"
+#include "tdc_mfma.h"
+
+namespace {
+
+constexpr int FM_FR = 9;     // weight fragments a wavefront may hold (k-groups of its slice)
+
+struct FmArgs {
+    const float *x, *uin_p, *wm_p;
+    float *y;
+    int C, N, H, W, Ho, Wo, K, stride, pad;
+    int NB1, NB3, KG1;
+    int TH, TW, QW, Q, P, QB;
+    int tiles_x, tiles;
+    int pitch1;             // LDS row pitch of the z1 tile, in 16-byte cells
+    int NBG, KS;            // output-channel blocks per workgroup, contraction slices
+};
+
+template <int MB1, int PBK>
+__global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
+{
+    extern __shared__ tdc_f4 lds4[];
+    tdc_f4 *__restrict__ z1s = lds4;                                   // [NB1][4][pitch1]
+    tdc_f4 *__restrict__ red = z1s + (size_t)4 * a.NB1 * a.pitch1;     // [wave][PBK][64]   (KS > 1)
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int g = lane >> 4, l16 = lane & 15;
+    const int tile = blockIdx.x % a.tiles, ng = blockIdx.x / a.tiles, b = blockIdx.y;
+    const int ty = tile / a.tiles_x, tx = tile - ty * a.tiles_x;
+    const int i0 = ty * a.TH, j0 = tx * a.TW;
+    const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;
+    const int HW = a.H * a.W;
+    const int KG2 = a.K * a.K * a.NB1;
+
+    // ---- this wavefront's slice of stage 2+3 and its weight fragments (in flight from here on)
+    const int nbi = wave % a.NBG, ks = wave / a.NBG;
+    const int nb = ng * a.NBG + nbi;
+    const int kg0 = (KG2 * ks) / a.KS, kg1 = (KG2 * (ks + 1)) / a.KS;
+    tdc_f4 wfrag[FM_FR];
+    {
+        const tdc_rsrc wrs = tdc_make_rsrc(a.wm_p + (size_t)nb * KG2 * 256, (unsigned)KG2 * 1024u);
+#pragma unroll
+        for (int f = 0; f < FM_FR; ++f)
+            wfrag[f] = tdc_buf_load4(wrs, ((unsigned)(kg0 + f) * 1024u + lane * 16u) | (kg0 + f < kg1 ? 0u : TDC_OOB));
+    }
+
+    // ------------------------------------------------------------------ stage 1 (Eq. 2)
+    {
+        constexpr int U = MB1 >= 4 ? 2 : 4;
+        const tdc_rsrc xrs = tdc_make_rsrc(a.x + (size_t)b * a.C * HW, (unsigned)a.C * HW * 4u);
+        const tdc_rsrc urs = tdc_make_rsrc(a.uin_p, (unsigned)a.NB1 * a.KG1 * 1024u);
+        const int n_mg = a.NB1 / MB1;
+        const int n_units = a.QB * n_mg;
+        int pg = 0, mg = 0, kg = 0;
+        unsigned xoff = 0;
+        const auto setup = [&](int u) {
+            pg = u % a.QB;
+            mg = u / a.QB;
+            kg = 0;
+            const int q = 16 * pg + l16;
+            const int qh = q / a.QW, qw = q - qh * a.QW;
+            const int h = h0 + qh, w = w0 + qw;
+            const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
+            xoff = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
+        };
+        auto next = [&](tdc_f4(&av)[MB1], tdc_f4(&bv)[1]) {
+            const unsigned dead = kg < a.KG1 ? 0u : TDC_OOB;
+#pragma unroll
+            for (int mb = 0; mb < MB1; ++mb)
+                av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
+            // channels past C lie beyond the descriptor and read as 0 by themselves
+            const unsigned o = ((unsigned)(16 * kg + 4 * g) * HW * 4u + xoff) | dead | (xoff & TDC_OOB);
+            bv[0] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
+                             tdc_buf_load(xrs, o + 12u * HW)};
+            ++kg;
+        };
+        TdcPipe<MB1, 1, U> pipe;
+        for (int u = wave; u < n_units; u += nw) {
+            setup(u);
+            pipe.start(next);
+            tdc_f4 acc[MB1][1];
+            pipe.run(acc, a.KG1, next);
+#pragma unroll
+            for (int mb = 0; mb < MB1; ++mb) z1s[((mg * MB1 + mb) * 4 + g) * a.pitch1 + 16 * pg + l16] = acc[mb][0];
+        }
+    }
+    __syncthreads();
+
+    // ------------------------------------------------------------------ stages 2+3 (Eqs. 3, 4 folded)
+    tdc_f4 acc[PBK];
+    int qbase[PBK];
+#pragma unroll
+    for (int pb = 0; pb < PBK; ++pb) {
+        acc[pb] = tdc_f4_zero();
+        const int p = 16 * pb + l16;
+        const int ph = p / a.TW, pw = p - ph * a.TW;
+        qbase[pb] = g * a.pitch1 + (p < a.P ? ph * a.stride * a.QW + pw * a.stride : 0);
+    }
+    {
+        // position of k-group kg0 within (tap, d1-block); all of it wave-uniform
+        const int tap0 = kg0 / a.NB1;
+        int dg = kg0 - tap0 * a.NB1;
+        const int r0 = tap0 / a.K;
+        int s = tap0 - r0 * a.K;
+        int toff = r0 * a.QW + s;
+#pragma unroll
+        for (int f = 0; f < FM_FR; ++f) {
+            if (kg0 + f < kg1) {
+                const int cell = dg * 4 * a.pitch1 + toff;
+#pragma unroll
+                for (int pb = 0; pb < PBK; ++pb) {
+                    const tdc_f4 bv = z1s[cell + qbase[pb]];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[pb] = tdc_mfma(wfrag[f][j], bv[j], acc[pb]);
+                }
+                if (++dg == a.NB1) {
+                    dg = 0;
+                    ++toff;
+                    if (++s == a.K) {
+                        s = 0;
+                        toff += a.QW - a.K;
+                    }
+                }
+            }
+        }
+    }
+
+    const int P2 = a.Ho * a.Wo;
+    float *__restrict__ yb = a.y + (size_t)b * a.N * P2;
+    if (a.KS == 1) {
+#pragma unroll
+        for (int pb = 0; pb < PBK; ++pb) {
+            const int p = 16 * pb + l16;
+            const int ph = p / a.TW, pw = p - ph * a.TW;
+            const int i = i0 + ph, j = j0 + pw;
+            if (p < a.P && i < a.Ho && j < a.Wo) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int n = 16 * nb + 4 * g + c;
+                    if (n < a.N) yb[(size_t)n * P2 + i * a.Wo + j] = acc[pb][c];
+                }
+            }
+        }
+        return;
+    }
+    // partial sums of the KS slices, [wave = ks*NBG + block][pb][lane], then a fixed-order sum
+#pragma unroll
+    for (int pb = 0; pb < PBK; ++pb) red[(wave * PBK + pb) * 64 + lane] = acc[pb];
+    __syncthreads();
+    for (int e = threadIdx.x; e < a.NBG * PBK * 64; e += blockDim.x) {
+        const int ln = e & 63, pb = (e >> 6) % PBK, blk = (e >> 6) / PBK;
+        tdc_f4 sum = red[(blk * PBK + pb) * 64 + ln];
+        for (int k = 1; k < a.KS; ++k) {
+            const tdc_f4 v = red[((k * a.NBG + blk) * PBK + pb) * 64 + ln];
+            sum += v;
+        }
+        const int p = 16 * pb + (ln & 15);
+        const int ph = p / a.TW, pw = p - ph * a.TW;
+        const int i = i0 + ph, j = j0 + pw;
+        if (p < a.P && i < a.Ho && j < a.Wo) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int n = 16 * (ng * a.NBG + blk) + 4 * (ln >> 4) + c;
+                if (n < a.N) yb[(size_t)n * P2 + i * a.Wo + j] = sum[c];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+// nbg = output-channel blocks per workgroup; the workgroup has nw = nbg * KS wavefronts
+bool tdc_fm_supported(const TdcDims &d, int tile_h, int tile_w, int nw, int mb1, int nbg)
+{
+    if (mb1 != 1 && mb1 != 2 && mb1 != 4) return false;
+    if (d.NB1 % mb1 || nbg < 1 || d.NB3 % nbg || nw < 1 || nw > 8 || nw % nbg) return false;
+    const int pbk = (tile_h * tile_w + 15) / 16;
+    if (pbk < 1 || pbk > 4) return false;
+    const int ks = nw / nbg, kg2 = d.K * d.K * d.NB1;
+    if (ks > kg2) return false;
+    // the longest slice: ceil over the uneven split used by the kernel
+    int longest = 0;
+    for (int k = 0; k < ks; ++k) longest = longest > (kg2 * (k + 1)) / ks - (kg2 * k) / ks ? longest : (kg2 * (k + 1)) / ks - (kg2 * k) / ks;
+    return longest <= FM_FR;
+}
+
+TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int nbg)
+{
+    TdcFusedGeom g;
+    g.TH = tile_h;
+    g.TW = tile_w;
+    g.QH = (tile_h - 1) * d.stride + d.K;
+    g.QW = (tile_w - 1) * d.stride + d.K;
+    g.Q = g.QH * g.QW;
+    g.QB = (g.Q + 15) / 16;
+    g.PBk = (tile_h * tile_w + 15) / 16;
+    g.tiles_x = (d.Wo + tile_w - 1) / tile_w;
+    g.tiles_y = (d.Ho + tile_h - 1) / tile_h;
+    g.pitch1 = 16 * g.QB + 4;
+    g.pitch2 = 0;
+    g.weights_in_lds = false;
+    const int ks = nbg > 0 ? nw / nbg : 1;
+    g.lds_bytes = (size_t)16 * d.NB1 * g.pitch1 * sizeof(float) + (ks > 1 ? (size_t)nw * g.PBk * 1024 : 0);
+    return g;
+}
+
+hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s, const float *x,
+                         const float *uin_p, const float *wm_p, float *y)
+{
+    FmArgs a;
+    a.x = x; a.uin_p = uin_p; a.wm_p = wm_p; a.y = y;
+    a.C = d.C; a.N = d.N; a.H = d.H; a.W = d.W; a.Ho = d.Ho; a.Wo = d.Wo;
+    a.K = d.K; a.stride = d.stride; a.pad = d.pad;
+    a.NB1 = d.NB1; a.NB3 = d.NB3; a.KG1 = d.KG1;
+    a.TH = g.TH; a.TW = g.TW; a.QW = g.QW; a.Q = g.Q; a.P = g.TH * g.TW; a.QB = g.QB;
+    a.tiles_x = g.tiles_x; a.tiles = g.tiles_x * g.tiles_y;
+    a.pitch1 = g.pitch1;
+    a.NBG = t.mb[1]; a.KS = t.waves[0] / t.mb[1];
+    dim3 grid((unsigned)(a.tiles * (d.NB3 / a.NBG)), (unsigned)d.B), block(64 * t.waves[0]);
+#define TDC_FM_CASE(M_, P_)                                                                        \
+    if (t.mb[0] == M_ && g.PBk == P_) {                                                            \
+        if (g.lds_bytes > 48 * 1024) {                                                             \
+            hipError_t e = hipFuncSetAttribute((const void *)tdc_fm_kernel<M_, P_>,                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,         \
+                                               (int)g.lds_bytes);                                  \
+            if (e != hipSuccess) return e;                                                         \
+        }                                                                                          \
+        hipLaunchKernelGGL((tdc_fm_kernel<M_, P_>), grid, block, g.lds_bytes, s, a);               \
+        return hipGetLastError();                                                                  \
+    }
+    TDC_FM_CASE(1, 1) TDC_FM_CASE(1, 2) TDC_FM_CASE(1, 3) TDC_FM_CASE(1, 4)
+    TDC_FM_CASE(2, 1) TDC_FM_CASE(2, 2) TDC_FM_CASE(2, 3) TDC_FM_CASE(2, 4)
+    TDC_FM_CASE(4, 1) TDC_FM_CASE(4, 2) TDC_FM_CASE(4, 3) TDC_FM_CASE(4, 4)
+#undef TDC_FM_CASE
+    return hipErrorInvalidValue;
+}

@@ -81,6 +81,14 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
                             const float *x, const float *uin_p, const float *core_p,
                             const float *uout_p, float *y);
 
+// ---- one-launch kernel: stage 1 into LDS, then the merged stage-2/3 convolution (tdc_fm.hip).
+// Tuning fields: tile_h, tile_w, waves[0], mb[0] = stage-1 register tile, mb[1] = output-channel
+// blocks per workgroup (the wavefronts split the contraction waves[0] / mb[1] ways).
+bool tdc_fm_supported(const TdcDims &d, int tile_h, int tile_w, int nw, int mb1, int nbg);
+TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int nbg);
+hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s, const float *x,
+                         const float *uin_p, const float *wm_p, float *y);
+
 // ---- selector (tdc_select.cpp): fills every zero field of `t`
 struct TdcDeviceInfo {
     int cus;             // compute units

@@ -186,6 +186,81 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
     return best;
 }
 
+// FUSED_MERGED: stage 1 as in FUSED (dealt over nw wavefronts), then every wavefront runs its
+// slice of the merged convolution out of registers and LDS.  Fitted to ~2700 tunings of the
+// batch-1, stride-1 layers (median relative error 8%; the picked tuning within 4% of the best
+// wherever this variant is competitive): 0.76 us per stage-1 unit (a memory round trip) plus
+// 0.16 us per k-group and its MFMAs, 0.11 us per weight fragment and pixel block of the tail, a
+// cross-slice sum, the bytes of x a CU pulls (input tile with halo, once per workgroup), and a
+// dispatch term per 256 workgroups -- the recomputation of stage 1 by every output-channel
+// group shows up there and in the x bytes.
+struct FmCoef {
+    double launch = 0.2465;
+    double s1_unit = 0.7627, s1_kg = 0.1599, s1_mfma = 0.0364;
+    double frag = 0.1123;         // per weight fragment and pixel block, times the MFMA pipe share
+    double reduce = 0.2451;       // per pixel block when the contraction is sliced
+    double x_mb = 20.8968;        // per MB of x per CU
+    double wgs = 1.6149;          // per 256 workgroups
+};
+
+struct FmChoice {
+    double us = 1e300;
+    int th = 0, tw = 0, nw = 0, mb1 = 0, nbg = 0;
+};
+
+double fm_us(const FmCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw, int mb1, int nbg)
+{
+    const int KG2 = d.K * d.K * d.NB1, ks = nw / nbg;
+    const long wgs = (long)g.tiles_x * g.tiles_y * (d.NB3 / nbg) * d.B;
+    const int resident = std::max(1, std::min({(int)(dev.lds_per_wg / std::max<size_t>(g.lds_bytes, 1)), kWavesPerCu / nw, 8}));
+    const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
+    const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
+    const double share = std::max(1.0, per_cu * nw / 4.0);
+    const int r1 = cdiv(g.QB * (d.NB1 / mb1), nw);
+    const int frags = cdiv(KG2, ks);
+    double t = r1 * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * mb1 * share));
+    t += g.PBk * frags * c.frag * share + (ks > 1 ? c.reduce * g.PBk : 0.0);
+    t += per_cu * c.x_mb * g.QB * 16.0 * d.C * 4e-6;
+    return c.launch + rounds * t + c.wgs * wgs / 256.0;
+}
+
+FmChoice best_fm(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &forced)
+{
+    const FmCoef c;
+    FmChoice best;
+    const int ks_min = cdiv(d.K * d.K * d.NB1, 9);   // a wavefront holds nine weight fragments
+    const int th_lo = forced.tile_h ? forced.tile_h : 1, th_hi = forced.tile_h ? forced.tile_h : std::min(d.Ho, 8);
+    const int tw_lo = forced.tile_w ? forced.tile_w : 1, tw_hi = forced.tile_w ? forced.tile_w : std::min(d.Wo, 32);
+    // pass 0: the calibrated region only; pass 1 (shapes that have no tuning there): anything launchable
+    for (int pass = 0; pass < 2 && best.us >= 1e299; ++pass)
+    for (int th = th_lo; th <= th_hi; ++th)
+        for (int tw = tw_lo; tw <= tw_hi; ++tw) {
+            if (th * tw > 64) continue;
+            if (!forced.tile_w && tw < std::min(d.Wo, 4)) continue;
+            for (int nbg = 1; nbg <= 8; ++nbg)
+                for (int nw = nbg; nw <= 8; nw += nbg)
+                    for (int mb1 : kMb) {
+                        if (forced.waves[0] && nw != forced.waves[0]) continue;
+                        if (forced.mb[0] && mb1 != forced.mb[0]) continue;
+                        if (forced.mb[1] && nbg != forced.mb[1]) continue;
+                        if (!tdc_fm_supported(d, th, tw, nw, mb1, nbg)) continue;
+                        // the calibrated region: 4 or 8 wavefronts, as few contraction slices as the
+                        // register budget allows, or twice that
+                        const int ks = nw / nbg;
+                        if (pass == 0 && !forced.waves[0] && nw != 4 && nw != 8) continue;
+                        if (pass == 0 && !forced.waves[0] && !forced.mb[1] && ks != ks_min && ks != 2 * ks_min) continue;
+                        const TdcFusedGeom g = tdc_fm_geometry(d, th, tw, nw, nbg);
+                        if ((long)g.lds_bytes > dev.lds_per_wg) continue;
+                        const double us = fm_us(c, d, dev, g, nw, mb1, nbg);
+                        if (us < best.us) {
+                            best.us = us;
+                            best.th = th; best.tw = tw; best.nw = nw; best.mb1 = mb1; best.nbg = nbg;
+                        }
+                    }
+        }
+    return best;
+}
+
 struct StageChoice {
     double us = 1e300;
     int mb = 1, pb = 1, nw = 1;
@@ -245,6 +320,16 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
         if (model_us) *model_us = c.us;
         return TDC_OK;
     }
+    if (forced.variant == TDC_VARIANT_FUSED_MERGED) {
+        const FmChoice c = best_fm(d, dev, forced);
+        if (c.us >= 1e299) return TDC_ERR_BAD_TUNING;
+        t->tile_h = c.th; t->tile_w = c.tw;
+        t->waves[0] = t->waves[1] = t->waves[2] = c.nw;
+        t->mb[0] = c.mb1; t->mb[1] = c.nbg; t->mb[2] = 1;
+        t->pb[0] = t->pb[1] = t->pb[2] = 1;
+        if (model_us) *model_us = c.us;
+        return TDC_OK;
+    }
     if (forced.variant == TDC_VARIANT_MERGED) {
         const StageChoice a = best_stage(dev, d.B, d.NB1, cdiv(d.H * d.W, 16), d.KG1, forced.mb[0], forced.pb[0], forced.waves[0], 0);
         const StageChoice b = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1], forced.pb[1],
@@ -295,8 +380,27 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
         split_us = s[0].us + s[1].us + s[2].us;
     }
 
-    // MERGED (stage 1, then stages 2+3 as one convolution R1 -> N) against the others: only below
-    // the throughput regime, where its extra MACs cost nothing and its saved launch counts.
+    // The merged forms (stage 3 folded into the core) against the others: only below the throughput
+    // regime, where their extra MACs cost nothing and the saved launches count.  The one-launch
+    // form's estimate is optimistic once the contraction is cut into three or more slices, so it
+    // has to win by a margin.
+    if (forced.variant == TDC_VARIANT_AUTO && !pixels_fill_chip && d.stride == 1) {   // calibrated at stride 1 only
+        const StageChoice m2 = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1], forced.pb[1],
+                                          forced.waves[1], d.stride);
+        tdc_tuning free_choice = forced;
+        free_choice.mb[0] = free_choice.mb[1] = free_choice.mb[2] = 0;
+        free_choice.waves[0] = 0;
+        const FmChoice fm = best_fm(d, dev, free_choice);
+        if (fm.us * 1.1 < f.us && fm.us * 1.1 < split_us && fm.us * 1.1 < s[0].us + m2.us) {
+            t->variant = TDC_VARIANT_FUSED_MERGED;
+            t->tile_h = fm.th; t->tile_w = fm.tw;
+            t->waves[0] = t->waves[1] = t->waves[2] = fm.nw;
+            t->mb[0] = fm.mb1; t->mb[1] = fm.nbg; t->mb[2] = 1;
+            t->pb[0] = t->pb[1] = t->pb[2] = 1;
+            if (model_us) *model_us = fm.us;
+            return TDC_OK;
+        }
+    }
     if (forced.variant == TDC_VARIANT_AUTO && !pixels_fill_chip) {
         const StageChoice m = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1], forced.pb[1],
                                          forced.waves[1], d.stride);

@@ -92,9 +92,9 @@ def test_selector_fills_a_launchable_tuning_for_every_workload():
         for L in config_layers(cfg):
             t = B.tdc_select_tuning(B.make_shape(**L.asdict()))
             d = t.as_dict()
-            assert d["variant"] in ("split", "fused", "chain", "merged"), d
-            assert all(1 <= w <= 8 for w in d["waves"]) and all(m in (1, 2, 4) for m in d["mb"])
-            if d["variant"] in ("fused", "chain"):
+            assert d["variant"] in ("split", "fused", "chain", "merged", "fused_merged"), d
+            assert all(1 <= w <= 8 for w in d["waves"]) and all(1 <= m <= 8 for m in d["mb"])
+            if d["variant"] in ("fused", "chain", "fused_merged"):
                 assert 1 <= d["tile_h"] <= L.Ho and 1 <= d["tile_w"] <= L.Wo
 
 

@@ -14,7 +14,7 @@ from parity_util import assert_parity, run_gpu
 pytestmark = pytest.mark.gpu
 
 VARIANTS = {"naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT, "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN,
-            "merged": B.VARIANT_MERGED, "auto": B.VARIANT_AUTO}
+            "merged": B.VARIANT_MERGED, "fused_merged": B.VARIANT_FUSED_MERGED, "auto": B.VARIANT_AUTO}
 
 
 def _announce(*parts):
@@ -113,6 +113,36 @@ def test_forced_merged_tunings(orc, tuning, layer):
     assert_parity(got, want, "%s [%s]" % (layer.name(), desc))
 
 
+FM_FORCED = [
+    (Layer(1, 64, 64, 56, 56, 16, 16), dict(tile_h=1, tile_w=14, waves=(4, 0, 0), mb=(1, 4, 0))),          # no k-split
+    (Layer(1, 128, 128, 28, 28, 32, 32), dict(tile_h=1, tile_w=14, waves=(8, 0, 0), mb=(2, 4, 0))),        # 2 slices
+    (Layer(1, 256, 256, 14, 14, 64, 64), dict(tile_h=2, tile_w=14, waves=(8, 0, 0), mb=(1, 2, 0))),        # 4 slices, 2 pixel blocks
+    (Layer(1, 256, 256, 14, 14, 64, 64), dict(tile_h=4, tile_w=14, waves=(4, 0, 0), mb=(4, 1, 0))),        # 4 pixel blocks, ragged tile rows
+    (Layer(2, 33, 72, 12, 40, 32, 57, 3, 2, 1), dict(tile_h=4, tile_w=16, waves=(4, 0, 0), mb=(1, 1, 0))), # stride 2, N not a multiple of 16
+    (Layer(2, 33, 80, 12, 40, 16, 57, 3, 2, 1), dict(tile_h=3, tile_w=10, waves=(5, 0, 0), mb=(1, 5, 0))), # five blocks per workgroup
+    (Layer(1, 8, 8, 11, 13, 5, 3, 5, 1, 2), dict(tile_h=4, tile_w=13, waves=(4, 0, 0), mb=(1, 1, 0))),     # 5x5 taps
+    (Layer(3, 20, 24, 19, 23, 17, 33), dict(tile_h=3, tile_w=7, waves=(6, 0, 0), mb=(1, 2, 0))),           # uneven slices (18 k-groups / 3)
+]
+
+
+@pytest.mark.parametrize("layer,tuning", FM_FORCED, ids=["%s_%dx%d_w%d_mb%d_nbg%d" % (
+    l.name(), t["tile_h"], t["tile_w"], t["waves"][0], t["mb"][0], t["mb"][1]) for l, t in FM_FORCED])
+def test_forced_fused_merged_tunings(orc, layer, tuning):
+    """The one-launch kernel with contraction slices, several pixel blocks and channel-block groups."""
+    _announce("forced fused_merged", tuning, layer.name())
+    inputs = make_inputs(layer, 79)
+    want = _oracle(orc, layer, inputs)
+    got, desc = run_gpu(layer, inputs, B.make_tuning(variant=B.VARIANT_FUSED_MERGED, **tuning))
+    assert_parity(got, want, "%s [%s]" % (layer.name(), desc))
+
+
+def test_fused_merged_refuses_what_it_cannot_hold():
+    """Ranks whose contraction slices exceed the fragments a wavefront keeps in registers are refused."""
+    with pytest.raises(B.TdcError) as err:
+        B.tdc_plan_create(B.make_shape(1, 512, 512, 7, 7, 152, 152), 0, B.make_tuning(variant=B.VARIANT_FUSED_MERGED))
+    assert err.value.status == B.TDC_ERR_BAD_TUNING
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_full_size_workloads(orc, cfg):
     """Every layer of the five synthetic workloads at full size, in the launch configuration the
@@ -129,7 +159,7 @@ def test_full_size_workloads(orc, cfg):
     print("[config %d] worst E_inf=%.2e E_el=%.2e" % ((cfg,) + worst), flush=True)
 
 
-@pytest.mark.parametrize("variant", ["split", "fused", "chain", "merged"])
+@pytest.mark.parametrize("variant", ["split", "fused", "chain", "merged", "fused_merged"])
 def test_dense_path_agrees_too(orc, variant):
     """The GPU result also matches the dense convolution with the kernel of Eq. 1."""
     layer = Layer(1, 24, 20, 14, 14, 12, 9)
@@ -140,7 +170,7 @@ def test_dense_path_agrees_too(orc, variant):
     assert_parity(got, want, desc)
 
 
-@pytest.mark.parametrize("variant", ["naive", "split", "fused", "chain", "merged"])
+@pytest.mark.parametrize("variant", ["naive", "split", "fused", "chain", "merged", "fused_merged"])
 def test_unpacked_weights_path(orc, variant):
     """Without tdc_plan_pack_weights the library re-lays the weights out on every call."""
     layer = Layer(2, 20, 24, 19, 23, 17, 33)
