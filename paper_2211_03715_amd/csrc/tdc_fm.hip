@@ -33,6 +33,8 @@ struct FmArgs {
     int tiles_x, tiles;
     int pitch1;             // LDS row pitch of the z1 tile, in 16-byte cells
     int NBG, KS;            // output-channel blocks per workgroup, contraction slices
+    int kg_q, kg_r;         // KG2 = KS * kg_q + kg_r: the first kg_r slices take kg_q + 1 k-groups
+    TdcDiv div_tiles, div_tiles_x, div_NBG, div_QB, div_QW, div_TW, div_NB1, div_K;   // constant divisors
 };
 
 template <int MB1, int PBK>
@@ -45,17 +47,17 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int g = lane >> 4, l16 = lane & 15;
-    const int tile = blockIdx.x % a.tiles, ng = blockIdx.x / a.tiles, b = blockIdx.y;
-    const int ty = tile / a.tiles_x, tx = tile - ty * a.tiles_x;
+    const int ng = tdc_div(blockIdx.x, a.div_tiles), tile = blockIdx.x - ng * a.tiles, b = blockIdx.y;
+    const int ty = tdc_div(tile, a.div_tiles_x), tx = tile - ty * a.tiles_x;
     const int i0 = ty * a.TH, j0 = tx * a.TW;
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;
     const int HW = a.H * a.W;
     const int KG2 = a.K * a.K * a.NB1;
 
     // ---- this wavefront's slice of stage 2+3 and its weight fragments (in flight from here on)
-    const int nbi = wave % a.NBG, ks = wave / a.NBG;
+    const int ks = tdc_div(wave, a.div_NBG), nbi = wave - ks * a.NBG;
     const int nb = ng * a.NBG + nbi;
-    const int kg0 = (KG2 * ks) / a.KS, kg1 = (KG2 * (ks + 1)) / a.KS;
+    const int kg0 = ks * a.kg_q + min(ks, a.kg_r), kg1 = kg0 + a.kg_q + (ks < a.kg_r ? 1 : 0);
     tdc_f4 wfrag[FM_FR];
     {
         const tdc_rsrc wrs = tdc_make_rsrc(a.wm_p + (size_t)nb * KG2 * 256, (unsigned)KG2 * 1024u);
@@ -74,11 +76,11 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
         int pg = 0, mg = 0, kg = 0;
         unsigned xoff = 0;
         const auto setup = [&](int u) {
-            pg = u % a.QB;
-            mg = u / a.QB;
+            mg = tdc_div(u, a.div_QB);
+            pg = u - mg * a.QB;
             kg = 0;
             const int q = 16 * pg + l16;
-            const int qh = q / a.QW, qw = q - qh * a.QW;
+            const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
             const int h = h0 + qh, w = w0 + qw;
             const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
             xoff = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
@@ -113,14 +115,14 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
     for (int pb = 0; pb < PBK; ++pb) {
         acc[pb] = tdc_f4_zero();
         const int p = 16 * pb + l16;
-        const int ph = p / a.TW, pw = p - ph * a.TW;
+        const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
         qbase[pb] = g * a.pitch1 + (p < a.P ? ph * a.stride * a.QW + pw * a.stride : 0);
     }
     {
         // position of k-group kg0 within (tap, d1-block); all of it wave-uniform
-        const int tap0 = kg0 / a.NB1;
+        const int tap0 = tdc_div(kg0, a.div_NB1);
         int dg = kg0 - tap0 * a.NB1;
-        const int r0 = tap0 / a.K;
+        const int r0 = tdc_div(tap0, a.div_K);
         int s = tap0 - r0 * a.K;
         int toff = r0 * a.QW + s;
 #pragma unroll
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
 #pragma unroll
         for (int pb = 0; pb < PBK; ++pb) {
             const int p = 16 * pb + l16;
-            const int ph = p / a.TW, pw = p - ph * a.TW;
+            const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
             const int i = i0 + ph, j = j0 + pw;
             if (p < a.P && i < a.Ho && j < a.Wo) {
 #pragma unroll
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
             sum += v;
         }
         const int p = 16 * pb + (ln & 15);
-        const int ph = p / a.TW, pw = p - ph * a.TW;
+        const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
         const int i = i0 + ph, j = j0 + pw;
         if (p < a.P && i < a.Ho && j < a.Wo) {
 #pragma unroll
@@ -198,10 +200,7 @@ bool tdc_fm_supported(const TdcDims &d, int tile_h, int tile_w, int nw, int mb1,
     if (pbk < 1 || pbk > 4) return false;
     const int ks = nw / nbg, kg2 = d.K * d.K * d.NB1;
     if (ks > kg2) return false;
-    // the longest slice: ceil over the uneven split used by the kernel
-    int longest = 0;
-    for (int k = 0; k < ks; ++k) longest = longest > (kg2 * (k + 1)) / ks - (kg2 * k) / ks ? longest : (kg2 * (k + 1)) / ks - (kg2 * k) / ks;
-    return longest <= FM_FR;
+    return (kg2 + ks - 1) / ks <= FM_FR;   // the longest slice must fit the fragment registers
 }
 
 TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int nbg)
@@ -236,6 +235,12 @@ hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGe
     a.tiles_x = g.tiles_x; a.tiles = g.tiles_x * g.tiles_y;
     a.pitch1 = g.pitch1;
     a.NBG = t.mb[1]; a.KS = t.waves[0] / t.mb[1];
+    const int kg2 = d.K * d.K * d.NB1;
+    a.kg_q = kg2 / a.KS; a.kg_r = kg2 % a.KS;
+    a.div_tiles = tdc_make_div((unsigned)a.tiles); a.div_tiles_x = tdc_make_div((unsigned)a.tiles_x);
+    a.div_NBG = tdc_make_div((unsigned)a.NBG); a.div_QB = tdc_make_div((unsigned)a.QB);
+    a.div_QW = tdc_make_div((unsigned)a.QW); a.div_TW = tdc_make_div((unsigned)a.TW);
+    a.div_NB1 = tdc_make_div((unsigned)a.NB1); a.div_K = tdc_make_div((unsigned)a.K);
     dim3 grid((unsigned)(a.tiles * (d.NB3 / a.NBG)), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_FM_CASE(M_, P_)                                                                        \
     if (t.mb[0] == M_ && g.PBk == P_) {                                                            \

@@ -36,9 +36,24 @@ struct GemmArgs {
     int NBm;             // 16-blocks of output channels (a multiple of MB)
     int KG;              // 16-wide k-groups of the contraction
     int NBk;             // stage 2: k-groups per tap (= NB1)
-    int n_pgroups;
+    int n_pgroups, n_mgroups;
+    int pg_major;        // order of the logical workgroup ids, see tdc_logical_block
     int H, W, Wo, K, stride, pad;   // stage 2 geometry
+    int kg_q, kg_r;      // KG = waves * kg_q + kg_r: the first kg_r wavefronts take kg_q + 1 k-groups
+    TdcDiv div_inner, div_Wo, div_NBk, div_K;   // launch-time constant divisors (see tdc_mfma.h)
 };
+
+// Workgroups are dealt to the chip's 8 XCDs round-robin by blockIdx.x, and every XCD has its own
+// L2.  Remap so that each XCD gets one contiguous range of logical ids: neighbours in the logical
+// order -- workgroups that share a weight block (channel-group-major order) or an activation
+// block (pixel-group-major order) -- then fetch that operand into one L2 instead of eight.
+__device__ __forceinline__ int tdc_logical_block(int bid, int n)
+{
+    constexpr int XCDS = 8;
+    const int per = n / XCDS, rem = n % XCDS;
+    const int xcd = bid % XCDS, slot = bid / XCDS;
+    return xcd * per + min(xcd, rem) + slot;
+}
 
 // Stateful operand fetcher of one wavefront: each call returns the next k-group of its range.
 template <int MODE, int MB, int PB>
@@ -99,7 +114,11 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int g = lane >> 4, l16 = lane & 15;
-    const int pg = blockIdx.x % a.n_pgroups, mg = blockIdx.x / a.n_pgroups, b = blockIdx.y;
+    const int lb = tdc_logical_block(blockIdx.x, gridDim.x);
+    const int inner = a.pg_major ? a.n_mgroups : a.n_pgroups;   // one division on the way to the first load
+    const int hi = tdc_div(lb, a.div_inner), lo = lb - hi * inner;
+    const int pg = a.pg_major ? hi : lo, mg = a.pg_major ? lo : hi;
+    const int b = blockIdx.y;
 
     GemmNext<MODE, MB, PB> next;
     next.wstride = (unsigned)a.KG * 1024u;
@@ -113,7 +132,7 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
         const int p = 16 * (pg * PB + pb) + l16;
         next.pval[pb] = p < a.out_pix;
         if (MODE == 2) {
-            const int i = p / a.Wo, j = p - i * a.Wo;
+            const int i = tdc_div(p, a.div_Wo), j = p - i * a.Wo;
             next.ih0[pb] = i * a.stride - a.pad;
             next.iw0[pb] = j * a.stride - a.pad;
             next.poff[pb] = next.ih0[pb] * a.W + next.iw0[pb];
@@ -122,13 +141,13 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
             next.poff[pb] = p;
         }
     }
-    const int kg0 = (int)(((long)a.KG * wave) / nw);
+    const int kg0 = wave * a.kg_q + min(wave, a.kg_r);
     next.kg = kg0;
-    next.kg_end = (int)(((long)a.KG * (wave + 1)) / nw);
+    next.kg_end = kg0 + a.kg_q + (wave < a.kg_r ? 1 : 0);
     {
-        const int tap = kg0 / a.NBk;
+        const int tap = tdc_div(kg0, a.div_NBk);
         next.dg = kg0 - tap * a.NBk;
-        next.r = tap / a.K;
+        next.r = tdc_div(tap, a.div_K);
         next.s = tap - next.r * a.K;
     }
 
@@ -193,13 +212,23 @@ int pick_u(int kg_per_wave, int umax)
 }
 
 template <int MODE>
-hipError_t launch_stage(const GemmArgs &a, int mb, int pb, int waves, int batch, hipStream_t s)
+hipError_t launch_stage(const GemmArgs &a_in, int mb, int pb, int waves, int batch, hipStream_t s)
 {
+    GemmArgs a = a_in;
     const int n_mgroups = a.NBm / mb;
+    a.n_mgroups = n_mgroups;
+    // keep the larger operand's re-use inside one XCD: weights when they outweigh the activations
+    a.pg_major = (double)a.NBm * a.KG * 1024.0 < (double)a.act_rows_valid * a.act_pix * 4.0;
+    a.kg_q = a.KG / waves;
+    a.kg_r = a.KG % waves;
+    a.div_inner = tdc_make_div((unsigned)(a.pg_major ? n_mgroups : a.n_pgroups));
+    a.div_Wo = tdc_make_div((unsigned)a.Wo);
+    a.div_NBk = tdc_make_div((unsigned)a.NBk);
+    a.div_K = tdc_make_div((unsigned)a.K);
     dim3 grid((unsigned)(n_mgroups * a.n_pgroups), (unsigned)batch), block(64 * waves);
     const size_t lds = waves > 1 ? (size_t)waves * mb * pb * 256 * sizeof(float) : 0;
     const int kg_per_wave = (a.KG + waves - 1) / waves;
-    const int umax = mb * pb <= 2 ? 4 : (mb * pb == 4 ? 4 : 2);
+    const int umax = mb * pb <= 4 ? 4 : 2;
     int u = pick_u(kg_per_wave, umax);
     if (mb * pb == 4 && u != 4) u = 2;          // compiled sizes: {2,4} for four blocks, {2} beyond
     if (mb * pb > 4) u = 2;

@@ -52,6 +52,33 @@ __device__ __forceinline__ tdc_f4 tdc_buf_load4(tdc_rsrc r, unsigned byte_off)
     return __builtin_bit_cast(tdc_f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
 }
 
+// Division by a launch-time constant.  An integer division costs a lone wavefront some 300 cycles
+// (a dependent chain of ~25 VALU instructions), and a kernel prologue here has half a dozen of
+// them between its first instruction and its first load: at microsecond kernel durations that is
+// measurable (0.15 us each).  The host precomputes a multiplier instead (Granlund & Montgomery):
+//   m = floor(2^32 * (2^L - d) / d) + 1,  L = ceil(log2 d),  q = (t + ((x - t) >> min(L,1))) >> max(L-1,0),
+//   t = mulhi(m, x); exact for every 0 <= x < 2^32 and 1 <= d < 2^31.
+struct TdcDiv {
+    unsigned m, sh1, sh2;
+};
+
+inline TdcDiv tdc_make_div(unsigned d)
+{
+    unsigned L = 0;
+    while ((1ull << L) < d) ++L;
+    TdcDiv r;
+    r.m = (unsigned)((((1ull << 32) * ((1ull << L) - d)) / d) + 1);
+    r.sh1 = L < 1 ? L : 1;
+    r.sh2 = L > 1 ? L - 1 : 0;
+    return r;
+}
+
+__device__ __forceinline__ int tdc_div(int x, const TdcDiv &d)
+{
+    const unsigned t = __umulhi(d.m, (unsigned)x);
+    return (int)((t + (((unsigned)x - t) >> d.sh1)) >> d.sh2);
+}
+
 // acc[mb][pb] += A(mb, step j) * B(pb, step j) for the four steps of one k-group.  Successive
 // MFMAs may target the same accumulator: v_mfma_f32_16x16x4_f32 issues every 32 cycles even in a
 // dependent chain (measured), so no extra accumulators are needed to keep the pipe busy.
