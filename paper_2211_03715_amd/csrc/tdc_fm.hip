@@ -44,6 +44,7 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
     tdc_f4 *__restrict__ z1s = lds4;                                   // [NB1][4][pitch1]
     tdc_f4 *__restrict__ red = z1s + (size_t)4 * a.NB1 * a.pitch1;     // [wave][PBK][64]   (KS > 1)
 
+    TDC_PROBE(0);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int g = lane >> 4, l16 = lane & 15;
@@ -59,13 +60,8 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
     const int nb = ng * a.NBG + nbi;
     const int kg0 = ks * a.kg_q + min(ks, a.kg_r), kg1 = kg0 + a.kg_q + (ks < a.kg_r ? 1 : 0);
     tdc_f4 wfrag[FM_FR];
-    {
-        const tdc_rsrc wrs = tdc_make_rsrc(a.wm_p + (size_t)nb * KG2 * 256, (unsigned)KG2 * 1024u);
-#pragma unroll
-        for (int f = 0; f < FM_FR; ++f)
-            wfrag[f] = tdc_buf_load4(wrs, ((unsigned)(kg0 + f) * 1024u + lane * 16u) | (kg0 + f < kg1 ? 0u : TDC_OOB));
-    }
 
+    TDC_PROBE(1);
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
         constexpr int U = MB1 >= 4 ? 2 : 4;
@@ -97,16 +93,34 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
             ++kg;
         };
         TdcPipe<MB1, 1, U> pipe;
-        for (int u = wave; u < n_units; u += nw) {
+        int u = wave;
+        if (u < n_units) {
             setup(u);
             pipe.start(next);
+        }
+        // The weight fragments of stage 2+3 go out right behind the first stage-1 operands: loads
+        // return in order, so stage 1 can start as soon as its own data is there while these are
+        // still in flight; a dead fragment (past the slice) reads as zero.
+        {
+            const tdc_rsrc wrs = tdc_make_rsrc(a.wm_p + (size_t)nb * KG2 * 256, (unsigned)KG2 * 1024u);
+#pragma unroll
+            for (int f = 0; f < FM_FR; ++f)
+                wfrag[f] = tdc_buf_load4(wrs, ((unsigned)(kg0 + f) * 1024u + lane * 16u) | (kg0 + f < kg1 ? 0u : TDC_OOB));
+        }
+        for (; u < n_units; u += nw) {
+            if (u != wave) {
+                setup(u);
+                pipe.start(next);
+            }
             tdc_f4 acc[MB1][1];
             pipe.run(acc, a.KG1, next);
 #pragma unroll
             for (int mb = 0; mb < MB1; ++mb) z1s[((mg * MB1 + mb) * 4 + g) * a.pitch1 + 16 * pg + l16] = acc[mb][0];
         }
     }
+    TDC_PROBE(2);
     __syncthreads();
+    TDC_PROBE(3);
 
     // ------------------------------------------------------------------ stages 2+3 (Eqs. 3, 4 folded)
     tdc_f4 acc[PBK];
@@ -125,28 +139,26 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
         const int r0 = tdc_div(tap0, a.div_K);
         int s = tap0 - r0 * a.K;
         int toff = r0 * a.QW + s;
+        // No branch on "fragment f is live": a dead fragment is all zeros and multiplies cell 0, so
+        // the LDS reads of all fragments can be issued ahead of the MFMAs.
 #pragma unroll
         for (int f = 0; f < FM_FR; ++f) {
-            if (kg0 + f < kg1) {
-                const int cell = dg * 4 * a.pitch1 + toff;
+            const int cell = kg0 + f < kg1 ? dg * 4 * a.pitch1 + toff : 0;
 #pragma unroll
-                for (int pb = 0; pb < PBK; ++pb) {
-                    const tdc_f4 bv = z1s[cell + qbase[pb]];
+            for (int pb = 0; pb < PBK; ++pb) {
+                const tdc_f4 bv = z1s[cell + (kg0 + f < kg1 ? qbase[pb] : 0)];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[pb] = tdc_mfma(wfrag[f][j], bv[j], acc[pb]);
-                }
-                if (++dg == a.NB1) {
-                    dg = 0;
-                    ++toff;
-                    if (++s == a.K) {
-                        s = 0;
-                        toff += a.QW - a.K;
-                    }
-                }
+                for (int j = 0; j < 4; ++j) acc[pb] = tdc_mfma(wfrag[f][j], bv[j], acc[pb]);
             }
+            const bool wrap_d = ++dg == a.NB1;
+            dg = wrap_d ? 0 : dg;
+            const bool wrap_s = wrap_d && ++s == a.K;   // s advances only when dg wraps
+            toff += wrap_d ? (wrap_s ? a.QW - a.K + 1 : 1) : 0;
+            s = wrap_s ? 0 : s;
         }
     }
 
+    TDC_PROBE(4);
     const int P2 = a.Ho * a.Wo;
     float *__restrict__ yb = a.y + (size_t)b * a.N * P2;
     if (a.KS == 1) {
@@ -163,12 +175,14 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
                 }
             }
         }
+        TDC_PROBE(7);
         return;
     }
     // partial sums of the KS slices, [wave = ks*NBG + block][pb][lane], then a fixed-order sum
 #pragma unroll
     for (int pb = 0; pb < PBK; ++pb) red[(wave * PBK + pb) * 64 + lane] = acc[pb];
     __syncthreads();
+    TDC_PROBE(5);
     for (int e = threadIdx.x; e < a.NBG * PBK * 64; e += blockDim.x) {
         const int ln = e & 63, pb = (e >> 6) % PBK, blk = (e >> 6) / PBK;
         tdc_f4 sum = red[(blk * PBK + pb) * 64 + ln];
@@ -187,6 +201,7 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
             }
         }
     }
+    TDC_PROBE(7);
 }
 
 }  // namespace
