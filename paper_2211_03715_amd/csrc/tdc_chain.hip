@@ -31,6 +31,7 @@ struct ChainArgs {
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
     int mb1;                // stage-1 register tile height (1, 2 or 4 channel blocks)
     int vec;                // 1: tile width, image width and tile origin are multiples of 4 -> 16-byte stores
+    TdcDiv div_tiles_x, div_QW, div_TW, div_npg1;   // launch-time constant divisors (npg1: stage-1 pixel groups)
 };
 
 __device__ __forceinline__ void tdc_buf_store(tdc_rsrc r, unsigned byte_off, float v)
@@ -56,13 +57,13 @@ struct ChainStage1 {
 
     __device__ __forceinline__ void setup(int u)
     {
-        pg = u % n_pg;
-        mg = u / n_pg;
+        mg = tdc_div(u, a.div_npg1);
+        pg = u - mg * n_pg;
         kg = 0;
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
             const int q = 16 * (pg * PB + pb) + l16;
-            const int qh = q / a.QW, qw = q - qh * a.QW;
+            const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
             const int h = h0 + qh, w = w0 + qw;
             const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
             xoff[pb] = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int g = lane >> 4, l16 = lane & 15;
-    const int ty = blockIdx.x / a.tiles_x, tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
+    const int ty = tdc_div(blockIdx.x, a.div_tiles_x), tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
     const int i0 = ty * a.TH, j0 = tx * a.TW;                   // first output pixel of the tile
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;  // first input pixel (may be < 0)
 
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
             const int p = 16 * (pg * PB + pb) + l16;
-            const int ph = p / a.TW, pw = p - ph * a.TW;
+            const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
             qbase[pb] = g * a.pitch1 + (p < a.P ? ph * a.stride * a.QW + pw * a.stride : 0);
         }
         tdc_f4 acc2[NB2][PB];
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int p = 16 * (pg * PB + pb) + 4 * g + i;
-                const int ph = p / a.TW, pw = p - ph * a.TW;
+                const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
                 const int oi = i0 + ph, oj = j0 + pw;
                 yq[pb][i] = (p < a.P && oi < a.Ho && oj < a.Wo) ? (unsigned)(oi * a.Wo + oj) * 4u : TDC_OOB;
             }
@@ -319,6 +320,8 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.w_uout4 = (int)(tdc_packed_floats_uout(d) / 4);
     a.mb1 = t.mb[0];
     a.vec = (g.TW % 4 == 0 && d.Wo % 4 == 0) ? 1 : 0;
+    a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
+    a.div_TW = tdc_make_div((unsigned)g.TW); a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_LAUNCH(N_, P_, W_)                                                                         \
     {                                                                                                  \

@@ -40,6 +40,7 @@ struct FusedArgs {
     int tiles_x;
     int pitch1, pitch2;     // LDS row pitches of the z1 / z2 tiles, in 16-byte units
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
+    TdcDiv div_tiles_x, div_QW, div_TW, div_npg1, div_npg2;   // launch-time constant divisors (pixel groups of stage 1 / stages 2, 3)
 };
 
 // LDS tiles hold 16-byte cells: cell (cb, g, col) = channels 16*cb + 4*g + {0,1,2,3} of pixel col,
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
     const int g = lane >> 4, l16 = lane & 15;
-    const int ty = blockIdx.x / a.tiles_x, tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
+    const int ty = tdc_div(blockIdx.x, a.div_tiles_x), tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
     const int i0 = ty * a.TH, j0 = tx * a.TW;                   // first output pixel of the tile
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;  // first input pixel (may be < 0)
     const int HW = a.H * a.W;
@@ -75,13 +76,13 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
         int pg = 0, mg = 0, kg = 0;
         unsigned xoff[PB];       // byte offset of this lane's pixel in a channel row, or TDC_OOB
         const auto setup = [&](int u) {
-            pg = u % n_pg;
-            mg = u / n_pg;
+            mg = tdc_div(u, a.div_npg1);
+            pg = u - mg * n_pg;
             kg = 0;
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const int q = 16 * (pg * PB + pb) + l16;
-                const int qh = q / a.QW, qw = q - qh * a.QW;
+                const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
                 const int h = h0 + qh, w = w0 + qw;
                 const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
                 xoff[pb] = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
@@ -156,12 +157,12 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
         const int KG2 = a.K * a.K * a.NB1;
         const tdc_rsrc wrs = tdc_make_rsrc(a.core_p, (unsigned)a.w_core4 * 16u);
         for (int u = wave; u < n_pg * n_mg; u += nw) {
-            const int pg = u % n_pg, mg = u / n_pg;
+            const int mg = tdc_div(u, a.div_npg2), pg = u - mg * n_pg;
             int qbase[PB];
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const int p = 16 * (pg * PB + pb) + l16;
-                const int ph = p / a.TW, pw = p - ph * a.TW;
+                const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
                 qbase[pb] = g * a.pitch1 + (p < a.P ? ph * a.stride * a.QW + pw * a.stride : 0);
             }
             int kg = 0, dg = 0, s = 0, toff = 0;     // toff = r*QW + s
@@ -213,13 +214,13 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
         float *__restrict__ yb = a.y + (size_t)b * a.N * P2;
         const tdc_rsrc wrs = tdc_make_rsrc(a.uout_p, (unsigned)a.w_uout4 * 16u);
         for (int u = wave; u < n_pg * n_mg; u += nw) {
-            const int pg = u % n_pg, mg = u / n_pg;
+            const int mg = tdc_div(u, a.div_npg2), pg = u - mg * n_pg;
             int yoff[PB], col[PB];
             bool ok[PB];
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const int p = 16 * (pg * PB + pb) + l16;
-                const int ph = p / a.TW, pw = p - ph * a.TW;
+                const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
                 const int i = i0 + ph, j = j0 + pw;
                 ok[pb] = p < a.P && i < a.Ho && j < a.Wo;
                 yoff[pb] = i * a.Wo + j;
@@ -312,6 +313,10 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.pitch1 = g.pitch1; a.pitch2 = g.pitch2;
     a.w_core4 = (int)(tdc_packed_floats_core(d) / 4);
     a.w_uout4 = (int)(tdc_packed_floats_uout(d) / 4);
+    a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
+    a.div_TW = tdc_make_div((unsigned)g.TW);
+    a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
+    a.div_npg2 = tdc_make_div((unsigned)((g.PBk + t.pb[0] - 1) / t.pb[0]));
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_LAUNCH(A_, B_, C_, D_, W_)                                                                 \
     {                                                                                                  \
