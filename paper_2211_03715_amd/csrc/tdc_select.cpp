@@ -39,13 +39,13 @@ struct FusedCoef {
 
 // One GEMM launch of SPLIT, MERGED or DENSE.  Fitted to ~2500 stage tunings of the batch-1 layers
 // (median relative error 5%, the picked tuning within 10% of the best one timed): a launch
-// costs ~2.6 us however small; a k-group ~0.065 us of issue per wavefront plus its MFMAs; the K x K
+// costs ~2.4 us however small; a k-group ~0.065 us of issue per wavefront plus its MFMAs; the K x K
 // stage pays for its gathered activation loads per pixel block; and the activation operand is
 // re-read by every output-channel group, which is what makes taller register tiles (mb > 1) pay
 // once there are many channel blocks -- charged as k-group loads per CU over the whole launch,
 // more per load for a strided gather.
 struct StageCoef {
-    double launch = 2.5930;
+    double launch = 2.35;
     double kg = 0.0649, mfma = 0.0785;
     double conv_b = 0.0255;       // K x K stage: per k-group and pixel block of the register tile
     double reduce = 0.3158;       // cross-wavefront sum through LDS, per 16x16 block of the tile
@@ -187,24 +187,25 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 }
 
 // FUSED_MERGED: stage 1 as in FUSED (dealt over nw wavefronts), then every wavefront runs its
-// slice of the merged convolution out of registers and LDS.  Fitted to ~2700 tunings of the
+// slice of the merged convolution out of registers and LDS.  Fitted to ~3300 tunings of the
 // batch-1, stride-1 layers (median relative error 8%; the picked tuning within 4% of the best
-// wherever this variant is competitive): 0.76 us per stage-1 unit (a memory round trip) plus
-// 0.16 us per k-group and its MFMAs, 0.11 us per weight fragment and pixel block of the tail, a
-// cross-slice sum, the bytes of x a CU pulls (input tile with halo, once per workgroup), and a
-// dispatch term per 256 workgroups -- the recomputation of stage 1 by every output-channel
-// group shows up there and in the x bytes.
+// wherever this variant is competitive): per stage-1 unit 0.18 us plus 0.10 us per k-group (its
+// operands come from memory) and its MFMAs, 0.09 us per weight fragment and pixel block of the
+// tail, 0.75 us for a cross-slice sum, the bytes of x a CU pulls (input tile with halo, once per
+// workgroup), and a dispatch term per 256 workgroups -- the recomputation of stage 1 by every
+// output-channel group shows up there and in the x bytes.
 struct FmCoef {
-    double launch = 0.2465;
-    double s1_unit = 0.7627, s1_kg = 0.1599, s1_mfma = 0.0364;
-    double frag = 0.1123;         // per weight fragment and pixel block, times the MFMA pipe share
-    double reduce = 0.2451;       // per pixel block when the contraction is sliced
-    double x_mb = 20.8968;        // per MB of x per CU
-    double wgs = 1.6149;          // per 256 workgroups
+    double launch = 1.2735;
+    double s1_unit = 0.1772, s1_kg = 0.0982, s1_mfma = 0.0562;
+    double frag = 0.0910;         // per weight fragment and pixel block, times the MFMA pipe share
+    double reduce = 0.7517;       // per pixel block when the contraction is sliced
+    double x_mb = 17.1877;        // per MB of x per CU
+    double wgs = 0.8449;          // per 256 workgroups
 };
 
 struct FmChoice {
     double us = 1e300;
+    bool calibrated = false;      // found inside the region the coefficients were fitted on
     int th = 0, tw = 0, nw = 0, mb1 = 0, nbg = 0;
 };
 
@@ -244,10 +245,10 @@ FmChoice best_fm(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &f
                         if (forced.mb[0] && mb1 != forced.mb[0]) continue;
                         if (forced.mb[1] && nbg != forced.mb[1]) continue;
                         if (!tdc_fm_supported(d, th, tw, nw, mb1, nbg)) continue;
-                        // the calibrated region: 4 or 8 wavefronts, as few contraction slices as the
+                        // the calibrated region: 2, 4 or 8 wavefronts, as few contraction slices as the
                         // register budget allows, or twice that
                         const int ks = nw / nbg;
-                        if (pass == 0 && !forced.waves[0] && nw != 4 && nw != 8) continue;
+                        if (pass == 0 && !forced.waves[0] && nw != 2 && nw != 4 && nw != 8) continue;
                         if (pass == 0 && !forced.waves[0] && !forced.mb[1] && ks != ks_min && ks != 2 * ks_min) continue;
                         const TdcFusedGeom g = tdc_fm_geometry(d, th, tw, nw, nbg);
                         if ((long)g.lds_bytes > dev.lds_per_wg) continue;
@@ -255,6 +256,7 @@ FmChoice best_fm(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &f
                         if (us < best.us) {
                             best.us = us;
                             best.th = th; best.tw = tw; best.nw = nw; best.mb1 = mb1; best.nbg = nbg;
+                            best.calibrated = pass == 0;
                         }
                     }
         }
@@ -383,7 +385,7 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     // The merged forms (stage 3 folded into the core) against the others: only below the throughput
     // regime, where their extra MACs cost nothing and the saved launches count.  The one-launch
     // form's estimate is optimistic once the contraction is cut into three or more slices, so it
-    // has to win by a margin.
+    // has to win by a margin, and only tunings inside its calibrated region are considered.
     if (forced.variant == TDC_VARIANT_AUTO && !pixels_fill_chip && d.stride == 1) {   // calibrated at stride 1 only
         const StageChoice m2 = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1], forced.pb[1],
                                           forced.waves[1], d.stride);
@@ -391,7 +393,8 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
         free_choice.mb[0] = free_choice.mb[1] = free_choice.mb[2] = 0;
         free_choice.waves[0] = 0;
         const FmChoice fm = best_fm(d, dev, free_choice);
-        if (fm.us * 1.1 < f.us && fm.us * 1.1 < split_us && fm.us * 1.1 < s[0].us + m2.us) {
+        const double fm_us = fm.calibrated ? fm.us * 1.05 : 1e300;
+        if (fm_us < f.us && fm_us < split_us && fm_us < s[0].us + m2.us) {
             t->variant = TDC_VARIANT_FUSED_MERGED;
             t->tile_h = fm.th; t->tile_w = fm.tw;
             t->waves[0] = t->waves[1] = t->waves[2] = fm.nw;
