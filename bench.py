@@ -32,9 +32,16 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
-# layer name; None until measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per layer call (all its kernels) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/cfg2.txt, each scaled by what the same counter reads for a plain 256 MiB
+# device copy (FETCH_SIZE under-reads 2.0x on this machine, WRITE_SIZE is exact): (fetched, written) KiB,
+# keyed by layer name and the variant that was profiled.
+MEASURED_TRAFFIC = {
+    ("b1_c64_n64_56x56_r16-16_k3_s1_p1", "fused-merged"): (5777.3, 784.0),
+    ("b1_c128_n128_28x28_r32-32_k3_s1_p1", "fused-merged"): (4540.4, 784.0),
+    ("b1_c256_n256_14x14_r64-64_k3_s1_p1", "merged"): (1050.9 + 1047.9, 57.0 + 196.0),
+    ("b1_c512_n512_7x7_r128-128_k3_s1_p1", "merged"): (1099.9 + 2579.7, 24.5 + 98.0),
+}
 
 
 def _time_events(fn, iters, torch):
@@ -234,7 +241,10 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": R.flops(Ld) / sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC.get(Ld.name())
+    traffic = MEASURED_TRAFFIC.get((Ld.name(), pd["plan"].split(" ")[0]))
+    roof["traffic"] = None if traffic is None else (traffic[0] + traffic[1]) * 1024.0      # bytes per layer call
+    roof["traffic_fetch_write_kib"] = traffic
+    roof["algorithmic_bytes"] = R.bytes_compulsory(Ld)
     roof["kernel"] = pd["plan"]
     roof["layer"] = Ld.name()
     roof["launch_us"] = pd["latency_us"]
