@@ -1,7 +1,12 @@
 // SPLIT variant: the three stages (Eqs. 2, 3, 4) as three fp32-MFMA GEMM kernels,
 //   D[b][m][p] = sum_k Wt[k][m] * Act[b][k][p],
 // with pixels p along the lanes (contiguous in NCHW), output channels m in the MFMA rows
-// and the intermediates z1 [B][R1P][H*W], z2 [B][R2P][Ho*Wo] in plan-owned workspace.
+// and the intermediates z1, z2 in plan-owned workspace in a blocked layout,
+//   z[b][channel block cb][pixel][16 channels],
+// which is the accumulator layout of the producing kernel (a lane holds channels 4g..4g+3 of one
+// pixel: one 16-byte store) and the B-operand layout of the consuming one (one 16-byte load per
+// lane and k-group, a wavefront reading 16 pixels x 64 bytes): the intermediates never pay the
+// four 4-byte loads per k-group that NCHW activations cost.
 // Stage 2 is an implicit GEMM: k = (tap, d1) and the activation operand is gathered from
 // z1 at the tap's offset, with zero for taps that fall outside the image.
 //
@@ -30,6 +35,7 @@ struct GemmArgs {
     float *out;
     int act_rows;        // channel rows per image in act (C, R1P, R2P)
     int act_rows_valid;  // rows that exist in memory (C for stage 1, all otherwise)
+    int out_blocked;     // out is a blocked intermediate (see the head of this file), not NCHW
     int act_pix;         // pixels per row in act
     int out_rows;        // channel rows per image in out (R1P, R2P, N)
     int out_pix;         // pixels per row in out
@@ -56,7 +62,8 @@ __device__ __forceinline__ int tdc_logical_block(int bid, int n)
 }
 
 // Stateful operand fetcher of one wavefront: each call returns the next k-group of its range.
-template <int MODE, int MB, int PB>
+// ACTB: the activation operand is a blocked intermediate.
+template <int MODE, bool ACTB, int MB, int PB>
 struct GemmNext {
     tdc_rsrc wrs, ars;                // packed weights of this tile's first m-block; activations of this image
     unsigned wlane;                   // byte offset of this lane inside a 1 KiB weight fragment
@@ -79,11 +86,15 @@ struct GemmNext {
             for (int pb = 0; pb < PB; ++pb) {
                 const int h = ih0[pb] + r, w = iw0[pb] + s;
                 const bool ok = pval[pb] && h >= 0 && h < H && w >= 0 && w < W;
-                const unsigned base = (unsigned)((16 * dg + 4 * g) * act_pix + poff[pb] + toff) * 4u;
                 const unsigned bad = ok ? dead : TDC_OOB;
-                bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
-                                  tdc_buf_load(ars, (base + 8u * act_pix) | bad),
-                                  tdc_buf_load(ars, (base + 12u * act_pix) | bad)};
+                if (ACTB) {
+                    bv[pb] = tdc_buf_load4(ars, ((unsigned)((dg * act_pix + poff[pb] + toff) * 16 + 4 * g) * 4u) | bad);
+                } else {
+                    const unsigned base = (unsigned)((16 * dg + 4 * g) * act_pix + poff[pb] + toff) * 4u;
+                    bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
+                                      tdc_buf_load(ars, (base + 8u * act_pix) | bad),
+                                      tdc_buf_load(ars, (base + 12u * act_pix) | bad)};
+                }
             }
             if (++dg == NBk) {
                 dg = 0;
@@ -96,18 +107,22 @@ struct GemmNext {
             // rows past the last channel lie beyond the descriptor and read as 0 by themselves
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
-                const unsigned base = (unsigned)((16 * kg + 4 * g) * act_pix + poff[pb]) * 4u;
                 const unsigned bad = pval[pb] ? dead : TDC_OOB;
-                bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
-                                  tdc_buf_load(ars, (base + 8u * act_pix) | bad),
-                                  tdc_buf_load(ars, (base + 12u * act_pix) | bad)};
+                if (ACTB) {
+                    bv[pb] = tdc_buf_load4(ars, ((unsigned)((kg * act_pix + poff[pb]) * 16 + 4 * g) * 4u) | bad);
+                } else {
+                    const unsigned base = (unsigned)((16 * kg + 4 * g) * act_pix + poff[pb]) * 4u;
+                    bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
+                                      tdc_buf_load(ars, (base + 8u * act_pix) | bad),
+                                      tdc_buf_load(ars, (base + 12u * act_pix) | bad)};
+                }
             }
         }
         ++kg;
     }
 };
 
-template <int MODE, int MB, int PB, int U>
+template <int MODE, bool ACTB, int MB, int PB, int U>
 __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
 {
     extern __shared__ float red[];
@@ -120,7 +135,7 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     const int pg = a.pg_major ? hi : lo, mg = a.pg_major ? lo : hi;
     const int b = blockIdx.y;
 
-    GemmNext<MODE, MB, PB> next;
+    GemmNext<MODE, ACTB, MB, PB> next;
     next.wstride = (unsigned)a.KG * 1024u;
     next.wrs = tdc_make_rsrc(a.wp + (size_t)mg * MB * a.KG * 256, MB * next.wstride);
     next.ars = tdc_make_rsrc(a.act + (size_t)b * a.act_rows * a.act_pix, (unsigned)a.act_rows_valid * a.act_pix * 4u);
@@ -160,17 +175,23 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     TDC_PROBE((MODE - 1) * 5 + 2);
 
     float *__restrict__ outb = a.out + (size_t)b * a.out_rows * a.out_pix;
+    tdc_f4 *__restrict__ outb4 = reinterpret_cast<tdc_f4 *>(outb);   // blocked: cell (cb, p, g) = [(cb*out_pix + p)*4 + g]
     if (nw == 1) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb)
+            for (int pb = 0; pb < PB; ++pb) {
+                const int p = 16 * (pg * PB + pb) + l16;
+                if (a.out_blocked) {
+                    if (p < a.out_pix) outb4[((size_t)(mg * MB + mb) * a.out_pix + p) * 4 + g] = acc[mb][pb];
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int m = 16 * (mg * MB + mb) + 4 * g + i;
-                    const int p = 16 * (pg * PB + pb) + l16;
-                    if (m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = acc[mb][pb][i];
+                    for (int i = 0; i < 4; ++i) {
+                        const int m = 16 * (mg * MB + mb) + 4 * g + i;
+                        if (m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = acc[mb][pb][i];
+                    }
                 }
+            }
         return;
     }
     // Partial sums of every wavefront to LDS, [wave][(mb*PB + pb)*4 + i][lane], then a fixed-order sum.
@@ -183,6 +204,23 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
             for (int i = 0; i < 4; ++i) red[wave * E + ((mb * PB + pb) * 4 + i) * 64 + lane] = acc[mb][pb][i];
     __syncthreads();
     TDC_PROBE((MODE - 1) * 5 + 3);
+    if (a.out_blocked) {
+        for (int e = threadIdx.x; e < E / 4; e += blockDim.x) {   // one 16-byte cell per thread
+            const int ln = e & 63, blk = e >> 6;
+            tdc_f4 sum;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float v = red[(blk * 4 + i) * 64 + ln];
+                for (int ww = 1; ww < nw; ++ww) v += red[ww * E + (blk * 4 + i) * 64 + ln];
+                sum[i] = v;
+            }
+            const int pb = blk % PB, mb = blk / PB;
+            const int p = 16 * (pg * PB + pb) + (ln & 15);
+            if (p < a.out_pix) outb4[((size_t)(mg * MB + mb) * a.out_pix + p) * 4 + (ln >> 4)] = sum;
+        }
+        TDC_PROBE((MODE - 1) * 5 + 4);
+        return;
+    }
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         float sum = red[e];
         for (int ww = 1; ww < nw; ++ww) sum += red[ww * E + e];
@@ -211,7 +249,7 @@ int pick_u(int kg_per_wave, int umax)
     return best;
 }
 
-template <int MODE>
+template <int MODE, bool ACTB>
 hipError_t launch_stage(const GemmArgs &a_in, int mb, int pb, int waves, int batch, hipStream_t s)
 {
     GemmArgs a = a_in;
@@ -234,7 +272,7 @@ hipError_t launch_stage(const GemmArgs &a_in, int mb, int pb, int waves, int bat
     if (mb * pb > 4) u = 2;
 #define TDC_CASE(M_, P_, U_)                                                                      \
     if (mb == M_ && pb == P_ && u == U_) {                                                        \
-        hipLaunchKernelGGL((tdc_gemm_kernel<MODE, M_, P_, U_>), grid, block, lds, s, a);          \
+        hipLaunchKernelGGL((tdc_gemm_kernel<MODE, ACTB, M_, P_, U_>), grid, block, lds, s, a);    \
         return hipGetLastError();                                                                 \
     }
     TDC_CASE(1, 1, 1) TDC_CASE(1, 1, 2) TDC_CASE(1, 1, 3) TDC_CASE(1, 1, 4)
@@ -262,27 +300,27 @@ hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s
     // stage 1 (Eq. 2): z1 = U_in^T x
     a.act = x; a.wp = uin_p; a.out = z1;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
-    a.out_rows = 16 * d.NB1; a.out_pix = HW;
+    a.out_rows = 16 * d.NB1; a.out_pix = HW; a.out_blocked = 1;
     a.NBm = d.NB1; a.KG = d.KG1; a.NBk = 1;
     a.n_pgroups = ((HW + 15) / 16 + t.pb[0] - 1) / t.pb[0];
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
-    hipError_t e = launch_stage<1>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
+    hipError_t e = launch_stage<1, false>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
     if (e != hipSuccess) return e;
     // stage 2 (Eq. 3): z2 = core conv of z1
     a.act = z1; a.wp = core_p; a.out = z2;
     a.act_rows = 16 * d.NB1; a.act_rows_valid = 16 * d.NB1; a.act_pix = HW;
-    a.out_rows = 16 * d.NB2; a.out_pix = P;
+    a.out_rows = 16 * d.NB2; a.out_pix = P; a.out_blocked = 1;
     a.NBm = d.NB2; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
-    e = launch_stage<2>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+    e = launch_stage<2, true>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
     if (e != hipSuccess) return e;
     // stage 3 (Eq. 4): y = U_out^T z2
     a.act = z2; a.wp = uout_p; a.out = y;
     a.act_rows = 16 * d.NB2; a.act_rows_valid = 16 * d.NB2; a.act_pix = P;
-    a.out_rows = d.N; a.out_pix = P;
+    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0;
     a.NBm = d.NB3; a.KG = d.NB2; a.NBk = 1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[2] - 1) / t.pb[2];
-    return launch_stage<3>(a, t.mb[2], t.pb[2], t.waves[2], d.B, s);
+    return launch_stage<3, true>(a, t.mb[2], t.pb[2], t.waves[2], d.B, s);
 }
 
 // The undecomposed layer (Eq. 1's kernel applied directly): the stage-2 implicit GEMM with the
@@ -296,11 +334,11 @@ hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s
     GemmArgs a;
     a.act = x; a.wp = w_p; a.out = y;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
-    a.out_rows = d.N; a.out_pix = P;
+    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0;
     a.NBm = d.NB2; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
-    return launch_stage<2>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+    return launch_stage<2, false>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
 }
 
 // MERGED variant: two launches.  Stage 1 as in SPLIT; then one implicit GEMM R1 -> N with the
@@ -314,16 +352,16 @@ hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t 
     GemmArgs a;
     a.act = x; a.wp = uin_p; a.out = z1;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
-    a.out_rows = 16 * d.NB1; a.out_pix = HW;
+    a.out_rows = 16 * d.NB1; a.out_pix = HW; a.out_blocked = 1;
     a.NBm = d.NB1; a.KG = d.KG1; a.NBk = 1;
     a.n_pgroups = ((HW + 15) / 16 + t.pb[0] - 1) / t.pb[0];
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
-    hipError_t e = launch_stage<1>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
+    hipError_t e = launch_stage<1, false>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
     if (e != hipSuccess) return e;
     a.act = z1; a.wp = wm_p; a.out = y;
     a.act_rows = 16 * d.NB1; a.act_rows_valid = 16 * d.NB1; a.act_pix = HW;
-    a.out_rows = d.N; a.out_pix = P;
+    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0;
     a.NBm = d.NB3; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
-    return launch_stage<2>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+    return launch_stage<2, true>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
 }
