@@ -123,6 +123,25 @@ int tdc_conv_tucker2(tdc_plan *plan, void *hip_stream,
                      const float *x, const float *U_in, const float *core, const float *U_out,
                      float *y, const tdc_shape *shape);
 
+/* Optional output epilogue for the _ex entry points: with acc the convolution result,
+ *     y = acc + bias[n] + residual[same element as y],   then   y = max(y, 0) if relu != 0,
+ * applied in the store of y (no extra pass, no extra launch).  It lets a chain of layers with
+ * batch-norm folded into the weights and bias, ReLU, and a ResNet shortcut run as one call per
+ * layer (the paper's end-to-end models, section 7.3, have such layers between the Tucker
+ * convolutions).  bias: device pointer to N floats or NULL.  residual: device pointer to a tensor
+ * shaped and laid out like y, or NULL; it must not overlap y.  A NULL epilogue is no epilogue;
+ * tdc_conv_tucker2(...) == tdc_conv_tucker2_ex(..., NULL).  Same ownership, asynchrony and error rules
+ * as the plain calls. */
+typedef struct tdc_epilogue {
+    const float *bias;
+    const float *residual;
+    int32_t relu;
+} tdc_epilogue;
+
+int tdc_conv_tucker2_ex(tdc_plan *plan, void *hip_stream,
+                        const float *x, const float *U_in, const float *core, const float *U_out,
+                        float *y, const tdc_shape *shape, const tdc_epilogue *epilogue);
+
 /* The undecomposed layer, y = K (*) x with the dense kernel W[C][N][K][K] = K(c,n,r,s) of Eq. 1
  * (same index order as `core`, same padding / stride / cross-correlation rule, x and y as above).
  * This is the "original convolution" of the paper's rank selection (section 6): a layer is only
@@ -136,6 +155,8 @@ int tdc_conv_tucker2(tdc_plan *plan, void *hip_stream,
 int tdc_plan_pack_dense(tdc_plan *plan, void *hip_stream, const float *W);
 int tdc_conv_dense(tdc_plan *plan, void *hip_stream, const float *x, const float *W, float *y,
                    const tdc_shape *shape);
+int tdc_conv_dense_ex(tdc_plan *plan, void *hip_stream, const float *x, const float *W, float *y,
+                      const tdc_shape *shape, const tdc_epilogue *epilogue);
 
 /* Release the plan and its workspace.  NULL is accepted. */
 int tdc_plan_destroy(tdc_plan *plan);

@@ -195,3 +195,16 @@ def conv_factored(sh: Shape, x, U_in, core, U_out, lib=None, return_intermediate
     if return_intermediates:
         return y, macs, z1, z2
     return y, macs
+
+
+def apply_epilogue(y, bias=None, residual=None, relu: bool = False):
+    """The output epilogue in float64: y + bias[n] + residual, then max(., 0) if relu.
+    y: float64 [batch][N][Ho][Wo]; bias: [N] or None; residual: shaped like y or None."""
+    out = np.array(y, dtype=np.float64, copy=True)
+    if bias is not None:
+        out += np.asarray(bias, dtype=np.float64).reshape(1, -1, 1, 1)
+    if residual is not None:
+        out += np.asarray(residual, dtype=np.float64)
+    if relu:
+        out = np.maximum(out, 0.0)
+    return out

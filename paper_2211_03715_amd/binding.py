@@ -30,7 +30,8 @@ VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "
 EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", "tdc_conv_tucker2",
            "tdc_plan_destroy", "tdc_plan_get_tuning", "tdc_plan_describe", "tdc_plan_workspace_bytes",
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
-           "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks"]
+           "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks",
+           "tdc_conv_tucker2_ex", "tdc_conv_dense_ex"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -59,6 +60,10 @@ class tdc_rank_layer(ctypes.Structure):
 class tdc_rank_choice(ctypes.Structure):
     _fields_ = [("decomposed", ctypes.c_int32), ("R1", ctypes.c_int32), ("R2", ctypes.c_int32),
                 ("latency_us", ctypes.c_double), ("macs", ctypes.c_double)]
+
+
+class tdc_epilogue(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("residual", ctypes.c_void_p), ("relu", ctypes.c_int32)]
 
 
 class TdcError(RuntimeError):
@@ -94,6 +99,11 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_plan_pack_dense.restype = ip
     lib.tdc_conv_dense.argtypes = [vp, vp, vp, vp, vp, sp]
     lib.tdc_conv_dense.restype = ip
+    ep = ctypes.POINTER(tdc_epilogue)
+    lib.tdc_conv_tucker2_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp, ep]
+    lib.tdc_conv_tucker2_ex.restype = ip
+    lib.tdc_conv_dense_ex.argtypes = [vp, vp, vp, vp, vp, sp, ep]
+    lib.tdc_conv_dense_ex.restype = ip
     lib.tdc_plan_destroy.argtypes = [vp]
     lib.tdc_plan_destroy.restype = ip
     lib.tdc_plan_get_tuning.argtypes = [vp, tp]
@@ -221,6 +231,25 @@ def tdc_conv_dense(plan, x, W, y, shape: tdc_shape, stream=None) -> None:
     rc = load().tdc_conv_dense(plan, _stream(stream), _ptr(x), _ptr(W), _ptr(y), ctypes.byref(shape))
     if rc != TDC_OK:
         raise TdcError(rc, "tdc_conv_dense")
+
+
+def make_epilogue(bias=None, residual=None, relu=False) -> tdc_epilogue:
+    """bias / residual: torch tensors on the plan's device (or raw device pointers) or None."""
+    return tdc_epilogue(_ptr(bias), _ptr(residual), 1 if relu else 0)
+
+
+def tdc_conv_tucker2_ex(plan, x, U_in, core, U_out, y, shape: tdc_shape, epilogue: Optional[tdc_epilogue], stream=None) -> None:
+    rc = load().tdc_conv_tucker2_ex(plan, _stream(stream), _ptr(x), _ptr(U_in), _ptr(core), _ptr(U_out), _ptr(y),
+                                    ctypes.byref(shape), ctypes.byref(epilogue) if epilogue is not None else None)
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_conv_tucker2_ex")
+
+
+def tdc_conv_dense_ex(plan, x, W, y, shape: tdc_shape, epilogue: Optional[tdc_epilogue], stream=None) -> None:
+    rc = load().tdc_conv_dense_ex(plan, _stream(stream), _ptr(x), _ptr(W), _ptr(y), ctypes.byref(shape),
+                                  ctypes.byref(epilogue) if epilogue is not None else None)
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_conv_dense_ex")
 
 
 def tdc_plan_get_tuning(plan) -> tdc_tuning:

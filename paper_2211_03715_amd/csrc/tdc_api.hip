@@ -357,7 +357,14 @@ int tdc_plan_pack_weights(tdc_plan *p, void *hip_stream, const float *U_in, cons
 int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float *U_in, const float *core,
                      const float *U_out, float *y, const tdc_shape *shape)
 {
+    return tdc_conv_tucker2_ex(p, hip_stream, x, U_in, core, U_out, y, shape, nullptr);
+}
+
+int tdc_conv_tucker2_ex(tdc_plan *p, void *hip_stream, const float *x, const float *U_in, const float *core,
+                        const float *U_out, float *y, const tdc_shape *shape, const tdc_epilogue *epilogue)
+{
     if (!p || !x || !U_in || !core || !U_out || !y || !shape) return TDC_ERR_NULL;
+    const TdcEpi epi = epilogue ? TdcEpi{epilogue->bias, epilogue->residual, epilogue->relu} : TdcEpi{nullptr, nullptr, 0};
     if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
     if (p->tuning.variant == TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
     DeviceGuard guard(p->device);
@@ -366,7 +373,7 @@ int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float 
     const TdcDims &d = p->dims;
     hipError_t e;
     if (p->tuning.variant == TDC_VARIANT_NAIVE) {
-        e = tdc_launch_naive(d, s, x, U_in, core, U_out, p->z1, p->z2, y);
+        e = tdc_launch_naive(d, s, x, U_in, core, U_out, p->z1, p->z2, y, epi);
         return e == hipSuccess ? TDC_OK : TDC_ERR_HIP;
     }
     const bool packed = p->packed_from[0] == U_in && p->packed_from[1] == core && p->packed_from[2] == U_out;
@@ -378,15 +385,15 @@ int tdc_conv_tucker2(tdc_plan *p, void *hip_stream, const float *x, const float 
         if (e != hipSuccess) return TDC_ERR_HIP;
     }
     if (p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
-        e = tdc_launch_fm(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, y);
+        e = tdc_launch_fm(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, y, epi);
     else if (p->tuning.variant == TDC_VARIANT_MERGED)
-        e = tdc_launch_merged(d, p->tuning, s, x, p->uin_p, p->core_p, p->z1, y);
+        e = tdc_launch_merged(d, p->tuning, s, x, p->uin_p, p->core_p, p->z1, y, epi);
     else if (p->tuning.variant == TDC_VARIANT_SPLIT)
-        e = tdc_launch_split(d, p->tuning, s, x, p->uin_p, p->core_p, p->uout_p, p->z1, p->z2, y);
+        e = tdc_launch_split(d, p->tuning, s, x, p->uin_p, p->core_p, p->uout_p, p->z1, p->z2, y, epi);
     else if (p->tuning.variant == TDC_VARIANT_CHAIN)
-        e = tdc_launch_chain(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, p->uout_p, y);
+        e = tdc_launch_chain(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, p->uout_p, y, epi);
     else
-        e = tdc_launch_fused(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, p->uout_p, y);
+        e = tdc_launch_fused(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, p->uout_p, y, epi);
     return e == hipSuccess ? TDC_OK : TDC_ERR_HIP;
 }
 
@@ -404,7 +411,14 @@ int tdc_plan_pack_dense(tdc_plan *p, void *hip_stream, const float *W)
 
 int tdc_conv_dense(tdc_plan *p, void *hip_stream, const float *x, const float *W, float *y, const tdc_shape *shape)
 {
+    return tdc_conv_dense_ex(p, hip_stream, x, W, y, shape, nullptr);
+}
+
+int tdc_conv_dense_ex(tdc_plan *p, void *hip_stream, const float *x, const float *W, float *y, const tdc_shape *shape,
+                      const tdc_epilogue *epilogue)
+{
     if (!p || !x || !W || !y || !shape) return TDC_ERR_NULL;
+    const TdcEpi epi = epilogue ? TdcEpi{epilogue->bias, epilogue->residual, epilogue->relu} : TdcEpi{nullptr, nullptr, 0};
     if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
     if (p->tuning.variant != TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
     DeviceGuard guard(p->device);
@@ -414,7 +428,7 @@ int tdc_conv_dense(tdc_plan *p, void *hip_stream, const float *x, const float *W
         p->packed_from[1] = nullptr;
         if (tdc_launch_pack_core(p->dims, s, W, p->core_p) != hipSuccess) return TDC_ERR_HIP;
     }
-    return tdc_launch_dense(p->dims, p->tuning, s, x, p->core_p, y) == hipSuccess ? TDC_OK : TDC_ERR_HIP;
+    return tdc_launch_dense(p->dims, p->tuning, s, x, p->core_p, y, epi) == hipSuccess ? TDC_OK : TDC_ERR_HIP;
 }
 
 int tdc_plan_get_tuning(const tdc_plan *p, tdc_tuning *out)

@@ -31,6 +31,7 @@ struct ChainArgs {
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
     int mb1;                // stage-1 register tile height (1, 2 or 4 channel blocks)
     int vec;                // 1: tile width, image width and tile origin are multiples of 4 -> 16-byte stores
+    TdcEpi epi;
     TdcDiv div_tiles_x, div_QW, div_TW, div_npg1;   // launch-time constant divisors (npg1: stage-1 pixel groups)
 };
 
@@ -248,6 +249,20 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
                     for (int pb = 0; pb < PB; ++pb) acc3[pb] = tdc_mfma(acc2[kg][pb][j], u[kg][j], acc3[pb]);
             // channels past N lie beyond the descriptor: the hardware drops those stores
             const unsigned plane = (unsigned)(16 * nb + l16) * P2 * 4u;
+            if (a.epi.bias || a.epi.residual || a.epi.relu) {
+                // this lane holds channel 16*nb + l16 at the four pixels 4*g + i of every block
+                const int n = 16 * nb + l16;
+                const float bias = (a.epi.bias && n < a.N) ? a.epi.bias[n] : 0.f;
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float v = acc3[pb][i] + bias;
+                        if (a.epi.residual && n < a.N && !(yq[pb][i] & TDC_OOB))
+                            v += a.epi.residual[(size_t)b * a.N * P2 + (size_t)n * P2 + (yq[pb][i] >> 2)];
+                        acc3[pb][i] = a.epi.relu ? fmaxf(v, 0.f) : v;
+                    }
+            }
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 if (a.vec) {
@@ -306,9 +321,10 @@ TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int ld
 
 hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
-                            const float *uout_p, float *y)
+                            const float *uout_p, float *y, const TdcEpi &epi)
 {
     ChainArgs a;
+    a.epi = epi;
     a.x = x; a.uin_p = uin_p; a.core_p = core_p; a.uout_p = uout_p; a.y = y;
     a.C = d.C; a.N = d.N; a.H = d.H; a.W = d.W; a.Ho = d.Ho; a.Wo = d.Wo;
     a.K = d.K; a.stride = d.stride; a.pad = d.pad;

@@ -34,6 +34,7 @@ struct FmArgs {
     int pitch1;             // LDS row pitch of the z1 tile, in 16-byte cells
     int NBG, KS;            // output-channel blocks per workgroup, contraction slices
     int kg_q, kg_r;         // KG2 = KS * kg_q + kg_r: the first kg_r slices take kg_q + 1 k-groups
+    TdcEpi epi;
     TdcDiv div_tiles, div_tiles_x, div_NBG, div_QB, div_QW, div_TW, div_NB1, div_K;   // constant divisors
 };
 
@@ -171,7 +172,10 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int n = 16 * nb + 4 * g + c;
-                    if (n < a.N) yb[(size_t)n * P2 + i * a.Wo + j] = acc[pb][c];
+                    if (n < a.N) {
+                        const size_t idx = (size_t)n * P2 + i * a.Wo + j;
+                        yb[idx] = tdc_apply_epilogue(a.epi, acc[pb][c], n, (size_t)b * a.N * P2 + idx);
+                    }
                 }
             }
         }
@@ -197,7 +201,10 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int n = 16 * (ng * a.NBG + blk) + 4 * (ln >> 4) + c;
-                if (n < a.N) yb[(size_t)n * P2 + i * a.Wo + j] = sum[c];
+                if (n < a.N) {
+                    const size_t idx = (size_t)n * P2 + i * a.Wo + j;
+                    yb[idx] = tdc_apply_epilogue(a.epi, sum[c], n, (size_t)b * a.N * P2 + idx);
+                }
             }
         }
     }
@@ -239,9 +246,10 @@ TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, i
 }
 
 hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s, const float *x,
-                         const float *uin_p, const float *wm_p, float *y)
+                         const float *uin_p, const float *wm_p, float *y, const TdcEpi &epi)
 {
     FmArgs a;
+    a.epi = epi;
     a.x = x; a.uin_p = uin_p; a.wm_p = wm_p; a.y = y;
     a.C = d.C; a.N = d.N; a.H = d.H; a.W = d.W; a.Ho = d.Ho; a.Wo = d.Wo;
     a.K = d.K; a.stride = d.stride; a.pad = d.pad;

@@ -40,6 +40,7 @@ struct FusedArgs {
     int tiles_x;
     int pitch1, pitch2;     // LDS row pitches of the z1 / z2 tiles, in 16-byte units
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
+    TdcEpi epi;
     TdcDiv div_tiles_x, div_QW, div_TW, div_npg1, div_npg2;   // launch-time constant divisors (pixel groups of stage 1 / stages 2, 3)
 };
 
@@ -251,7 +252,10 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int n = 16 * (mg * MB3 + mb) + 4 * g + i;
-                        if (ok[pb] && n < a.N) yb[(size_t)n * P2 + yoff[pb]] = acc[mb][pb][i];
+                        if (ok[pb] && n < a.N) {
+                            const size_t idx = (size_t)n * P2 + yoff[pb];
+                            yb[idx] = tdc_apply_epilogue(a.epi, acc[mb][pb][i], n, (size_t)b * a.N * P2 + idx);
+                        }
                     }
         }
     }
@@ -301,9 +305,10 @@ TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w, int ld
 
 hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
-                            const float *uout_p, float *y)
+                            const float *uout_p, float *y, const TdcEpi &epi)
 {
     FusedArgs a;
+    a.epi = epi;
     a.x = x; a.uin_p = uin_p; a.core_p = core_p; a.uout_p = uout_p; a.y = y;
     a.C = d.C; a.N = d.N; a.H = d.H; a.W = d.W; a.Ho = d.Ho; a.Wo = d.Wo;
     a.K = d.K; a.stride = d.stride; a.pad = d.pad;

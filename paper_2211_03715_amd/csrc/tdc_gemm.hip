@@ -36,6 +36,7 @@ struct GemmArgs {
     int act_rows;        // channel rows per image in act (C, R1P, R2P)
     int act_rows_valid;  // rows that exist in memory (C for stage 1, all otherwise)
     int out_blocked;     // out is a blocked intermediate (see the head of this file), not NCHW
+    TdcEpi epi;          // applied to an NCHW output only (the layer's y)
     int act_pix;         // pixels per row in act
     int out_rows;        // channel rows per image in out (R1P, R2P, N)
     int out_pix;         // pixels per row in out
@@ -188,7 +189,10 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int m = 16 * (mg * MB + mb) + 4 * g + i;
-                        if (m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = acc[mb][pb][i];
+                        if (m < a.out_rows && p < a.out_pix) {
+                            const size_t idx = (size_t)m * a.out_pix + p;
+                            outb[idx] = tdc_apply_epilogue(a.epi, acc[mb][pb][i], m, (size_t)b * a.out_rows * a.out_pix + idx);
+                        }
                     }
                 }
             }
@@ -228,7 +232,10 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
         const int pb = blk % PB, mb = blk / PB;
         const int m = 16 * (mg * MB + mb) + 4 * (ln >> 4) + i;
         const int p = 16 * (pg * PB + pb) + (ln & 15);
-        if (m < a.out_rows && p < a.out_pix) outb[(size_t)m * a.out_pix + p] = sum;
+        if (m < a.out_rows && p < a.out_pix) {
+            const size_t idx = (size_t)m * a.out_pix + p;
+            outb[idx] = tdc_apply_epilogue(a.epi, sum, m, (size_t)b * a.out_rows * a.out_pix + idx);
+        }
     }
     TDC_PROBE((MODE - 1) * 5 + 4);
 }
@@ -293,10 +300,11 @@ bool tdc_gemm_unit_supported(int mb, int pb)
 
 hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
                             const float *uin_p, const float *core_p, const float *uout_p,
-                            float *z1, float *z2, float *y)
+                            float *z1, float *z2, float *y, const TdcEpi &epi)
 {
     const int HW = d.H * d.W, P = d.Ho * d.Wo;
     GemmArgs a;
+    a.epi = TdcEpi{nullptr, nullptr, 0};
     // stage 1 (Eq. 2): z1 = U_in^T x
     a.act = x; a.wp = uin_p; a.out = z1;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
@@ -317,7 +325,7 @@ hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s
     // stage 3 (Eq. 4): y = U_out^T z2
     a.act = z2; a.wp = uout_p; a.out = y;
     a.act_rows = 16 * d.NB2; a.act_rows_valid = 16 * d.NB2; a.act_pix = P;
-    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0;
+    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0; a.epi = epi;
     a.NBm = d.NB3; a.KG = d.NB2; a.NBk = 1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[2] - 1) / t.pb[2];
     return launch_stage<3, true>(a, t.mb[2], t.pb[2], t.waves[2], d.B, s);
@@ -328,13 +336,14 @@ hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s
 // 16-blocks of C and NB2 those of N; x has exactly C rows (rows of the last, partial block lie
 // beyond the buffer descriptor and read as zero) and y exactly N.
 hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
-                            const float *w_p, float *y)
+                            const float *w_p, float *y, const TdcEpi &epi)
 {
     const int HW = d.H * d.W, P = d.Ho * d.Wo;
     GemmArgs a;
+    a.epi = TdcEpi{nullptr, nullptr, 0};
     a.act = x; a.wp = w_p; a.out = y;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
-    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0;
+    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0; a.epi = epi;
     a.NBm = d.NB2; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
@@ -346,10 +355,11 @@ hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s
 // spends K*K*R1*N instead of K*K*R1*R2 + R2*N MACs per output pixel, but its output-channel
 // blocks are independent workgroups, which is what a small image lacks, and a launch is saved.
 hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
-                             const float *uin_p, const float *wm_p, float *z1, float *y)
+                             const float *uin_p, const float *wm_p, float *z1, float *y, const TdcEpi &epi)
 {
     const int HW = d.H * d.W, P = d.Ho * d.Wo;
     GemmArgs a;
+    a.epi = TdcEpi{nullptr, nullptr, 0};
     a.act = x; a.wp = uin_p; a.out = z1;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
     a.out_rows = 16 * d.NB1; a.out_pix = HW; a.out_blocked = 1;
@@ -360,7 +370,7 @@ hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t 
     if (e != hipSuccess) return e;
     a.act = z1; a.wp = wm_p; a.out = y;
     a.act_rows = 16 * d.NB1; a.act_rows_valid = 16 * d.NB1; a.act_pix = HW;
-    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0;
+    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0; a.epi = epi;
     a.NBm = d.NB3; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
     return launch_stage<2, true>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);

@@ -23,6 +23,14 @@
 
 #include "tdc.h"
 
+// Optional output epilogue, applied as the last kernel stores y:
+//   y = acc + bias[n] + residual[same element as y], then max(., 0) if relu.
+struct TdcEpi {
+    const float *bias;       // [N] or null
+    const float *residual;   // shaped and laid out like y, or null
+    int relu;
+};
+
 struct TdcDims {
     int B, C, N, H, W, R1, R2, K, stride, pad, Ho, Wo;
     int NB1, NB2, NB3;   // 16-blocks of the padded R1, R2, N
@@ -42,21 +50,21 @@ size_t tdc_packed_floats_uout(const TdcDims &d);
 
 // ---- plain kernels (tdc_naive.hip): raw weights, z1 [B][R1][H*W], z2 [B][R2][Ho*Wo]
 hipError_t tdc_launch_naive(const TdcDims &d, hipStream_t s, const float *x, const float *U_in,
-                            const float *core, const float *U_out, float *z1, float *z2, float *y);
+                            const float *core, const float *U_out, float *z1, float *z2, float *y, const TdcEpi &epi);
 
 // ---- three MFMA GEMM kernels (tdc_gemm.hip): packed weights, z1 [B][R1P][H*W], z2 [B][R2P][Ho*Wo]
 bool tdc_gemm_unit_supported(int mb, int pb);
 hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
                             const float *uin_p, const float *core_p, const float *uout_p,
-                            float *z1, float *z2, float *y);
+                            float *z1, float *z2, float *y, const TdcEpi &epi);
 
 // the dense K x K layer through the stage-2 kernel; `d` has R1 = C, R2 = N
 hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
-                            const float *w_p, float *y);
+                            const float *w_p, float *y, const TdcEpi &epi);
 
 // stage 1, then stages 2 and 3 as one implicit GEMM with the merged kernel
 hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
-                             const float *uin_p, const float *wm_p, float *z1, float *y);
+                             const float *uin_p, const float *wm_p, float *z1, float *y, const TdcEpi &epi);
 
 // ---- fused MFMA kernel (tdc_fused.hip)
 struct TdcFusedGeom {
@@ -72,14 +80,14 @@ bool tdc_fused_unit_supported(int mb1, int mb2, int mb3, int pb);
 TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit);
 hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
-                            const float *uout_p, float *y);
+                            const float *uout_p, float *y, const TdcEpi &epi);
 
 // ---- fused MFMA kernel with stages 2 and 3 chained in registers (tdc_chain.hip)
 bool tdc_chain_supported(int nb2, int mb1, int pb);
 TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit);
 hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
-                            const float *uout_p, float *y);
+                            const float *uout_p, float *y, const TdcEpi &epi);
 
 // ---- one-launch kernel: stage 1 into LDS, then the merged stage-2/3 convolution (tdc_fm.hip).
 // Tuning fields: tile_h, tile_w, waves[0], mb[0] = stage-1 register tile, mb[1] = output-channel
@@ -87,7 +95,7 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
 bool tdc_fm_supported(const TdcDims &d, int tile_h, int tile_w, int nw, int mb1, int nbg);
 TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int nbg);
 hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s, const float *x,
-                         const float *uin_p, const float *wm_p, float *y);
+                         const float *uin_p, const float *wm_p, float *y, const TdcEpi &epi);
 
 // ---- selector (tdc_select.cpp): fills every zero field of `t`
 struct TdcDeviceInfo {

@@ -18,6 +18,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include "tdc_internal.h"
+
 typedef float tdc_f4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ tdc_f4 tdc_mfma(float a, float b, tdc_f4 c)
@@ -50,6 +52,15 @@ __device__ __forceinline__ tdc_f4 tdc_buf_load4(tdc_rsrc r, unsigned byte_off)
 {
     typedef unsigned u4 __attribute__((ext_vector_type(4)));
     return __builtin_bit_cast(tdc_f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+}
+
+// The optional epilogue on one output value: channel n, element index idx within y.  The branches
+// are wave-uniform; without an epilogue nothing is loaded.
+__device__ __forceinline__ float tdc_apply_epilogue(const TdcEpi &e, float v, int n, size_t idx)
+{
+    if (e.bias) v += e.bias[n];
+    if (e.residual) v += e.residual[idx];
+    return e.relu ? fmaxf(v, 0.f) : v;
 }
 
 // Division by a launch-time constant.  An integer division costs a lone wavefront some 300 cycles

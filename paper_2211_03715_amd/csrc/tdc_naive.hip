@@ -3,6 +3,7 @@
 // variant reads the caller's weight layouts directly and supports every valid shape; it is
 // the in-library yardstick the MFMA variants are measured against, not the fast path.
 #include "tdc_internal.h"
+#include "tdc_mfma.h"
 
 namespace {
 
@@ -11,7 +12,7 @@ constexpr int TPB = 256;   // threads per block
 
 // out[b][m][p] = sum_k in[b][k][p] * Wt[k][m]      (1x1 convolution; Eq. 2 and Eq. 4)
 __global__ __launch_bounds__(TPB) void naive_pointwise(const float *__restrict__ in, const float *__restrict__ Wt,
-                                                       float *__restrict__ out, int Kc, int M, int P)
+                                                       float *__restrict__ out, int Kc, int M, int P, TdcEpi epi)
 {
     const int p = blockIdx.x * TPB + threadIdx.x;
     const int m0 = blockIdx.y * OT;
@@ -29,7 +30,10 @@ __global__ __launch_bounds__(TPB) void naive_pointwise(const float *__restrict__
     }
 #pragma unroll
     for (int j = 0; j < OT; ++j)
-        if (m0 + j < M) out[((size_t)b * M + m0 + j) * P + p] = acc[j];
+        if (m0 + j < M) {
+            const size_t idx = ((size_t)b * M + m0 + j) * P + p;
+            out[idx] = tdc_apply_epilogue(epi, acc[j], m0 + j, idx);
+        }
 }
 
 // z2[b][d2][i][j] = sum_{d1,r,s} z1pad[b][d1][i*st+r-pad][j*st+s-pad] * core[d1][d2][r][s]      (Eq. 3)
@@ -70,14 +74,14 @@ __global__ __launch_bounds__(TPB) void naive_core(TdcDims d, const float *__rest
 }  // namespace
 
 hipError_t tdc_launch_naive(const TdcDims &d, hipStream_t s, const float *x, const float *U_in,
-                            const float *core, const float *U_out, float *z1, float *z2, float *y)
+                            const float *core, const float *U_out, float *z1, float *z2, float *y, const TdcEpi &epi)
 {
     const int HW = d.H * d.W, P = d.Ho * d.Wo;
     hipLaunchKernelGGL(naive_pointwise, dim3((HW + TPB - 1) / TPB, (d.R1 + OT - 1) / OT, d.B), dim3(TPB), 0, s,
-                       x, U_in, z1, d.C, d.R1, HW);
+                       x, U_in, z1, d.C, d.R1, HW, TdcEpi{nullptr, nullptr, 0});
     hipLaunchKernelGGL(naive_core, dim3((P + TPB - 1) / TPB, (d.R2 + OT - 1) / OT, d.B), dim3(TPB), 0, s,
                        d, z1, core, z2);
     hipLaunchKernelGGL(naive_pointwise, dim3((P + TPB - 1) / TPB, (d.N + OT - 1) / OT, d.B), dim3(TPB), 0, s,
-                       z2, U_out, y, d.R2, d.N, P);
+                       z2, U_out, y, d.R2, d.N, P, epi);
     return hipGetLastError();
 }

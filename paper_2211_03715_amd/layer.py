@@ -37,25 +37,35 @@ class TuckerConv2d:
         self._weights = (U_in, core, U_out)
         B.tdc_plan_pack_weights(self.plan, U_in, core, U_out, stream)
 
-    def __call__(self, x, y=None, weights=None, stream=None):
+    def __call__(self, x, y=None, weights=None, stream=None, bias=None, residual=None, relu=False):
+        """y = layer(x), optionally followed by the fused epilogue y = relu?(y + bias[n] + residual)."""
         import torch
         U_in, core, U_out = weights if weights is not None else self._weights
         if y is None:
             y = torch.empty((self.shape.batch, self.shape.N, self.Ho, self.Wo), device=x.device,
                             dtype=torch.float32)
-        B.tdc_conv_tucker2(self.plan, x, U_in, core, U_out, y, self.shape, stream)
+        if bias is None and residual is None and not relu:
+            B.tdc_conv_tucker2(self.plan, x, U_in, core, U_out, y, self.shape, stream)
+        else:
+            B.tdc_conv_tucker2_ex(self.plan, x, U_in, core, U_out, y, self.shape,
+                                  B.make_epilogue(bias, residual, relu), stream)
         return y
 
-    def bind(self, x, y, weights=None, stream=None):
-        """Marshal the arguments of tdc_conv_tucker2 once and return a zero-argument launcher.
+    def bind(self, x, y, weights=None, stream=None, bias=None, residual=None, relu=False):
+        """Marshal the arguments of tdc_conv_tucker2(_ex) once and return a zero-argument launcher.
 
         For callers that enqueue the same buffers repeatedly: the per-call cost is one foreign
         call.  The tensors and the stream must outlive the launcher."""
         U_in, core, U_out = weights if weights is not None else self._weights
-        fn = B.load().tdc_conv_tucker2
         vp = ctypes.c_void_p
         args = (self.plan, vp(B._stream(stream)), vp(x.data_ptr()), vp(U_in.data_ptr()), vp(core.data_ptr()),
                 vp(U_out.data_ptr()), vp(y.data_ptr()), ctypes.byref(self.shape))
+        if bias is None and residual is None and not relu:
+            fn = B.load().tdc_conv_tucker2
+        else:
+            fn = B.load().tdc_conv_tucker2_ex
+            epi = B.make_epilogue(bias, residual, relu)
+            args = args + (ctypes.byref(epi),)
 
         def launch():
             rc = fn(*args)
@@ -101,22 +111,30 @@ class DenseConv2d:
         self._W = W
         B.tdc_plan_pack_dense(self.plan, W, stream)
 
-    def __call__(self, x, y=None, W=None, stream=None):
+    def __call__(self, x, y=None, W=None, stream=None, bias=None, residual=None, relu=False):
         import torch
         W = W if W is not None else self._W
         if y is None:
             y = torch.empty((self.shape.batch, self.shape.N, self.Ho, self.Wo), device=x.device,
                             dtype=torch.float32)
-        B.tdc_conv_dense(self.plan, x, W, y, self.shape, stream)
+        if bias is None and residual is None and not relu:
+            B.tdc_conv_dense(self.plan, x, W, y, self.shape, stream)
+        else:
+            B.tdc_conv_dense_ex(self.plan, x, W, y, self.shape, B.make_epilogue(bias, residual, relu), stream)
         return y
 
-    def bind(self, x, y, W=None, stream=None):
-        """Zero-argument launcher with the arguments of tdc_conv_dense marshalled once."""
+    def bind(self, x, y, W=None, stream=None, bias=None, residual=None, relu=False):
+        """Zero-argument launcher with the arguments of tdc_conv_dense(_ex) marshalled once."""
         W = W if W is not None else self._W
-        fn = B.load().tdc_conv_dense
         vp = ctypes.c_void_p
         args = (self.plan, vp(B._stream(stream)), vp(x.data_ptr()), vp(W.data_ptr()), vp(y.data_ptr()),
                 ctypes.byref(self.shape))
+        if bias is None and residual is None and not relu:
+            fn = B.load().tdc_conv_dense
+        else:
+            fn = B.load().tdc_conv_dense_ex
+            epi = B.make_epilogue(bias, residual, relu)
+            args = args + (ctypes.byref(epi),)
 
         def launch():
             rc = fn(*args)

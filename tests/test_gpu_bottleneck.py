@@ -1,0 +1,56 @@
+"""A bottleneck block (dense 1x1 + Tucker 3x3 + dense 1x1, epilogues fused) against the oracle, eagerly
+and replayed from a HIP graph."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2211_03715_amd.bottleneck import TuckerBottleneck, make_block_weights
+from parity_util import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_block(orc, blk, w, x):
+    y1, _ = orc.conv_dense_with(orc.Shape(**blk.l1.asdict()), x, w["W1"].astype(np.float64))
+    t1 = orc.apply_epilogue(y1, w["b1"], None, True).astype(np.float32)        # the GPU stores t1, t2 in fp32
+    y2, _ = orc.conv_factored(orc.Shape(**blk.l2.asdict()), t1, w["U_in"], w["core"], w["U_out"])
+    t2 = orc.apply_epilogue(y2, w["b2"], None, True).astype(np.float32)
+    y3, _ = orc.conv_dense_with(orc.Shape(**blk.l3.asdict()), t2, w["W3"].astype(np.float64))
+    return orc.apply_epilogue(y3, w["b3"], x, True)
+
+
+@pytest.mark.parametrize("shape", [(1, 64, 16, 14, 14, 8, 8), (2, 48, 24, 9, 11, 16, 20), (1, 256, 64, 56, 56, 16, 16)],
+                         ids=lambda s: "b%d_c%d_m%d_%dx%d_r%d-%d" % s)
+def test_bottleneck_eager_and_graph(orc, shape):
+    import torch
+    batch, C, M, H, W, R1, R2 = shape
+    print("[case] bottleneck", shape, flush=True)
+    sys.stdout.flush()
+    w = make_block_weights(C, M, R1, R2, 11)
+    blk = TuckerBottleneck(batch, C, M, H, W, R1, R2, w)
+    try:
+        rng = np.random.default_rng(5)
+        xs = [rng.standard_normal((batch, C, H, W), dtype=np.float32) for _ in range(3)]
+        wants = [_oracle_block(orc, blk, w, x) for x in xs]
+        x_dev = torch.from_numpy(xs[0]).to(blk.dev)
+        got = blk(x_dev)
+        torch.cuda.synchronize()
+        assert_parity(got.cpu().numpy(), wants[0], "eager " + blk.describe())
+        # graph: captured once, replayed on new inputs, with eager work and synchronisations in between
+        x_static = torch.empty_like(x_dev)
+        graph = blk.capture(x_static)
+        for rep in range(2):
+            for x, want in zip(xs, wants):
+                x_static.copy_(torch.from_numpy(x).to(blk.dev))
+                blk.y.fill_(float("nan"))
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                assert_parity(blk.y.cpu().numpy(), want, "graph replay")
+                eager = blk(x_static).clone()                 # the same block, eagerly, between replays
+                torch.cuda.synchronize()
+                assert torch.equal(eager, blk.y)
+                assert_parity(eager.cpu().numpy(), want, "eager between replays")
+    finally:
+        blk.close()
