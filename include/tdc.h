@@ -217,6 +217,22 @@ typedef struct tdc_rank_choice {
 int tdc_select_ranks(const tdc_rank_layer *layers, int n_layers, double budget, double theta,
                      double tie_tol, tdc_rank_choice *out);
 
+/* Producer side of the format, HOST pointers, host only (paper section 4).
+ * tdc_hosvd_tucker2: the projection of a dense kernel W[C][N][K][K] onto Tucker ranks (R1, R2) by
+ * truncated HOSVD -- U_in[C][R1] = the R1 leading left singular vectors of the mode-1 matricization
+ * (C x N*K*K), U_out[R2][N] = the transposed R2 leading left singular vectors of the mode-2
+ * matricization (N x C*K*K), core[R1][R2][K][K] = W x_1 U_in^T x_2 U_out -- in the layouts
+ * tdc_conv_tucker2 takes, so a pretrained layer can be decomposed and run.  Singular vectors are
+ * determined up to sign; the sign that makes each vector's largest-magnitude component positive
+ * is returned.  Requires 1 <= R1 <= C, 1 <= R2 <= N.  Arithmetic in fp64, results rounded to fp32.
+ * tdc_admm_project: the two auxiliary updates of the ADMM training loop that need only that
+ * projection:  K_hat <- proj(K + M)  (the tensor of Tucker ranks (R1, R2), in W's layout) and, in
+ * place,  M <- M + K - K_hat.  The K update itself needs the training loss's gradient and is the
+ * caller's.  Cost is O(C^3 + N^3 + C*N*K*K*(C + N)) per call, meant to run offline. */
+int tdc_hosvd_tucker2(const float *W, int C, int N, int K, int R1, int R2,
+                      float *U_in, float *core, float *U_out);
+int tdc_admm_project(const float *K_weights, float *M, int C, int N, int K, int R1, int R2, float *K_hat);
+
 /* Output size rule used everywhere: floor((in + 2*pad - K)/stride) + 1; returns 0 on bad input. */
 int tdc_out_size(int in, int K, int stride, int pad);
 

@@ -31,7 +31,7 @@ EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", 
            "tdc_plan_destroy", "tdc_plan_get_tuning", "tdc_plan_describe", "tdc_plan_workspace_bytes",
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
            "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks",
-           "tdc_conv_tucker2_ex", "tdc_conv_dense_ex"]
+           "tdc_conv_tucker2_ex", "tdc_conv_dense_ex", "tdc_hosvd_tucker2", "tdc_admm_project"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -127,6 +127,11 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_select_ranks.argtypes = [ctypes.POINTER(tdc_rank_layer), ip, ctypes.c_double, ctypes.c_double,
                                      ctypes.c_double, ctypes.POINTER(tdc_rank_choice)]
     lib.tdc_select_ranks.restype = ip
+    fp = ctypes.POINTER(ctypes.c_float)
+    lib.tdc_hosvd_tucker2.argtypes = [fp, ip, ip, ip, ip, ip, fp, fp, fp]
+    lib.tdc_hosvd_tucker2.restype = ip
+    lib.tdc_admm_project.argtypes = [fp, fp, ip, ip, ip, ip, ip, fp]
+    lib.tdc_admm_project.restype = ip
     if path is None:
         _lib = lib
     return lib
@@ -307,3 +312,43 @@ def tdc_select_ranks(layers, tables, dense_latency, budget: float, theta: float 
         raise TdcError(rc, "tdc_select_ranks")
     return [{"decomposed": bool(o.decomposed), "R1": o.R1, "R2": o.R2, "latency_us": o.latency_us, "macs": o.macs}
             for o in out]
+
+
+def _host_f32(a, shape=None):
+    import numpy as np
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if shape is not None and a.shape != tuple(shape):
+        raise ValueError("expected shape %s, got %s" % (tuple(shape), a.shape))
+    return a
+
+
+def tdc_hosvd_tucker2(W, R1: int, R2: int):
+    """W: numpy float32 [C][N][K][K] on the host.  Returns (U_in [C][R1], core [R1][R2][K][K], U_out [R2][N])."""
+    import numpy as np
+    W = _host_f32(W)
+    if W.ndim != 4 or W.shape[2] != W.shape[3]:
+        raise ValueError("W must be [C][N][K][K]")
+    C, N, K, _ = W.shape
+    U_in = np.empty((C, max(R1, 1)), dtype=np.float32)
+    core = np.empty((max(R1, 1), max(R2, 1), K, K), dtype=np.float32)
+    U_out = np.empty((max(R2, 1), N), dtype=np.float32)
+    fp = ctypes.POINTER(ctypes.c_float)
+    rc = load().tdc_hosvd_tucker2(W.ctypes.data_as(fp), C, N, K, R1, R2, U_in.ctypes.data_as(fp), core.ctypes.data_as(fp),
+                                  U_out.ctypes.data_as(fp))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_hosvd_tucker2")
+    return U_in, core, U_out
+
+
+def tdc_admm_project(K_weights, M, R1: int, R2: int):
+    """K_hat <- proj(K + M), M <- M + K - K_hat.  numpy float32 [C][N][K][K] on the host; returns (K_hat, M_new)."""
+    import numpy as np
+    Kw = _host_f32(K_weights)
+    Mn = _host_f32(M, Kw.shape).copy()
+    C, N, K, _ = Kw.shape
+    K_hat = np.empty_like(Kw)
+    fp = ctypes.POINTER(ctypes.c_float)
+    rc = load().tdc_admm_project(Kw.ctypes.data_as(fp), Mn.ctypes.data_as(fp), C, N, K, R1, R2, K_hat.ctypes.data_as(fp))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_admm_project")
+    return K_hat, Mn

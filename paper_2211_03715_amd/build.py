@@ -13,7 +13,7 @@ OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libtdc.so")
 
 SOURCES = ["tdc_api.hip", "tdc_pack.hip", "tdc_naive.hip", "tdc_gemm.hip", "tdc_fused.hip", "tdc_chain.hip",
-           "tdc_fm.hip", "tdc_select.cpp", "tdc_ranks.cpp"]
+           "tdc_fm.hip", "tdc_select.cpp", "tdc_ranks.cpp", "tdc_hosvd.cpp"]
 
 # Packed-fp32 VALU instructions are switched off for every device translation unit.
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
