@@ -37,10 +37,10 @@ if ROOT not in sys.path:
 # device copy (FETCH_SIZE under-reads 2.0x on this machine, WRITE_SIZE is exact): (fetched, written) KiB,
 # keyed by layer name and the variant that was profiled.
 MEASURED_TRAFFIC = {
-    ("b1_c64_n64_56x56_r16-16_k3_s1_p1", "fused-merged"): (5777.3, 784.0),
-    ("b1_c128_n128_28x28_r32-32_k3_s1_p1", "fused-merged"): (4540.4, 784.0),
-    ("b1_c256_n256_14x14_r64-64_k3_s1_p1", "merged"): (1050.9 + 1047.9, 57.0 + 196.0),
-    ("b1_c512_n512_7x7_r128-128_k3_s1_p1", "merged"): (1099.9 + 2579.7, 24.5 + 98.0),
+    ("b1_c64_n64_56x56_r16-16_k3_s1_p1", "fused-merged"): (5796.2, 784.0),
+    ("b1_c128_n128_28x28_r32-32_k3_s1_p1", "fused-merged"): (4554.4, 784.0),
+    ("b1_c256_n256_14x14_r64-64_k3_s1_p1", "merged"): (1090.9 + 1047.9, 49.0 + 196.0),
+    ("b1_c512_n512_7x7_r128-128_k3_s1_p1", "merged"): (1118.8 + 2579.7, 24.5 + 98.0),
 }
 
 
@@ -114,7 +114,7 @@ def oracle_layer_times(L, inp, budget_s=1.5):
     return out
 
 
-def cpu_baseline(layers, inputs, budget_s=12.0, max_sweeps=400):
+def cpu_baseline(layers, inputs, budget_s=12.0, max_sweeps=100000):
     """The oracle as it stands (three-stage, Eqs. 2-4, fp64 accumulation, OpenMP over output channels)."""
     from oracle import tdc_oracle as orc
     from paper_2211_03715_amd import roofline as R

@@ -39,13 +39,14 @@ struct FusedCoef {
 
 // One GEMM launch of SPLIT, MERGED or DENSE.  Fitted to ~2500 stage tunings of the batch-1 layers
 // (median relative error 5%, the picked tuning within 10% of the best one timed): a launch
-// costs ~2.4 us however small; a k-group ~0.065 us of issue per wavefront plus its MFMAs; the K x K
+// costs ~2.2 us however small plus 0.05 us per wavefront of its workgroups; a k-group ~0.065 us of issue per wavefront plus its MFMAs; the K x K
 // stage pays for its gathered activation loads per pixel block; and the activation operand is
 // re-read by every output-channel group, which is what makes taller register tiles (mb > 1) pay
 // once there are many channel blocks -- charged as k-group loads per CU over the whole launch,
 // more per load for a strided gather.
 struct StageCoef {
-    double launch = 2.35;
+    double launch = 2.15;
+    double wave = 0.05;           // per wavefront of the workgroup (dispatch, partial-sum traffic)
     double kg = 0.0649, mfma = 0.0785;
     double conv_b = 0.0255;       // K x K stage: per k-group and pixel block of the register tile
     double reduce = 0.3158;       // cross-wavefront sum through LDS, per 16x16 block of the tile
@@ -121,15 +122,18 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 // groups: rounds23 * (KG2 * (kg + blk2 * NB2*PB*share) + NB3 * (nb + blk3 * NB2*PB*share)).  This
 // variant serves the throughput regime, so the estimate also charges the bytes a CU pulls and
 // pushes (input tile incl. halo, output tile) and the scalar-store path taken when tile or image
-// width is not a multiple of 4.  Fitted to ~4700 tunings (median relative error 12%).
+// width is not a multiple of 4, and the number of output row segments a CU writes (tiles that span
+// whole image rows store longer runs).  Fitted to ~2600 tunings of the batch-8/32 layers (median
+// relative error 11%).
 struct ChainCoef {
-    double launch = 2.9589;
-    double s1_unit = 0.4462, s1_kg = 0.1433, s1_mfma = 0.0401;
-    double kg2_glb = 0.1780, blk2 = 0.0202;
-    double nb3_lds = 0.0671, blk3 = 0.0190;
-    double w_kb = 0.0552;
-    double x_mb = 45.4569, y_mb = 76.1014;   // per MB per CU
-    double novec = 0.2232;                   // per output-channel block and pixel block stored with 4-byte stores
+    double launch = 1.0626;
+    double s1_unit = 0.0, s1_kg = 0.2896, s1_mfma = 0.1063;
+    double kg2_glb = 0.1124, blk2 = 0.0;
+    double nb3_lds = 0.1759, blk3 = 0.0475;
+    double w_kb = 0.0431;
+    double x_mb = 11.5236, y_mb = 13.0568;   // per MB per CU
+    double y_rows = 4.2918;                  // per 1000 output row segments (tile rows x channels) per CU
+    double novec = 0.2391;                   // per output-channel block and pixel block stored with 4-byte stores
 };
 
 double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw, int mb1,
@@ -150,7 +154,7 @@ double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, 
     t += r23 * (KG2 * ((wl ? 0.0 : c.kg2_glb) + c.blk2 * d.NB2 * pb * share) +
                 d.NB3 * ((wl ? c.nb3_lds : 0.0) + c.blk3 * d.NB2 * pb * share + (vec ? 0.0 : c.novec * pb)));
     t += c.w_kb * w_kb * per_cu;
-    t += per_cu * (c.x_mb * g.QB * 16.0 * d.C * 4e-6 + c.y_mb * g.PBk * 16.0 * d.N * 4e-6);
+    t += per_cu * (c.x_mb * g.QB * 16.0 * d.C * 4e-6 + c.y_mb * g.PBk * 16.0 * d.N * 4e-6 + c.y_rows * g.TH * d.N * 1e-3);
     return c.launch + rounds * t;
 }
 
@@ -293,7 +297,7 @@ StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n
                 const double act_loads = (double)batch * (n_mblocks / mb) * n_pblocks * kgroups / dev.cus;
                 const double us = c.launch +
                                   rounds * (kgw * (c.kg + c.mfma * mb * pb * share + (conv_stride ? c.conv_b * pb : 0.0)) +
-                                            (nw > 1 ? c.reduce * mb * pb : 0.0)) +
+                                            (nw > 1 ? c.reduce * mb * pb : 0.0) + c.wave * nw) +
                                   act_loads * (conv_stride ? c.act_conv * conv_stride : c.act_1x1);
                 if (us < best.us) {
                     best.us = us;
@@ -386,7 +390,7 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     // regime, where their extra MACs cost nothing and the saved launches count.  The one-launch
     // form's estimate is optimistic once the contraction is cut into three or more slices, so it
     // has to win by a margin, and only tunings inside its calibrated region are considered.
-    if (forced.variant == TDC_VARIANT_AUTO && !pixels_fill_chip && d.stride == 1) {   // calibrated at stride 1 only
+    if (forced.variant == TDC_VARIANT_AUTO && !pixels_fill_chip) {
         const StageChoice m2 = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1], forced.pb[1],
                                           forced.waves[1], d.stride);
         tdc_tuning free_choice = forced;
