@@ -47,7 +47,7 @@ struct GemmArgs {
     int pg_major;        // order of the logical workgroup ids, see tdc_logical_block
     int H, W, Wo, K, stride, pad;   // stage 2 geometry
     int kg_q, kg_r;      // KG = waves * kg_q + kg_r: the first kg_r wavefronts take kg_q + 1 k-groups
-    TdcDiv div_inner, div_Wo, div_NBk, div_K;   // launch-time constant divisors (see tdc_mfma.h)
+    TdcDiv div_inner, div_Wo, div_NBk, div_K;   // launch-time constant divisors (see tdc_div.h)
 };
 
 // Workgroups are dealt to the chip's 8 XCDs round-robin by blockIdx.x, and every XCD has its own

@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include "tdc_internal.h"
+#include "tdc_div.h"
 
 typedef float tdc_f4 __attribute__((ext_vector_type(4)));
 
@@ -63,31 +64,9 @@ __device__ __forceinline__ float tdc_apply_epilogue(const TdcEpi &e, float v, in
     return e.relu ? fmaxf(v, 0.f) : v;
 }
 
-// Division by a launch-time constant.  An integer division costs a lone wavefront some 300 cycles
-// (a dependent chain of ~25 VALU instructions), and a kernel prologue here has half a dozen of
-// them between its first instruction and its first load: at microsecond kernel durations that is
-// measurable (0.15 us each).  The host precomputes a multiplier instead (Granlund & Montgomery):
-//   m = floor(2^32 * (2^L - d) / d) + 1,  L = ceil(log2 d),  q = (t + ((x - t) >> min(L,1))) >> max(L-1,0),
-//   t = mulhi(m, x); exact for every 0 <= x < 2^32 and 1 <= d < 2^31.
-struct TdcDiv {
-    unsigned m, sh1, sh2;
-};
-
-inline TdcDiv tdc_make_div(unsigned d)
-{
-    unsigned L = 0;
-    while ((1ull << L) < d) ++L;
-    TdcDiv r;
-    r.m = (unsigned)((((1ull << 32) * ((1ull << L) - d)) / d) + 1);
-    r.sh1 = L < 1 ? L : 1;
-    r.sh2 = L > 1 ? L - 1 : 0;
-    return r;
-}
-
 __device__ __forceinline__ int tdc_div(int x, const TdcDiv &d)
 {
-    const unsigned t = __umulhi(d.m, (unsigned)x);
-    return (int)((t + (((unsigned)x - t) >> d.sh1)) >> d.sh2);
+    return (int)tdc_div_from_hi((unsigned)x, __umulhi(d.m, (unsigned)x), d);
 }
 
 // acc[mb][pb] += A(mb, step j) * B(pb, step j) for the four steps of one k-group.  Successive

@@ -134,3 +134,47 @@ def test_selector_handles_the_dense_layer():
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError):
         B.load(str(tmp_path / "libtdc.so"))
+
+
+def test_constant_division_matches_integer_division(tmp_path):
+    """The kernels divide by launch-time constants with a precomputed multiplier (csrc/tdc_div.h).
+    A host program built from that header compares it with `/` for every divisor up to 4096 (and a
+    few large ones) on all dividends below 2^16, a dense band around every multiple of the divisor
+    near 2^31, and 2^20 pseudo-random 32-bit dividends."""
+    import shutil
+    import subprocess
+    cxx = shutil.which("g++")
+    assert cxx, "g++ is needed for this test"
+    src = tmp_path / "divcheck.cpp"
+    src.write_text(r'''
+#include <cstdio>
+#include <cstdint>
+#include "tdc_div.h"
+static int check(unsigned d, unsigned x, const TdcDiv &c) {
+    const unsigned t = (unsigned)(((uint64_t)c.m * x) >> 32);
+    if (tdc_div_from_hi(x, t, c) != x / d) { std::printf("d=%u x=%u\n", d, x); return 1; }
+    return 0;
+}
+int main() {
+    unsigned big[] = {4097u, 12345u, 65535u, 65536u, 65537u, 1000003u, 0x3fffffffu, 0x40000000u, 0x7fffffffu};
+    uint64_t bad = 0, n = 0;
+    for (unsigned i = 1; i <= 4096 + sizeof big / sizeof *big; ++i) {
+        const unsigned d = i <= 4096 ? i : big[i - 4097];
+        const TdcDiv c = tdc_make_div(d);
+        for (unsigned x = 0; x < 65536; ++x, ++n) bad += check(d, x, c);
+        const unsigned q = 0x80000000u / d;
+        for (unsigned k = (q > 2 ? q - 2 : 0); k <= q + 2; ++k)
+            for (int o = -2; o <= 2; ++o, ++n) bad += check(d, (unsigned)((uint64_t)k * d + o), c);
+        bad += check(d, 0xffffffffu, c) + check(d, 0x7fffffffu, c);
+        uint64_t s = 0x9e3779b97f4a7c15ull * d;
+        for (int r = 0; r < 256; ++r, ++n) { s = s * 6364136223846793005ull + 1442695040888963407ull; bad += check(d, (unsigned)(s >> 32), c); }
+    }
+    std::printf("checked %llu bad %llu\n", (unsigned long long)n, (unsigned long long)bad);
+    return bad != 0;
+}
+''')
+    exe = tmp_path / "divcheck"
+    inc = os.path.join(os.path.dirname(B.__file__), "csrc")
+    subprocess.run([cxx, "-O2", "-I", inc, str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout[-2000:]
