@@ -69,7 +69,7 @@ def _time_sync(fn, iters, torch):
 
 def _time_cold(conv, L, x, torch, min_bytes=512 << 20, max_sets=2048):
     """Seconds per call when every call reads and writes buffers no earlier call of the pass touched."""
-    y_shape = (L.batch, L.N, conv.Ho, conv.Wo)
+    y_shape = conv.out_shape()
     per_set = 4 * (x.numel() + L.batch * L.N * conv.Ho * conv.Wo)
     n_sets = max(2, min(max_sets, -(-min_bytes // per_set)))
     xs = [x.clone() for _ in range(n_sets)]
@@ -142,6 +142,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default: the ResNet-18-shaped sweep)")
     ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged"])
+    ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"],
+                    help="activation layout (default NCHW, the layout the metric's workload is stated in)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the per-layer oracle times")
     ap.add_argument("--brief", action="store_true",
                     help="only the queued latency per layer (no sync / cold-cache / dense-kernel columns)")
@@ -166,16 +168,17 @@ def main():
     variant = {"auto": B.VARIANT_AUTO, "naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT,
                "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN, "merged": B.VARIANT_MERGED}[args.variant]
 
+    layout = B.LAYOUT_NHWC if args.layout == "nhwc" else B.LAYOUT_NCHW
     layers = config_layers(args.config)
     host_inputs = [make_inputs(L, layer_seed(args.config, i)) for i, L in enumerate(layers)]
     convs, xs, ys = [], [], []
     for L, inp in zip(layers, host_inputs):
         t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
-        conv = TuckerConv2d(L, 0, B.make_tuning(variant=variant) if variant else None)
+        conv = TuckerConv2d(L, 0, B.make_tuning(variant=variant) if variant else None, layout=layout)
         conv.pack(t["U_in"], t["core"], t["U_out"])         # one-off re-layout, untimed (as in the paper)
         convs.append(conv)
-        xs.append(t["x"])
-        ys.append(torch.empty((L.batch, L.N, conv.Ho, conv.Wo), device=dev, dtype=torch.float32))
+        xs.append(t["x"].permute(0, 2, 3, 1).contiguous() if layout == B.LAYOUT_NHWC else t["x"])
+        ys.append(torch.empty(conv.out_shape(), device=dev, dtype=torch.float32))
     torch.cuda.synchronize()
 
     # arguments marshalled once; one foreign call per layer and step
@@ -215,7 +218,7 @@ def main():
             cold, n_sets = _time_cold(conv, L, xs[i], torch)
             row["cold_latency_us"], row["cold_buffer_sets"] = cold * 1e6, n_sets
             # the undecomposed layer on this library's own dense kernel (the t2 of the paper's threshold test)
-            dense = DenseConv2d(L, 0)
+            dense = DenseConv2d(L, 0, layout=layout)
             W = torch.from_numpy(make_dense_inputs(L, layer_seed(args.config, i) + 500)["W"]).to(dev)
             dense.pack(W)
             dl = dense.bind(xs[i], ys[i])
@@ -241,7 +244,7 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": R.flops(Ld) / sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    traffic = MEASURED_TRAFFIC.get((Ld.name(), pd["plan"].split(" ")[0]))
+    traffic = MEASURED_TRAFFIC.get((Ld.name(), pd["plan"].split(" ")[0])) if layout == B.LAYOUT_NCHW else None
     roof["traffic"] = None if traffic is None else (traffic[0] + traffic[1]) * 1024.0      # bytes per layer call
     roof["traffic_fetch_write_kib"] = traffic
     roof["algorithmic_bytes"] = R.bytes_compulsory(Ld)
@@ -260,7 +263,7 @@ def main():
             3: "rank sweep at C=N=256, 14x14, (R1,R2) in {8,16,32,64,128}^2, batch 1",
             4: "stride/batch variants: 128->256 s2 56->28 r32/64 and 128->128 28x28 r32, batch 1/8/32",
             5: "ResNet-50-style chain of 16 Tucker-2 3x3 layers, ranks round(0.3C) to 8, batch 1"}[args.config]),
-            "layers_per_step": len(layers), "variant": args.variant},
+            "layers_per_step": len(layers), "variant": args.variant, "layout": args.layout},
         "roofline": roof,
         "layers": per_layer,
         "null_launch_us": null_us,

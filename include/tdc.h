@@ -55,14 +55,18 @@ typedef enum tdc_status {
     TDC_ERR_BAD_TUNING = -7       /* a forced tuning does not fit the shape or the hardware   */
 } tdc_status;
 
-/* Layer geometry.  Supported domain: layout 0 (NCHW); square K in 1..7;
- * stride in 1..4; pad in 0..K-1; any positive batch, C, N, H, W, R1, R2 for which
- * every tensor has fewer than 2^31 elements. */
+/* Layer geometry.  Supported domain: square K in 1..7; stride in 1..4; pad in 0..K-1; any
+ * positive batch, C, N, H, W, R1, R2 for which every tensor has fewer than 2^31 elements.
+ * layout selects how the activations are stored: 0 = NCHW, x[batch][C][H][W] and
+ * y[batch][N][Ho][Wo]; 1 = NHWC, x[batch][H][W][C] and y[batch][Ho][Wo][N] (the pixel-major
+ * order the paper writes its tensors in, section 3); an epilogue's residual is laid out like y.
+ * NHWC moves channels four at a time: C and N must be multiples of 4 and x, y and the residual
+ * 16-byte aligned, else TDC_ERR_UNSUPPORTED.  Weights have one layout, whatever the activations'. */
 typedef struct tdc_shape {
     int32_t batch, C, N, H, W;
     int32_t R1, R2, K;
     int32_t stride, pad;
-    int32_t layout;               /* 0 = NCHW.  Other values: TDC_ERR_UNSUPPORTED */
+    int32_t layout;               /* 0 = NCHW, 1 = NHWC.  Other values: TDC_ERR_UNSUPPORTED */
 } tdc_shape;
 
 /* Kernel families the selector chooses between (section 5.5 of the paper picks tile

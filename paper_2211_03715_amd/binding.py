@@ -22,6 +22,7 @@ TDC_ERR_ALLOC = -5
 TDC_ERR_HIP = -6
 TDC_ERR_BAD_TUNING = -7
 
+LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN, VARIANT_DENSE, VARIANT_MERGED = 0, 1, 2, 3, 4, 5, 6
 VARIANT_FUSED_MERGED = 7
 VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense", 6: "merged", 7: "fused_merged"}

@@ -39,6 +39,12 @@ struct DeviceGuard {
     }
 };
 
+// NHWC kernels move x, y and the residual in 16-byte pieces
+bool misaligned16(const void *x, const void *y, const void *residual)
+{
+    return (((uintptr_t)x | (uintptr_t)y | (uintptr_t)residual) & 15u) != 0;
+}
+
 bool same_shape(const tdc_shape &a, const tdc_shape &b)
 {
     return a.batch == b.batch && a.C == b.C && a.N == b.N && a.H == b.H && a.W == b.W && a.R1 == b.R1 &&
@@ -50,7 +56,8 @@ int validate(const tdc_shape &s)
     if (s.batch < 1 || s.C < 1 || s.N < 1 || s.H < 1 || s.W < 1 || s.R1 < 1 || s.R2 < 1 || s.K < 1) return TDC_ERR_BAD_SHAPE;
     if (s.stride < 1 || s.pad < 0) return TDC_ERR_BAD_SHAPE;
     if ((long)s.H + 2L * s.pad < s.K || (long)s.W + 2L * s.pad < s.K) return TDC_ERR_BAD_SHAPE;
-    if (s.layout != 0) return TDC_ERR_UNSUPPORTED;
+    if (s.layout != 0 && s.layout != 1) return TDC_ERR_UNSUPPORTED;
+    if (s.layout == 1 && (s.C % 4 || s.N % 4)) return TDC_ERR_UNSUPPORTED;   // NHWC moves channels four at a time
     if (s.K > 7 || s.stride > 4 || s.pad > s.K - 1) return TDC_ERR_UNSUPPORTED;
     const long Ho = tdc_out_size(s.H, s.K, s.stride, s.pad), Wo = tdc_out_size(s.W, s.K, s.stride, s.pad);
     const long lim = 0x7fffffffL;
@@ -88,6 +95,7 @@ TdcDims make_dims(const tdc_shape &s)
     d.Wo = tdc_out_size(s.W, s.K, s.stride, s.pad);
     d.NB1 = (s.R1 + 15) / 16; d.NB2 = (s.R2 + 15) / 16; d.NB3 = (s.N + 15) / 16;
     d.KG1 = (s.C + 15) / 16;
+    d.nhwc = s.layout == 1;
     return d;
 }
 
@@ -367,6 +375,7 @@ int tdc_conv_tucker2_ex(tdc_plan *p, void *hip_stream, const float *x, const flo
     const TdcEpi epi = epilogue ? TdcEpi{epilogue->bias, epilogue->residual, epilogue->relu} : TdcEpi{nullptr, nullptr, 0};
     if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
     if (p->tuning.variant == TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
+    if (p->dims.nhwc && misaligned16(x, y, epi.residual)) return TDC_ERR_UNSUPPORTED;
     DeviceGuard guard(p->device);
     if (!guard.ok) return TDC_ERR_HIP;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -421,6 +430,7 @@ int tdc_conv_dense_ex(tdc_plan *p, void *hip_stream, const float *x, const float
     const TdcEpi epi = epilogue ? TdcEpi{epilogue->bias, epilogue->residual, epilogue->relu} : TdcEpi{nullptr, nullptr, 0};
     if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
     if (p->tuning.variant != TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
+    if (p->dims.nhwc && misaligned16(x, y, epi.residual)) return TDC_ERR_UNSUPPORTED;
     DeviceGuard guard(p->device);
     if (!guard.ok) return TDC_ERR_HIP;
     hipStream_t s = (hipStream_t)hip_stream;

@@ -10,7 +10,9 @@
 //   - stage 3 runs with the MFMA operands swapped, D = z2^T U_out, which leaves each lane with
 //     four consecutive PIXELS of one output channel: y is written with one 16-byte buffer store
 //     per lane instead of four 4-byte stores of four channels (scalar stores when the tile or
-//     image width is not a multiple of 4).
+//     image width is not a multiple of 4).  With NHWC activations (template flag) the operands
+//     stay unswapped instead: a lane then holds four consecutive CHANNELS of one pixel, which is
+//     the 16-byte store of that layout, and stage 1 reads x with one 16-byte load per lane.
 //
 // The paper's kernel keeps one output channel per thread and the R x S weights of the current
 // input channel in registers (section 5.2); here the register-resident object is the whole
@@ -48,7 +50,7 @@ __device__ __forceinline__ void tdc_buf_store4(tdc_rsrc r, unsigned byte_off, td
 
 // Stage 1 (Eq. 2) for the whole workgroup: z1 tile = U_in^T x into LDS cells.  `prefetched`
 // says that `pipe` already holds the first buffer of unit `wave` (issued before the weight copy).
-template <int MB1, int PB>
+template <int MB1, int PB, bool NHWC>
 struct ChainStage1 {
     const ChainArgs &a;
     tdc_rsrc xrs, urs;
@@ -67,7 +69,7 @@ struct ChainStage1 {
             const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
             const int h = h0 + qh, w = w0 + qw;
             const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
-            xoff[pb] = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
+            xoff[pb] = ok ? (unsigned)(h * a.W + w) * (NHWC ? 4u * a.C : 4u) : TDC_OOB;
         }
     }
     __device__ __forceinline__ void operator()(tdc_f4 (&av)[MB1], tdc_f4 (&bv)[PB])
@@ -76,26 +78,33 @@ struct ChainStage1 {
 #pragma unroll
         for (int mb = 0; mb < MB1; ++mb)
             av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
-        // channels past C lie beyond the descriptor and read as 0 by themselves
-        const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
+        if (NHWC) {
+            const int c = 16 * kg + 4 * g;
+            const unsigned cbad = c < a.C ? dead : TDC_OOB;
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-            const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
-            bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
-                              tdc_buf_load(xrs, o + 12u * HW)};
+            for (int pb = 0; pb < PB; ++pb) bv[pb] = tdc_buf_load4(xrs, (xoff[pb] + 4u * c) | cbad | (xoff[pb] & TDC_OOB));
+        } else {
+            // channels past C lie beyond the descriptor and read as 0 by themselves
+            const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) {
+                const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
+                bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
+                                  tdc_buf_load(xrs, o + 12u * HW)};
+            }
         }
         ++kg;
     }
 };
 
-template <int MB1, int PB>
+template <int MB1, int PB, bool NHWC>
 __device__ __forceinline__ void chain_stage1(const ChainArgs &a, tdc_f4 *__restrict__ z1s, int lane, int wave, int nw,
                                              int b, int h0, int w0, const tdc_f4 *__restrict__ wsrc_core,
                                              tdc_f4 *__restrict__ wC, tdc_f4 *__restrict__ wO, bool copy_weights)
 {
     constexpr int U = 4;
     const int HW = a.H * a.W;
-    ChainStage1<MB1, PB> next{a};
+    ChainStage1<MB1, PB, NHWC> next{a};
     next.xrs = tdc_make_rsrc(a.x + (size_t)b * a.C * HW, (unsigned)a.C * HW * 4u);
     next.urs = tdc_make_rsrc(a.uin_p, (unsigned)a.NB1 * a.KG1 * 1024u);
     next.lane = lane; next.g = lane >> 4; next.l16 = lane & 15;
@@ -143,7 +152,7 @@ __device__ __forceinline__ void chain_stage1(const ChainArgs &a, tdc_f4 *__restr
     }
 }
 
-template <int NB2, int PB, bool WLDS>
+template <int NB2, int PB, bool WLDS, bool NHWC>
 __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
 {
     extern __shared__ tdc_f4 lds4[];
@@ -162,9 +171,9 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
         const tdc_f4 *core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
-        if (a.mb1 == 4) chain_stage1<4, PB>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
-        else if (a.mb1 == 2) chain_stage1<2, PB>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
-        else chain_stage1<1, PB>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
+        if (a.mb1 == 4) chain_stage1<4, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
+        else if (a.mb1 == 2) chain_stage1<2, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
+        else chain_stage1<1, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
     }
     TDC_PROBE(3);
     __syncthreads();
@@ -216,10 +225,12 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
             pipe.start(next);
             pipe.run(acc2, KG2, next);
         }
-        // ---- stage 3: D[pixel 4*g + i][channel l16] = sum_d2 z2[d2][pixel] * U_out[d2][channel]
-        unsigned yq[PB][4];      // byte offset of pixel 4*g + i of block pb in one channel plane, or TDC_OOB
+        // ---- stage 3.  NCHW: D[pixel 4*g + i][channel l16] = sum_d2 z2[d2][pixel] * U_out[d2][channel];
+        //      NHWC: D[channel 4*g + i][pixel l16], the same products with the operands unswapped
+        unsigned yq[PB][4];      // NCHW: byte offset of pixel 4*g + i of block pb in one channel plane, or TDC_OOB
+        int ypix[PB];            // NHWC: index of pixel l16 of block pb in the output image, or -1
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
+        for (int pb = 0; pb < PB; ++pb) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int p = 16 * (pg * PB + pb) + 4 * g + i;
@@ -227,6 +238,11 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
                 const int oi = i0 + ph, oj = j0 + pw;
                 yq[pb][i] = (p < a.P && oi < a.Ho && oj < a.Wo) ? (unsigned)(oi * a.Wo + oj) * 4u : TDC_OOB;
             }
+            const int p = 16 * (pg * PB + pb) + l16;
+            const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
+            const int oi = i0 + ph, oj = j0 + pw;
+            ypix[pb] = (p < a.P && oi < a.Ho && oj < a.Wo) ? oi * a.Wo + oj : -1;
+        }
         tdc_f4 ua[2][NB2];
         const auto fetch = [&](int nb, tdc_f4(&u)[NB2]) {
             const bool live = nb < a.NB3;
@@ -246,7 +262,16 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int pb = 0; pb < PB; ++pb) acc3[pb] = tdc_mfma(acc2[kg][pb][j], u[kg][j], acc3[pb]);
+                    for (int pb = 0; pb < PB; ++pb)
+                        acc3[pb] = NHWC ? tdc_mfma(u[kg][j], acc2[kg][pb][j], acc3[pb]) : tdc_mfma(acc2[kg][pb][j], u[kg][j], acc3[pb]);
+            if (NHWC) {
+                const int n = 16 * nb + 4 * g;
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb)
+                    if (ypix[pb] >= 0 && n < a.N)
+                        tdc_store_nhwc(a.y, a.epi, acc3[pb], n, ((size_t)b * P2 + ypix[pb]) * a.N + n);
+                return;
+            }
             // channels past N lie beyond the descriptor: the hardware drops those stores
             const unsigned plane = (unsigned)(16 * nb + l16) * P2 * 4u;
             if (a.epi.bias || a.epi.residual || a.epi.relu) {
@@ -339,27 +364,32 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
     a.div_TW = tdc_make_div((unsigned)g.TW); a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
-#define TDC_LAUNCH(N_, P_, W_)                                                                         \
+#define TDC_LAUNCH(N_, P_, W_, L_)                                                                     \
     {                                                                                                  \
         if (g.lds_bytes > 48 * 1024) {                                                                 \
-            hipError_t e = hipFuncSetAttribute((const void *)tdc_chain_kernel<N_, P_, W_>,             \
+            hipError_t e = hipFuncSetAttribute((const void *)tdc_chain_kernel<N_, P_, W_, L_>,         \
                                                hipFuncAttributeMaxDynamicSharedMemorySize,             \
                                                (int)g.lds_bytes);                                      \
             if (e != hipSuccess) return e;                                                             \
         }                                                                                              \
-        hipLaunchKernelGGL((tdc_chain_kernel<N_, P_, W_>), grid, block, g.lds_bytes, s, a);            \
+        hipLaunchKernelGGL((tdc_chain_kernel<N_, P_, W_, L_>), grid, block, g.lds_bytes, s, a);        \
         return hipGetLastError();                                                                      \
+    }
+#define TDC_LAYOUT(N_, P_, W_)                                                                         \
+    {                                                                                                  \
+        if (d.nhwc) TDC_LAUNCH(N_, P_, W_, true) else TDC_LAUNCH(N_, P_, W_, false)                    \
     }
 #define TDC_X(N_)                                                                                      \
     if (d.NB2 == N_) {                                                                                 \
         if (t.pb[0] == 1) {                                                                            \
-            if (g.weights_in_lds) TDC_LAUNCH(N_, 1, true) else TDC_LAUNCH(N_, 1, false)                \
+            if (g.weights_in_lds) TDC_LAYOUT(N_, 1, true) else TDC_LAYOUT(N_, 1, false)                \
         } else {                                                                                       \
-            if (g.weights_in_lds) TDC_LAUNCH(N_, 2, true) else TDC_LAUNCH(N_, 2, false)                \
+            if (g.weights_in_lds) TDC_LAYOUT(N_, 2, true) else TDC_LAYOUT(N_, 2, false)                \
         }                                                                                              \
     }
     TDC_CHAIN_NB2(TDC_X)
 #undef TDC_X
+#undef TDC_LAYOUT
 #undef TDC_LAUNCH
     return hipErrorInvalidValue;
 }

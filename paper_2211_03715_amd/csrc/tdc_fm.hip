@@ -38,7 +38,7 @@ struct FmArgs {
     TdcDiv div_tiles, div_tiles_x, div_NBG, div_QB, div_QW, div_TW, div_NB1, div_K;   // constant divisors
 };
 
-template <int MB1, int PBK>
+template <int MB1, int PBK, bool NHWC>
 __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
 {
     extern __shared__ tdc_f4 lds4[];
@@ -80,17 +80,22 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
             const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
             const int h = h0 + qh, w = w0 + qw;
             const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
-            xoff = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
+            xoff = ok ? (unsigned)(h * a.W + w) * (NHWC ? 4u * a.C : 4u) : TDC_OOB;
         };
         auto next = [&](tdc_f4(&av)[MB1], tdc_f4(&bv)[1]) {
             const unsigned dead = kg < a.KG1 ? 0u : TDC_OOB;
 #pragma unroll
             for (int mb = 0; mb < MB1; ++mb)
                 av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
-            // channels past C lie beyond the descriptor and read as 0 by themselves
-            const unsigned o = ((unsigned)(16 * kg + 4 * g) * HW * 4u + xoff) | dead | (xoff & TDC_OOB);
-            bv[0] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
-                             tdc_buf_load(xrs, o + 12u * HW)};
+            if (NHWC) {
+                const int c = 16 * kg + 4 * g;
+                bv[0] = tdc_buf_load4(xrs, (xoff + 4u * c) | (c < a.C ? dead : TDC_OOB) | (xoff & TDC_OOB));
+            } else {
+                // channels past C lie beyond the descriptor and read as 0 by themselves
+                const unsigned o = ((unsigned)(16 * kg + 4 * g) * HW * 4u + xoff) | dead | (xoff & TDC_OOB);
+                bv[0] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
+                                 tdc_buf_load(xrs, o + 12u * HW)};
+            }
             ++kg;
         };
         TdcPipe<MB1, 1, U> pipe;
@@ -169,6 +174,11 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
             const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
             const int i = i0 + ph, j = j0 + pw;
             if (p < a.P && i < a.Ho && j < a.Wo) {
+                if (NHWC) {
+                    const int n = 16 * nb + 4 * g;
+                    if (n < a.N) tdc_store_nhwc(a.y, a.epi, acc[pb], n, ((size_t)b * P2 + i * a.Wo + j) * a.N + n);
+                    continue;
+                }
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int n = 16 * nb + 4 * g + c;
@@ -198,6 +208,11 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
         const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
         const int i = i0 + ph, j = j0 + pw;
         if (p < a.P && i < a.Ho && j < a.Wo) {
+            if (NHWC) {
+                const int n = 16 * (ng * a.NBG + blk) + 4 * (ln >> 4);
+                if (n < a.N) tdc_store_nhwc(a.y, a.epi, sum, n, ((size_t)b * P2 + i * a.Wo + j) * a.N + n);
+                continue;
+            }
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int n = 16 * (ng * a.NBG + blk) + 4 * (ln >> 4) + c;
@@ -265,20 +280,25 @@ hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGe
     a.div_QW = tdc_make_div((unsigned)a.QW); a.div_TW = tdc_make_div((unsigned)a.TW);
     a.div_NB1 = tdc_make_div((unsigned)a.NB1); a.div_K = tdc_make_div((unsigned)a.K);
     dim3 grid((unsigned)(a.tiles * (d.NB3 / a.NBG)), (unsigned)d.B), block(64 * t.waves[0]);
-#define TDC_FM_CASE(M_, P_)                                                                        \
-    if (t.mb[0] == M_ && g.PBk == P_) {                                                            \
+#define TDC_FM_LAUNCH(M_, P_, L_)                                                                  \
+    {                                                                                              \
         if (g.lds_bytes > 48 * 1024) {                                                             \
-            hipError_t e = hipFuncSetAttribute((const void *)tdc_fm_kernel<M_, P_>,                \
+            hipError_t e = hipFuncSetAttribute((const void *)tdc_fm_kernel<M_, P_, L_>,            \
                                                hipFuncAttributeMaxDynamicSharedMemorySize,         \
                                                (int)g.lds_bytes);                                  \
             if (e != hipSuccess) return e;                                                         \
         }                                                                                          \
-        hipLaunchKernelGGL((tdc_fm_kernel<M_, P_>), grid, block, g.lds_bytes, s, a);               \
+        hipLaunchKernelGGL((tdc_fm_kernel<M_, P_, L_>), grid, block, g.lds_bytes, s, a);           \
         return hipGetLastError();                                                                  \
+    }
+#define TDC_FM_CASE(M_, P_)                                                                        \
+    if (t.mb[0] == M_ && g.PBk == P_) {                                                            \
+        if (d.nhwc) TDC_FM_LAUNCH(M_, P_, true) else TDC_FM_LAUNCH(M_, P_, false)                  \
     }
     TDC_FM_CASE(1, 1) TDC_FM_CASE(1, 2) TDC_FM_CASE(1, 3) TDC_FM_CASE(1, 4)
     TDC_FM_CASE(2, 1) TDC_FM_CASE(2, 2) TDC_FM_CASE(2, 3) TDC_FM_CASE(2, 4)
     TDC_FM_CASE(4, 1) TDC_FM_CASE(4, 2) TDC_FM_CASE(4, 3) TDC_FM_CASE(4, 4)
 #undef TDC_FM_CASE
+#undef TDC_FM_LAUNCH
     return hipErrorInvalidValue;
 }

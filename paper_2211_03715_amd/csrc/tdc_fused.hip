@@ -2,8 +2,9 @@
 // TH x TW tile of output pixels of one image, and the intermediates never leave the CU.
 //
 //   stage 1  z1 tile (R1P channels x the QH x QW input tile incl. the K-1 halo) = U_in^T x,
-//            x read straight from HBM/L2 into MFMA B operands (each wavefront reads a
-//            16-pixel run of one channel row per lane group, contiguous in NCHW), result to LDS.
+//            x read straight from HBM/L2 into MFMA B operands (NCHW: each wavefront reads a
+//            16-pixel run of one channel row per lane group with 4-byte loads; NHWC, template
+//            flag: a lane's four channels of its pixel are one 16-byte load), result to LDS.
 //            Pixels of the halo that lie outside the image read x = 0, which is the zero
 //            padding of the core convolution because stage 1 has no bias.
 //   stage 2  z2 tile (R2P x TH*TW) = core conv, an implicit GEMM over k = (tap, d1) whose B
@@ -49,7 +50,7 @@ struct FusedArgs {
 // exactly the B operand of the next stage for k-group cb (see tdc_mfma.h).
 __device__ __forceinline__ int tdc_cell(int cb, int g, int pitch, int col) { return (cb * 4 + g) * pitch + col; }
 
-template <int MB1, int MB2, int MB3, int PB, bool WLDS>
+template <int MB1, int MB2, int MB3, int PB, bool WLDS, bool NHWC>
 __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
 {
     extern __shared__ tdc_f4 lds4[];
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
                 const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
                 const int h = h0 + qh, w = w0 + qw;
                 const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
-                xoff[pb] = ok ? (unsigned)(h * a.W + w) * 4u : TDC_OOB;
+                xoff[pb] = ok ? (unsigned)(h * a.W + w) * (NHWC ? 4u * a.C : 4u) : TDC_OOB;
             }
         };
         auto next = [&](tdc_f4(&av)[MB1], tdc_f4(&bv)[PB]) {
@@ -94,13 +95,21 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
 #pragma unroll
             for (int mb = 0; mb < MB1; ++mb)
                 av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
-            // channels past C lie beyond the descriptor and read as 0 by themselves
-            const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
+            if (NHWC) {
+                const int c = 16 * kg + 4 * g;
+                const unsigned cbad = c < a.C ? dead : TDC_OOB;
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
-                bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
-                                  tdc_buf_load(xrs, o + 12u * HW)};
+                for (int pb = 0; pb < PB; ++pb)
+                    bv[pb] = tdc_buf_load4(xrs, (xoff[pb] + 4u * c) | cbad | (xoff[pb] & TDC_OOB));
+            } else {
+                // channels past C lie beyond the descriptor and read as 0 by themselves
+                const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb) {
+                    const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
+                    bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
+                                      tdc_buf_load(xrs, o + 12u * HW)};
+                }
             }
             ++kg;
         };
@@ -248,7 +257,13 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
 #pragma unroll
             for (int mb = 0; mb < MB3; ++mb)
 #pragma unroll
-                for (int pb = 0; pb < PB; ++pb)
+                for (int pb = 0; pb < PB; ++pb) {
+                    if (NHWC) {
+                        const int n = 16 * (mg * MB3 + mb) + 4 * g;
+                        if (ok[pb] && n < a.N)
+                            tdc_store_nhwc(a.y, a.epi, acc[mb][pb], n, ((size_t)b * P2 + yoff[pb]) * a.N + n);
+                        continue;
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int n = 16 * (mg * MB3 + mb) + 4 * g + i;
@@ -257,6 +272,7 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
                             yb[idx] = tdc_apply_epilogue(a.epi, acc[mb][pb][i], n, (size_t)b * a.N * P2 + idx);
                         }
                     }
+                }
         }
     }
     TDC_PROBE(7);
@@ -323,20 +339,24 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
     a.div_npg2 = tdc_make_div((unsigned)((g.PBk + t.pb[0] - 1) / t.pb[0]));
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
-#define TDC_LAUNCH(A_, B_, C_, D_, W_)                                                                 \
+#define TDC_LAUNCH(A_, B_, C_, D_, W_, L_)                                                             \
     {                                                                                                  \
         if (g.lds_bytes > 48 * 1024) {                                                                 \
-            hipError_t e = hipFuncSetAttribute((const void *)tdc_fused_kernel<A_, B_, C_, D_, W_>,     \
+            hipError_t e = hipFuncSetAttribute((const void *)tdc_fused_kernel<A_, B_, C_, D_, W_, L_>, \
                                                hipFuncAttributeMaxDynamicSharedMemorySize,             \
                                                (int)g.lds_bytes);                                      \
             if (e != hipSuccess) return e;                                                             \
         }                                                                                              \
-        hipLaunchKernelGGL((tdc_fused_kernel<A_, B_, C_, D_, W_>), grid, block, g.lds_bytes, s, a);    \
+        hipLaunchKernelGGL((tdc_fused_kernel<A_, B_, C_, D_, W_, L_>), grid, block, g.lds_bytes, s, a);\
         return hipGetLastError();                                                                      \
     }
 #define TDC_X(A_, B_, C_, D_)                                                                          \
     if (t.mb[0] == A_ && t.mb[1] == B_ && t.mb[2] == C_ && t.pb[0] == D_) {                            \
-        if (g.weights_in_lds) TDC_LAUNCH(A_, B_, C_, D_, true) else TDC_LAUNCH(A_, B_, C_, D_, false)  \
+        if (g.weights_in_lds) {                                                                        \
+            if (d.nhwc) TDC_LAUNCH(A_, B_, C_, D_, true, true) else TDC_LAUNCH(A_, B_, C_, D_, true, false)    \
+        } else {                                                                                       \
+            if (d.nhwc) TDC_LAUNCH(A_, B_, C_, D_, false, true) else TDC_LAUNCH(A_, B_, C_, D_, false, false)  \
+        }                                                                                              \
     }
     TDC_FUSED_MENU(TDC_X)
 #undef TDC_X

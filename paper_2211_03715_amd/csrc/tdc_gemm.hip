@@ -1,6 +1,6 @@
 // SPLIT variant: the three stages (Eqs. 2, 3, 4) as three fp32-MFMA GEMM kernels,
 //   D[b][m][p] = sum_k Wt[k][m] * Act[b][k][p],
-// with pixels p along the lanes (contiguous in NCHW), output channels m in the MFMA rows
+// with pixels p along the lanes, output channels m in the MFMA rows
 // and the intermediates z1, z2 in plan-owned workspace in a blocked layout,
 //   z[b][channel block cb][pixel][16 channels],
 // which is the accumulator layout of the producing kernel (a lane holds channels 4g..4g+3 of one
@@ -35,8 +35,8 @@ struct GemmArgs {
     float *out;
     int act_rows;        // channel rows per image in act (C, R1P, R2P)
     int act_rows_valid;  // rows that exist in memory (C for stage 1, all otherwise)
-    int out_blocked;     // out is a blocked intermediate (see the head of this file), not NCHW
-    TdcEpi epi;          // applied to an NCHW output only (the layer's y)
+    int out_layout;      // TDC_ACT_BLOCKED: an intermediate (see the head of this file); else the layer's y, NCHW or NHWC
+    TdcEpi epi;          // applied to the layer's y only
     int act_pix;         // pixels per row in act
     int out_rows;        // channel rows per image in out (R1P, R2P, N)
     int out_pix;         // pixels per row in out
@@ -63,13 +63,16 @@ __device__ __forceinline__ int tdc_logical_block(int bid, int n)
 }
 
 // Stateful operand fetcher of one wavefront: each call returns the next k-group of its range.
-// ACTB: the activation operand is a blocked intermediate.
-template <int MODE, bool ACTB, int MB, int PB>
+// ACT: layout of the activation operand -- the caller's x (NCHW: four 4-byte loads per lane and
+// k-group, one per channel row; NHWC: the lane's four channels are 16 contiguous bytes) or a
+// blocked intermediate.
+template <int MODE, int ACT, int MB, int PB>
 struct GemmNext {
     tdc_rsrc wrs, ars;                // packed weights of this tile's first m-block; activations of this image
     unsigned wlane;                   // byte offset of this lane inside a 1 KiB weight fragment
     unsigned wstride;                 // bytes between consecutive m-blocks (KG fragments)
     int act_pix;
+    int C;                            // NHWC: channels per pixel (rows that exist)
     int kg, kg_end;                   // next k-group, end of range (wave-uniform)
     int dg, r, s, NBk, K, H, W;       // stage 2: position of kg within (tap, d1-group)
     int g;
@@ -88,8 +91,11 @@ struct GemmNext {
                 const int h = ih0[pb] + r, w = iw0[pb] + s;
                 const bool ok = pval[pb] && h >= 0 && h < H && w >= 0 && w < W;
                 const unsigned bad = ok ? dead : TDC_OOB;
-                if (ACTB) {
+                if (ACT == TDC_ACT_BLOCKED) {
                     bv[pb] = tdc_buf_load4(ars, ((unsigned)((dg * act_pix + poff[pb] + toff) * 16 + 4 * g) * 4u) | bad);
+                } else if (ACT == TDC_ACT_NHWC) {
+                    const int c = 16 * dg + 4 * g;
+                    bv[pb] = tdc_buf_load4(ars, ((unsigned)((poff[pb] + toff) * C + c) * 4u) | bad | (c < C ? 0u : TDC_OOB));
                 } else {
                     const unsigned base = (unsigned)((16 * dg + 4 * g) * act_pix + poff[pb] + toff) * 4u;
                     bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
@@ -105,12 +111,15 @@ struct GemmNext {
                 }
             }
         } else {
-            // rows past the last channel lie beyond the descriptor and read as 0 by themselves
+            // NCHW: rows past the last channel lie beyond the descriptor and read as 0 by themselves
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const unsigned bad = pval[pb] ? dead : TDC_OOB;
-                if (ACTB) {
+                if (ACT == TDC_ACT_BLOCKED) {
                     bv[pb] = tdc_buf_load4(ars, ((unsigned)((kg * act_pix + poff[pb]) * 16 + 4 * g) * 4u) | bad);
+                } else if (ACT == TDC_ACT_NHWC) {
+                    const int c = 16 * kg + 4 * g;
+                    bv[pb] = tdc_buf_load4(ars, ((unsigned)(poff[pb] * C + c) * 4u) | bad | (c < C ? 0u : TDC_OOB));
                 } else {
                     const unsigned base = (unsigned)((16 * kg + 4 * g) * act_pix + poff[pb]) * 4u;
                     bv[pb] = (tdc_f4){tdc_buf_load(ars, base | bad), tdc_buf_load(ars, (base + 4u * act_pix) | bad),
@@ -123,7 +132,7 @@ struct GemmNext {
     }
 };
 
-template <int MODE, bool ACTB, int MB, int PB, int U>
+template <int MODE, int ACT, int MB, int PB, int U>
 __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
 {
     extern __shared__ float red[];
@@ -136,12 +145,13 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     const int pg = a.pg_major ? hi : lo, mg = a.pg_major ? lo : hi;
     const int b = blockIdx.y;
 
-    GemmNext<MODE, ACTB, MB, PB> next;
+    GemmNext<MODE, ACT, MB, PB> next;
     next.wstride = (unsigned)a.KG * 1024u;
     next.wrs = tdc_make_rsrc(a.wp + (size_t)mg * MB * a.KG * 256, MB * next.wstride);
     next.ars = tdc_make_rsrc(a.act + (size_t)b * a.act_rows * a.act_pix, (unsigned)a.act_rows_valid * a.act_pix * 4u);
     next.wlane = lane * 16u;
     next.act_pix = a.act_pix;
+    next.C = a.act_rows_valid;
     next.NBk = a.NBk; next.K = a.K; next.H = a.H; next.W = a.W; next.g = g;
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
@@ -183,8 +193,12 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) {
                 const int p = 16 * (pg * PB + pb) + l16;
-                if (a.out_blocked) {
+                if (a.out_layout == TDC_ACT_BLOCKED) {
                     if (p < a.out_pix) outb4[((size_t)(mg * MB + mb) * a.out_pix + p) * 4 + g] = acc[mb][pb];
+                } else if (a.out_layout == TDC_ACT_NHWC) {
+                    const int m = 16 * (mg * MB + mb) + 4 * g;
+                    if (m < a.out_rows && p < a.out_pix)
+                        tdc_store_nhwc(a.out, a.epi, acc[mb][pb], m, ((size_t)b * a.out_pix + p) * a.out_rows + m);
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -198,8 +212,39 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
             }
         return;
     }
-    // Partial sums of every wavefront to LDS, [wave][(mb*PB + pb)*4 + i][lane], then a fixed-order sum.
+    // Partial sums of every wavefront to LDS, then a fixed-order sum, one output element per thread.
     constexpr int E = MB * PB * 256;
+    if (a.out_layout != TDC_ACT_NCHW) {
+        // channel-minor outputs: the partial sums stay as the lanes hold them, [wave][(mb*PB + pb)*64 + lane]
+        // 16-byte cells, so that consecutive threads sum and store consecutive channels of one pixel
+        tdc_f4 *__restrict__ red4 = reinterpret_cast<tdc_f4 *>(red);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int pb = 0; pb < PB; ++pb) red4[wave * (E / 4) + (mb * PB + pb) * 64 + lane] = acc[mb][pb];
+        __syncthreads();
+        TDC_PROBE((MODE - 1) * 5 + 3);
+        for (int e = threadIdx.x; e < E; e += blockDim.x) {
+            float sum = red[e];
+            for (int ww = 1; ww < nw; ++ww) sum += red[ww * E + e];
+            const int i = e & 3, ln = (e >> 2) & 63, blk = e >> 8;
+            const int pb = blk % PB, mb = blk / PB;
+            const int p = 16 * (pg * PB + pb) + (ln & 15);
+            if (p >= a.out_pix) continue;
+            if (a.out_layout == TDC_ACT_BLOCKED) {
+                outb[(((size_t)(mg * MB + mb) * a.out_pix + p) * 4 + (ln >> 4)) * 4 + i] = sum;
+            } else {
+                const int m = 16 * (mg * MB + mb) + 4 * (ln >> 4) + i;
+                if (m < a.out_rows) {
+                    const size_t idx = ((size_t)b * a.out_pix + p) * a.out_rows + m;
+                    a.out[idx] = tdc_apply_epilogue(a.epi, sum, m, idx);
+                }
+            }
+        }
+        TDC_PROBE((MODE - 1) * 5 + 4);
+        return;
+    }
+    // NCHW: [wave][(mb*PB + pb)*4 + i][lane], consecutive threads take consecutive pixels of one channel
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -208,23 +253,6 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
             for (int i = 0; i < 4; ++i) red[wave * E + ((mb * PB + pb) * 4 + i) * 64 + lane] = acc[mb][pb][i];
     __syncthreads();
     TDC_PROBE((MODE - 1) * 5 + 3);
-    if (a.out_blocked) {
-        for (int e = threadIdx.x; e < E / 4; e += blockDim.x) {   // one 16-byte cell per thread
-            const int ln = e & 63, blk = e >> 6;
-            tdc_f4 sum;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float v = red[(blk * 4 + i) * 64 + ln];
-                for (int ww = 1; ww < nw; ++ww) v += red[ww * E + (blk * 4 + i) * 64 + ln];
-                sum[i] = v;
-            }
-            const int pb = blk % PB, mb = blk / PB;
-            const int p = 16 * (pg * PB + pb) + (ln & 15);
-            if (p < a.out_pix) outb4[((size_t)(mg * MB + mb) * a.out_pix + p) * 4 + (ln >> 4)] = sum;
-        }
-        TDC_PROBE((MODE - 1) * 5 + 4);
-        return;
-    }
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         float sum = red[e];
         for (int ww = 1; ww < nw; ++ww) sum += red[ww * E + e];
@@ -256,7 +284,7 @@ int pick_u(int kg_per_wave, int umax)
     return best;
 }
 
-template <int MODE, bool ACTB>
+template <int MODE, int ACT>
 hipError_t launch_stage(const GemmArgs &a_in, int mb, int pb, int waves, int batch, hipStream_t s)
 {
     GemmArgs a = a_in;
@@ -279,7 +307,7 @@ hipError_t launch_stage(const GemmArgs &a_in, int mb, int pb, int waves, int bat
     if (mb * pb > 4) u = 2;
 #define TDC_CASE(M_, P_, U_)                                                                      \
     if (mb == M_ && pb == P_ && u == U_) {                                                        \
-        hipLaunchKernelGGL((tdc_gemm_kernel<MODE, ACTB, M_, P_, U_>), grid, block, lds, s, a);    \
+        hipLaunchKernelGGL((tdc_gemm_kernel<MODE, ACT, M_, P_, U_>), grid, block, lds, s, a);    \
         return hipGetLastError();                                                                 \
     }
     TDC_CASE(1, 1, 1) TDC_CASE(1, 1, 2) TDC_CASE(1, 1, 3) TDC_CASE(1, 1, 4)
@@ -308,27 +336,28 @@ hipError_t tdc_launch_split(const TdcDims &d, const tdc_tuning &t, hipStream_t s
     // stage 1 (Eq. 2): z1 = U_in^T x
     a.act = x; a.wp = uin_p; a.out = z1;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
-    a.out_rows = 16 * d.NB1; a.out_pix = HW; a.out_blocked = 1;
+    a.out_rows = 16 * d.NB1; a.out_pix = HW; a.out_layout = TDC_ACT_BLOCKED;
     a.NBm = d.NB1; a.KG = d.KG1; a.NBk = 1;
     a.n_pgroups = ((HW + 15) / 16 + t.pb[0] - 1) / t.pb[0];
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
-    hipError_t e = launch_stage<1, false>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
+    hipError_t e = d.nhwc ? launch_stage<1, TDC_ACT_NHWC>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s)
+                          : launch_stage<1, TDC_ACT_NCHW>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
     if (e != hipSuccess) return e;
     // stage 2 (Eq. 3): z2 = core conv of z1
     a.act = z1; a.wp = core_p; a.out = z2;
     a.act_rows = 16 * d.NB1; a.act_rows_valid = 16 * d.NB1; a.act_pix = HW;
-    a.out_rows = 16 * d.NB2; a.out_pix = P; a.out_blocked = 1;
+    a.out_rows = 16 * d.NB2; a.out_pix = P; a.out_layout = TDC_ACT_BLOCKED;
     a.NBm = d.NB2; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
-    e = launch_stage<2, true>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+    e = launch_stage<2, TDC_ACT_BLOCKED>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
     if (e != hipSuccess) return e;
     // stage 3 (Eq. 4): y = U_out^T z2
     a.act = z2; a.wp = uout_p; a.out = y;
     a.act_rows = 16 * d.NB2; a.act_rows_valid = 16 * d.NB2; a.act_pix = P;
-    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0; a.epi = epi;
+    a.out_rows = d.N; a.out_pix = P; a.out_layout = d.nhwc ? TDC_ACT_NHWC : TDC_ACT_NCHW; a.epi = epi;
     a.NBm = d.NB3; a.KG = d.NB2; a.NBk = 1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[2] - 1) / t.pb[2];
-    return launch_stage<3, true>(a, t.mb[2], t.pb[2], t.waves[2], d.B, s);
+    return launch_stage<3, TDC_ACT_BLOCKED>(a, t.mb[2], t.pb[2], t.waves[2], d.B, s);
 }
 
 // The undecomposed layer (Eq. 1's kernel applied directly): the stage-2 implicit GEMM with the
@@ -343,11 +372,12 @@ hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s
     a.epi = TdcEpi{nullptr, nullptr, 0};
     a.act = x; a.wp = w_p; a.out = y;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
-    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0; a.epi = epi;
+    a.out_rows = d.N; a.out_pix = P; a.out_layout = d.nhwc ? TDC_ACT_NHWC : TDC_ACT_NCHW; a.epi = epi;
     a.NBm = d.NB2; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
-    return launch_stage<2, false>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+    return d.nhwc ? launch_stage<2, TDC_ACT_NHWC>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s)
+                  : launch_stage<2, TDC_ACT_NCHW>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
 }
 
 // MERGED variant: two launches.  Stage 1 as in SPLIT; then one implicit GEMM R1 -> N with the
@@ -362,16 +392,17 @@ hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t 
     a.epi = TdcEpi{nullptr, nullptr, 0};
     a.act = x; a.wp = uin_p; a.out = z1;
     a.act_rows = d.C; a.act_rows_valid = d.C; a.act_pix = HW;
-    a.out_rows = 16 * d.NB1; a.out_pix = HW; a.out_blocked = 1;
+    a.out_rows = 16 * d.NB1; a.out_pix = HW; a.out_layout = TDC_ACT_BLOCKED;
     a.NBm = d.NB1; a.KG = d.KG1; a.NBk = 1;
     a.n_pgroups = ((HW + 15) / 16 + t.pb[0] - 1) / t.pb[0];
     a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
-    hipError_t e = launch_stage<1, false>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
+    hipError_t e = d.nhwc ? launch_stage<1, TDC_ACT_NHWC>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s)
+                          : launch_stage<1, TDC_ACT_NCHW>(a, t.mb[0], t.pb[0], t.waves[0], d.B, s);
     if (e != hipSuccess) return e;
     a.act = z1; a.wp = wm_p; a.out = y;
     a.act_rows = 16 * d.NB1; a.act_rows_valid = 16 * d.NB1; a.act_pix = HW;
-    a.out_rows = d.N; a.out_pix = P; a.out_blocked = 0; a.epi = epi;
+    a.out_rows = d.N; a.out_pix = P; a.out_layout = d.nhwc ? TDC_ACT_NHWC : TDC_ACT_NCHW; a.epi = epi;
     a.NBm = d.NB3; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
-    return launch_stage<2, true>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+    return launch_stage<2, TDC_ACT_BLOCKED>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
 }

@@ -31,10 +31,14 @@ struct TdcEpi {
     int relu;
 };
 
+// Activation layouts the kernels read (GEMM kernels: template parameter ACT) and write.
+enum { TDC_ACT_NCHW = 0, TDC_ACT_BLOCKED = 1, TDC_ACT_NHWC = 2 };
+
 struct TdcDims {
     int B, C, N, H, W, R1, R2, K, stride, pad, Ho, Wo;
     int NB1, NB2, NB3;   // 16-blocks of the padded R1, R2, N
     int KG1;             // ceil(C/16)
+    int nhwc;            // activations x, y (and an epilogue's residual) are [B][H][W][channels]; C % 4 == N % 4 == 0
 };
 
 // ---- weight re-layout (tdc_pack.hip)

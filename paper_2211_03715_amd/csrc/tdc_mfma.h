@@ -64,6 +64,17 @@ __device__ __forceinline__ float tdc_apply_epilogue(const TdcEpi &e, float v, in
     return e.relu ? fmaxf(v, 0.f) : v;
 }
 
+// NHWC output: the four accumulator registers of a lane are channels n .. n+3 (n a multiple of 4)
+// of one pixel, i.e. 16 contiguous bytes of y.  `cell` is the element index of channel n of that
+// pixel within the whole tensor; y and the residual are 16-byte aligned.
+__device__ __forceinline__ void tdc_store_nhwc(float *__restrict__ y, const TdcEpi &e, tdc_f4 v, int n, size_t cell)
+{
+    if (e.bias) v += (tdc_f4){e.bias[n], e.bias[n + 1], e.bias[n + 2], e.bias[n + 3]};
+    if (e.residual) v += *reinterpret_cast<const tdc_f4 *>(e.residual + cell);
+    if (e.relu) v = (tdc_f4){fmaxf(v[0], 0.f), fmaxf(v[1], 0.f), fmaxf(v[2], 0.f), fmaxf(v[3], 0.f)};
+    *reinterpret_cast<tdc_f4 *>(y + cell) = v;
+}
+
 __device__ __forceinline__ int tdc_div(int x, const TdcDiv &d)
 {
     return (int)tdc_div_from_hi((unsigned)x, __umulhi(d.m, (unsigned)x), d);

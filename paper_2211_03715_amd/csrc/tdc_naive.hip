@@ -11,19 +11,22 @@ constexpr int OT = 8;      // output channels per thread
 constexpr int TPB = 256;   // threads per block
 
 // out[b][m][p] = sum_k in[b][k][p] * Wt[k][m]      (1x1 convolution; Eq. 2 and Eq. 4)
+// in_nhwc / out_nhwc: that tensor is [b][p][channel] instead of [b][channel][p]
 __global__ __launch_bounds__(TPB) void naive_pointwise(const float *__restrict__ in, const float *__restrict__ Wt,
-                                                       float *__restrict__ out, int Kc, int M, int P, TdcEpi epi)
+                                                       float *__restrict__ out, int Kc, int M, int P, TdcEpi epi,
+                                                       int in_nhwc, int out_nhwc)
 {
     const int p = blockIdx.x * TPB + threadIdx.x;
     const int m0 = blockIdx.y * OT;
     const int b = blockIdx.z;
     if (p >= P) return;
-    const float *inb = in + (size_t)b * Kc * P + p;
+    const float *inb = in + (size_t)b * Kc * P + (in_nhwc ? (size_t)p * Kc : (size_t)p);
+    const size_t in_cs = in_nhwc ? 1 : (size_t)P;
     float acc[OT];
 #pragma unroll
     for (int j = 0; j < OT; ++j) acc[j] = 0.f;
     for (int k = 0; k < Kc; ++k) {
-        const float v = inb[(size_t)k * P];
+        const float v = inb[(size_t)k * in_cs];
 #pragma unroll
         for (int j = 0; j < OT; ++j)
             if (m0 + j < M) acc[j] = fmaf(v, Wt[(size_t)k * M + m0 + j], acc[j]);
@@ -31,7 +34,7 @@ __global__ __launch_bounds__(TPB) void naive_pointwise(const float *__restrict__
 #pragma unroll
     for (int j = 0; j < OT; ++j)
         if (m0 + j < M) {
-            const size_t idx = ((size_t)b * M + m0 + j) * P + p;
+            const size_t idx = out_nhwc ? ((size_t)b * P + p) * M + m0 + j : ((size_t)b * M + m0 + j) * P + p;
             out[idx] = tdc_apply_epilogue(epi, acc[j], m0 + j, idx);
         }
 }
@@ -78,10 +81,10 @@ hipError_t tdc_launch_naive(const TdcDims &d, hipStream_t s, const float *x, con
 {
     const int HW = d.H * d.W, P = d.Ho * d.Wo;
     hipLaunchKernelGGL(naive_pointwise, dim3((HW + TPB - 1) / TPB, (d.R1 + OT - 1) / OT, d.B), dim3(TPB), 0, s,
-                       x, U_in, z1, d.C, d.R1, HW, TdcEpi{nullptr, nullptr, 0});
+                       x, U_in, z1, d.C, d.R1, HW, TdcEpi{nullptr, nullptr, 0}, d.nhwc, 0);
     hipLaunchKernelGGL(naive_core, dim3((P + TPB - 1) / TPB, (d.R2 + OT - 1) / OT, d.B), dim3(TPB), 0, s,
                        d, z1, core, z2);
     hipLaunchKernelGGL(naive_pointwise, dim3((P + TPB - 1) / TPB, (d.N + OT - 1) / OT, d.B), dim3(TPB), 0, s,
-                       z2, U_out, y, d.R2, d.N, P, epi);
+                       z2, U_out, y, d.R2, d.N, P, epi, 0, d.nhwc);
     return hipGetLastError();
 }

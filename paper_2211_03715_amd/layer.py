@@ -13,15 +13,21 @@ from . import binding as B
 class TuckerConv2d:
     """One Tucker-2 convolution layer (paper section 3, Eqs. 2-4) bound to a device plan."""
 
-    def __init__(self, layer, device: int = 0, tuning: Optional[B.tdc_tuning] = None):
-        """``layer`` has fields batch, C, N, H, W, R1, R2, K, stride, pad (e.g. workloads.Layer)."""
+    def __init__(self, layer, device: int = 0, tuning: Optional[B.tdc_tuning] = None, layout: int = B.LAYOUT_NCHW):
+        """``layer`` has fields batch, C, N, H, W, R1, R2, K, stride, pad (e.g. workloads.Layer).
+        ``layout``: LAYOUT_NCHW (x [B][C][H][W], y [B][N][Ho][Wo]) or LAYOUT_NHWC (x [B][H][W][C], y [B][Ho][Wo][N])."""
         self.shape = B.make_shape(layer.batch, layer.C, layer.N, layer.H, layer.W, layer.R1, layer.R2,
-                                  layer.K, layer.stride, layer.pad)
+                                  layer.K, layer.stride, layer.pad, layout)
         self.Ho = B.tdc_out_size(layer.H, layer.K, layer.stride, layer.pad)
         self.Wo = B.tdc_out_size(layer.W, layer.K, layer.stride, layer.pad)
         self.plan = B.tdc_plan_create(self.shape, device, tuning)
         self.device = device
         self._weights = None
+
+    def out_shape(self):
+        """Shape of y in the plan's layout."""
+        s = self.shape
+        return (s.batch, self.Ho, self.Wo, s.N) if s.layout == B.LAYOUT_NHWC else (s.batch, s.N, self.Ho, self.Wo)
 
     def describe(self) -> str:
         return B.tdc_plan_describe(self.plan)
@@ -42,8 +48,7 @@ class TuckerConv2d:
         import torch
         U_in, core, U_out = weights if weights is not None else self._weights
         if y is None:
-            y = torch.empty((self.shape.batch, self.shape.N, self.Ho, self.Wo), device=x.device,
-                            dtype=torch.float32)
+            y = torch.empty(self.out_shape(), device=x.device, dtype=torch.float32)
         if bias is None and residual is None and not relu:
             B.tdc_conv_tucker2(self.plan, x, U_in, core, U_out, y, self.shape, stream)
         else:
@@ -90,9 +95,9 @@ class DenseConv2d:
     """The undecomposed K x K layer with the kernel W[C][N][K][K] of Eq. 1, on the same library: the
     "original convolution" the rank-selection threshold test (paper section 6) compares against."""
 
-    def __init__(self, layer, device: int = 0, tuning: Optional[B.tdc_tuning] = None):
+    def __init__(self, layer, device: int = 0, tuning: Optional[B.tdc_tuning] = None, layout: int = B.LAYOUT_NCHW):
         self.shape = B.make_shape(layer.batch, layer.C, layer.N, layer.H, layer.W, layer.R1, layer.R2,
-                                  layer.K, layer.stride, layer.pad)
+                                  layer.K, layer.stride, layer.pad, layout)
         self.Ho = B.tdc_out_size(layer.H, layer.K, layer.stride, layer.pad)
         self.Wo = B.tdc_out_size(layer.W, layer.K, layer.stride, layer.pad)
         t = tuning if tuning is not None else B.make_tuning()
@@ -100,6 +105,11 @@ class DenseConv2d:
         self.plan = B.tdc_plan_create(self.shape, device, t)
         self.device = device
         self._W = None
+
+    def out_shape(self):
+        """Shape of y in the plan's layout."""
+        s = self.shape
+        return (s.batch, self.Ho, self.Wo, s.N) if s.layout == B.LAYOUT_NHWC else (s.batch, s.N, self.Ho, self.Wo)
 
     def describe(self) -> str:
         return B.tdc_plan_describe(self.plan)
@@ -115,8 +125,7 @@ class DenseConv2d:
         import torch
         W = W if W is not None else self._W
         if y is None:
-            y = torch.empty((self.shape.batch, self.shape.N, self.Ho, self.Wo), device=x.device,
-                            dtype=torch.float32)
+            y = torch.empty(self.out_shape(), device=x.device, dtype=torch.float32)
         if bias is None and residual is None and not relu:
             B.tdc_conv_dense(self.plan, x, W, y, self.shape, stream)
         else:

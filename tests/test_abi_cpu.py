@@ -72,7 +72,9 @@ def test_validation_happens_before_any_device_call():
     for s in bad:
         rc, plan = _create(s)
         assert rc == B.TDC_ERR_BAD_SHAPE and not plan.value
-    unsupported = [B.make_shape(1, 4, 4, 8, 8, 2, 2, layout=1), B.make_shape(1, 4, 4, 8, 8, 2, 2, K=9, pad=4),
+    unsupported = [B.make_shape(1, 4, 4, 8, 8, 2, 2, layout=2), B.make_shape(1, 4, 4, 8, 8, 2, 2, layout=-1),
+                   B.make_shape(1, 6, 4, 8, 8, 2, 2, layout=B.LAYOUT_NHWC), B.make_shape(1, 4, 6, 8, 8, 2, 2, layout=B.LAYOUT_NHWC),
+                   B.make_shape(1, 4, 4, 8, 8, 2, 2, K=9, pad=4),
                    B.make_shape(1, 4, 4, 8, 8, 2, 2, stride=5), B.make_shape(1, 4, 4, 8, 8, 2, 2, K=3, pad=3),
                    B.make_shape(4096, 1024, 4, 1024, 1024, 2, 2)]
     for s in unsupported:
@@ -91,6 +93,7 @@ def test_selector_fills_a_launchable_tuning_for_every_workload():
     for cfg in range(1, 6):
         for L in config_layers(cfg):
             t = B.tdc_select_tuning(B.make_shape(**L.asdict()))
+            assert B.tdc_select_tuning(B.make_shape(**L.asdict(), layout=B.LAYOUT_NHWC)).as_dict() == t.as_dict()
             d = t.as_dict()
             assert d["variant"] in ("split", "fused", "chain", "merged", "fused_merged"), d
             assert all(1 <= w <= 8 for w in d["waves"]) and all(1 <= m <= 8 for m in d["mb"])
