@@ -12,7 +12,7 @@ All buffers are allocated when the block is built, so a call only enqueues three
 (four when the selector gives the Tucker layer two kernels) and can be captured into a HIP
 graph: `graph = block.capture(x_static)`, then `graph.replay()`.
 
-    python -m paper_2211_03715_amd.bottleneck          # eager vs graph latency of a few block shapes
+    python -m paper_2211_03715_amd.bottleneck [--nhwc]   # eager vs graph latency of a few block shapes
 """
 from __future__ import annotations
 
@@ -36,20 +36,24 @@ def make_block_weights(C: int, M: int, R1: int, R2: int, seed: int) -> Dict[str,
 
 
 class TuckerBottleneck:
-    def __init__(self, batch: int, C: int, M: int, H: int, W: int, R1: int, R2: int, weights: Dict, device: int = 0):
+    def __init__(self, batch: int, C: int, M: int, H: int, W: int, R1: int, R2: int, weights: Dict, device: int = 0,
+                 layout: int = B.LAYOUT_NCHW):
+        """``layout``: LAYOUT_NCHW (x, y [batch][C][H][W]) or LAYOUT_NHWC ([batch][H][W][C]); C, M multiples of 4 for NHWC."""
         import torch
         self.dev = torch.device("cuda", device)
+        self.layout = layout
         self.l1 = Layer(batch, C, M, H, W, 1, 1, 1, 1, 0)
         self.l2 = Layer(batch, M, M, H, W, R1, R2, 3, 1, 1)
         self.l3 = Layer(batch, M, C, H, W, 1, 1, 1, 1, 0)
         self.w = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.dev) for k, v in weights.items()}
-        self.conv1, self.conv2, self.conv3 = DenseConv2d(self.l1, device), TuckerConv2d(self.l2, device), DenseConv2d(self.l3, device)
+        self.conv1, self.conv2, self.conv3 = (DenseConv2d(self.l1, device, layout=layout), TuckerConv2d(self.l2, device, layout=layout),
+                                              DenseConv2d(self.l3, device, layout=layout))
         self.conv1.pack(self.w["W1"])
         self.conv2.pack(self.w["U_in"], self.w["core"], self.w["U_out"])
         self.conv3.pack(self.w["W3"])
-        self.t1 = torch.empty((batch, M, H, W), device=self.dev, dtype=torch.float32)
-        self.t2 = torch.empty((batch, M, H, W), device=self.dev, dtype=torch.float32)
-        self.y = torch.empty((batch, C, H, W), device=self.dev, dtype=torch.float32)
+        self.t1 = torch.empty(self.conv1.out_shape(), device=self.dev, dtype=torch.float32)
+        self.t2 = torch.empty(self.conv2.out_shape(), device=self.dev, dtype=torch.float32)
+        self.y = torch.empty(self.conv3.out_shape(), device=self.dev, dtype=torch.float32)
         self._launchers = None
         self._x = None
 
@@ -102,10 +106,12 @@ def main(argv=None) -> int:
     if not torch.cuda.is_available():
         sys.exit("bottleneck needs a GPU")
     B.load()
-    print("%-34s %8s %10s %10s  %s" % ("block (batch 1)", "kernels", "eager us", "graph us", "plans"), flush=True)
+    layout = B.LAYOUT_NHWC if argv and "--nhwc" in argv else B.LAYOUT_NCHW
+    print("%-34s %8s %10s %10s  %s" % ("block (batch 1, %s)" % ("NHWC" if layout else "NCHW"), "kernels", "eager us", "graph us", "plans"),
+          flush=True)
     for (C, M, HW, R) in ((256, 64, 56, 16), (512, 128, 28, 32), (1024, 256, 14, 64), (2048, 512, 7, 128)):
-        blk = TuckerBottleneck(1, C, M, HW, HW, R, R, make_block_weights(C, M, R, R, 7))
-        x = torch.randn((1, C, HW, HW), device=blk.dev)
+        blk = TuckerBottleneck(1, C, M, HW, HW, R, R, make_block_weights(C, M, R, R, 7), layout=layout)
+        x = torch.randn((1, HW, HW, C) if layout else (1, C, HW, HW), device=blk.dev)
         graph = blk.capture(x)
 
         def timed(fn, iters=300):
@@ -128,4 +134,4 @@ def main(argv=None) -> int:
 
 
 if __name__ == "__main__":
-    sys.exit(main())
+    sys.exit(main(sys.argv[1:]))

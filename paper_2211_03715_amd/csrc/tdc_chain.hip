@@ -19,6 +19,7 @@
 // R2-channel column of z2 for 16 or 32 pixels, which is what lets the 1x1 expansion ride along.
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
+#include "tdc_stage1.h"
 
 namespace {
 
@@ -48,107 +49,31 @@ __device__ __forceinline__ void tdc_buf_store4(tdc_rsrc r, unsigned byte_off, td
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), r, (int)byte_off, 0, 0);
 }
 
-// Stage 1 (Eq. 2) for the whole workgroup: z1 tile = U_in^T x into LDS cells.  `prefetched`
-// says that `pipe` already holds the first buffer of unit `wave` (issued before the weight copy).
-template <int MB1, int PB, bool NHWC>
-struct ChainStage1 {
-    const ChainArgs &a;
-    tdc_rsrc xrs, urs;
-    int lane, g, l16, h0, w0, HW, n_pg;
-    int pg, mg, kg;
-    unsigned xoff[PB];
-
-    __device__ __forceinline__ void setup(int u)
-    {
-        mg = tdc_div(u, a.div_npg1);
-        pg = u - mg * n_pg;
-        kg = 0;
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-            const int q = 16 * (pg * PB + pb) + l16;
-            const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
-            const int h = h0 + qh, w = w0 + qw;
-            const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
-            xoff[pb] = ok ? (unsigned)(h * a.W + w) * (NHWC ? 4u * a.C : 4u) : TDC_OOB;
-        }
-    }
-    __device__ __forceinline__ void operator()(tdc_f4 (&av)[MB1], tdc_f4 (&bv)[PB])
-    {
-        const unsigned dead = kg < a.KG1 ? 0u : TDC_OOB;
-#pragma unroll
-        for (int mb = 0; mb < MB1; ++mb)
-            av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
-        if (NHWC) {
-            const int c = 16 * kg + 4 * g;
-            const unsigned cbad = c < a.C ? dead : TDC_OOB;
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb) bv[pb] = tdc_buf_load4(xrs, (xoff[pb] + 4u * c) | cbad | (xoff[pb] & TDC_OOB));
-        } else {
-            // channels past C lie beyond the descriptor and read as 0 by themselves
-            const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
-                bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
-                                  tdc_buf_load(xrs, o + 12u * HW)};
-            }
-        }
-        ++kg;
-    }
-};
-
+// Stage 1 (Eq. 2) for the whole workgroup: z1 tile = U_in^T x into LDS cells, and the weights of
+// stages 2 and 3 into LDS when they fit (their first loads travel while stage 1 computes).
 template <int MB1, int PB, bool NHWC>
 __device__ __forceinline__ void chain_stage1(const ChainArgs &a, tdc_f4 *__restrict__ z1s, int lane, int wave, int nw,
-                                             int b, int h0, int w0, const tdc_f4 *__restrict__ wsrc_core,
-                                             tdc_f4 *__restrict__ wC, tdc_f4 *__restrict__ wO, bool copy_weights)
+                                             int b, int h0, int w0, tdc_f4 *__restrict__ wC, bool copy_weights)
 {
-    constexpr int U = 4;
-    const int HW = a.H * a.W;
-    ChainStage1<MB1, PB, NHWC> next{a};
-    next.xrs = tdc_make_rsrc(a.x + (size_t)b * a.C * HW, (unsigned)a.C * HW * 4u);
-    next.urs = tdc_make_rsrc(a.uin_p, (unsigned)a.NB1 * a.KG1 * 1024u);
-    next.lane = lane; next.g = lane >> 4; next.l16 = lane & 15;
-    next.h0 = h0; next.w0 = w0; next.HW = HW;
-    next.n_pg = (a.QB + PB - 1) / PB;
-    const int n_units = next.n_pg * (a.NB1 / MB1);
-    TdcPipe<MB1, PB, U> pipe;
-    int u = wave;
-    if (u < n_units) {
-        next.setup(u);
-        pipe.start(next);          // in flight while the weights are copied
-    }
+    TdcS1Geom sg;
+    sg.x_img = a.x + (size_t)b * a.C * a.H * a.W; sg.uin_p = a.uin_p;
+    sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
+    sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
+    sg.div_QW = a.div_QW; sg.div_npg = a.div_npg1;
+    TdcStage1<MB1, PB, (MB1 * PB >= 8 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);   // k-groups per operand buffer
+    s1.prefetch();
+    const tdc_f4 *__restrict__ core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
+    const tdc_f4 *__restrict__ uout4 = reinterpret_cast<const tdc_f4 *>(a.uout_p);
+    TdcWeightCopy<8> wc;
+    if (copy_weights) wc.load(core4, a.w_core4, uout4, a.w_uout4, 0);
+    s1.run(z1s);
     if (copy_weights) {
-        // core and U_out: global -> registers -> LDS, 8 x 16 bytes per thread and round
-        constexpr int CH = 8;
-        const tdc_f4 *__restrict__ src[2] = {wsrc_core, reinterpret_cast<const tdc_f4 *>(a.uout_p)};
-        tdc_f4 *dst[2] = {wC, wO};
-        const int cnt[2] = {a.w_core4, a.w_uout4};
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-            for (int base = threadIdx.x; base < cnt[t]; base += CH * blockDim.x) {
-                tdc_f4 tmp[CH];
-#pragma unroll
-                for (int c = 0; c < CH; ++c) tmp[c] = src[t][min(base + c * (int)blockDim.x, cnt[t] - 1)];
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    const int i = base + c * blockDim.x;
-                    if (i < cnt[t]) dst[t][i] = tmp[c];
-                }
-            }
-    }
-    for (; u < n_units; u += nw) {
-        if (u != wave) {
-            next.setup(u);
-            pipe.start(next);
+        const int n = a.w_core4 + a.w_uout4, round = 8 * (int)blockDim.x;
+        wc.store(wC, n, 0);
+        for (int base = round; base < n; base += round) {
+            wc.load(core4, a.w_core4, uout4, a.w_uout4, base);
+            wc.store(wC, n, base);
         }
-        tdc_f4 acc[MB1][PB];
-        pipe.run(acc, a.KG1, next);
-#pragma unroll
-        for (int mb = 0; mb < MB1; ++mb)
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb)
-                if (next.pg * PB + pb < a.QB)
-                    z1s[((next.mg * MB1 + mb) * 4 + next.g) * a.pitch1 + 16 * (next.pg * PB + pb) + next.l16] = acc[mb][pb];
     }
 }
 
@@ -170,10 +95,9 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
     TDC_PROBE(0);
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
-        const tdc_f4 *core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
-        if (a.mb1 == 4) chain_stage1<4, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
-        else if (a.mb1 == 2) chain_stage1<2, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
-        else chain_stage1<1, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, core4, wC, wO, WLDS);
+        if (a.mb1 == 4) chain_stage1<4, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
+        else if (a.mb1 == 2) chain_stage1<2, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
+        else chain_stage1<1, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
     }
     TDC_PROBE(3);
     __syncthreads();
@@ -197,14 +121,16 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
         }
         tdc_f4 acc2[NB2][PB];
         {
-            constexpr int U = 1;
+            // weights streamed from L2 (they did not fit in LDS) need two k-groups of lookahead to cover
+            // its latency; a dead k-group then multiplies zeros (the buffer load returns 0)
+            constexpr int U = (WLDS || NB2 > 4) ? 1 : 2;
             int kg = 0, dg = 0, s = 0, toff = 0;     // toff = r*QW + s
             auto next = [&](tdc_f4(&av)[NB2], tdc_f4(&bv)[PB]) {
                 const bool live = kg < KG2;
 #pragma unroll
                 for (int mb = 0; mb < NB2; ++mb) {
                     const int frag = mb * KG2 + kg;
-                    // a dead fetch is never multiplied (one k-group per buffer); it only has to stay in range
+                    // WLDS: a dead fetch is never multiplied (one k-group per buffer); it only has to stay in range
                     if (WLDS) av[mb] = wC[(live ? frag : 0) * 64 + lane];
                     else av[mb] = tdc_buf_load4(crs, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
                 }
@@ -243,7 +169,8 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
             const int oi = i0 + ph, oj = j0 + pw;
             ypix[pb] = (p < a.P && oi < a.Ho && oj < a.Wo) ? oi * a.Wo + oj : -1;
         }
-        tdc_f4 ua[2][NB2];
+        constexpr int D3 = (WLDS || NB2 > 4) ? 2 : 3;     // U_out blocks in flight (from L2: one more)
+        tdc_f4 ua[D3][NB2];
         const auto fetch = [&](int nb, tdc_f4(&u)[NB2]) {
             const bool live = nb < a.NB3;
 #pragma unroll
@@ -300,11 +227,23 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
             }
         };
         fetch(0, ua[0]);
-        for (int nb = 0; nb < a.NB3; nb += 2) {
-            fetch(nb + 1, ua[1]);
-            emit(nb, ua[0]);
-            fetch(nb + 2, ua[0]);
-            if (nb + 1 < a.NB3) emit(nb + 1, ua[1]);
+        if constexpr (D3 == 3) {
+            fetch(1, ua[1]);
+            for (int nb = 0; nb < a.NB3; nb += 3) {
+                fetch(nb + 2, ua[2]);
+                emit(nb, ua[0]);
+                fetch(nb + 3, ua[0]);
+                if (nb + 1 < a.NB3) emit(nb + 1, ua[1]);
+                fetch(nb + 4, ua[1]);
+                if (nb + 2 < a.NB3) emit(nb + 2, ua[2]);
+            }
+        } else {
+            for (int nb = 0; nb < a.NB3; nb += 2) {
+                fetch(nb + 1, ua[1]);
+                emit(nb, ua[0]);
+                fetch(nb + 2, ua[0]);
+                if (nb + 1 < a.NB3) emit(nb + 1, ua[1]);
+            }
         }
     }
     TDC_PROBE(7);

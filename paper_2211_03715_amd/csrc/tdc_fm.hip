@@ -19,6 +19,7 @@
 // through LDS in a fixed order.
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
+#include "tdc_stage1.h"
 
 namespace {
 
@@ -65,45 +66,13 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
     TDC_PROBE(1);
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
-        constexpr int U = MB1 >= 4 ? 2 : 4;
-        const tdc_rsrc xrs = tdc_make_rsrc(a.x + (size_t)b * a.C * HW, (unsigned)a.C * HW * 4u);
-        const tdc_rsrc urs = tdc_make_rsrc(a.uin_p, (unsigned)a.NB1 * a.KG1 * 1024u);
-        const int n_mg = a.NB1 / MB1;
-        const int n_units = a.QB * n_mg;
-        int pg = 0, mg = 0, kg = 0;
-        unsigned xoff = 0;
-        const auto setup = [&](int u) {
-            mg = tdc_div(u, a.div_QB);
-            pg = u - mg * a.QB;
-            kg = 0;
-            const int q = 16 * pg + l16;
-            const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
-            const int h = h0 + qh, w = w0 + qw;
-            const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
-            xoff = ok ? (unsigned)(h * a.W + w) * (NHWC ? 4u * a.C : 4u) : TDC_OOB;
-        };
-        auto next = [&](tdc_f4(&av)[MB1], tdc_f4(&bv)[1]) {
-            const unsigned dead = kg < a.KG1 ? 0u : TDC_OOB;
-#pragma unroll
-            for (int mb = 0; mb < MB1; ++mb)
-                av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
-            if (NHWC) {
-                const int c = 16 * kg + 4 * g;
-                bv[0] = tdc_buf_load4(xrs, (xoff + 4u * c) | (c < a.C ? dead : TDC_OOB) | (xoff & TDC_OOB));
-            } else {
-                // channels past C lie beyond the descriptor and read as 0 by themselves
-                const unsigned o = ((unsigned)(16 * kg + 4 * g) * HW * 4u + xoff) | dead | (xoff & TDC_OOB);
-                bv[0] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
-                                 tdc_buf_load(xrs, o + 12u * HW)};
-            }
-            ++kg;
-        };
-        TdcPipe<MB1, 1, U> pipe;
-        int u = wave;
-        if (u < n_units) {
-            setup(u);
-            pipe.start(next);
-        }
+        TdcS1Geom sg;
+        sg.x_img = a.x + (size_t)b * a.C * HW; sg.uin_p = a.uin_p;
+        sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
+        sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
+        sg.div_QW = a.div_QW; sg.div_npg = a.div_QB;
+        TdcStage1<MB1, 1, (MB1 >= 4 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);
+        s1.prefetch();
         // The weight fragments of stage 2+3 go out right behind the first stage-1 operands: loads
         // return in order, so stage 1 can start as soon as its own data is there while these are
         // still in flight; a dead fragment (past the slice) reads as zero.
@@ -113,16 +82,7 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
             for (int f = 0; f < FM_FR; ++f)
                 wfrag[f] = tdc_buf_load4(wrs, ((unsigned)(kg0 + f) * 1024u + lane * 16u) | (kg0 + f < kg1 ? 0u : TDC_OOB));
         }
-        for (; u < n_units; u += nw) {
-            if (u != wave) {
-                setup(u);
-                pipe.start(next);
-            }
-            tdc_f4 acc[MB1][1];
-            pipe.run(acc, a.KG1, next);
-#pragma unroll
-            for (int mb = 0; mb < MB1; ++mb) z1s[((mg * MB1 + mb) * 4 + g) * a.pitch1 + 16 * pg + l16] = acc[mb][0];
-        }
+        s1.run(z1s);
     }
     TDC_PROBE(2);
     __syncthreads();

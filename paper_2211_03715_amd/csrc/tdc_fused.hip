@@ -29,6 +29,7 @@
 // After that, stages 2 and 3 touch only LDS.
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
+#include "tdc_stage1.h"
 
 namespace {
 
@@ -70,90 +71,29 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
     TDC_PROBE(0);
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
-        constexpr int U = 4;
-        const tdc_rsrc xrs = tdc_make_rsrc(a.x + (size_t)b * a.C * HW, (unsigned)a.C * HW * 4u);
-        const tdc_rsrc urs = tdc_make_rsrc(a.uin_p, (unsigned)a.NB1 * a.KG1 * 1024u);
-        const int n_pg = (a.QB + PB - 1) / PB, n_mg = a.NB1 / MB1;
-        const int n_units = n_pg * n_mg;
-        int pg = 0, mg = 0, kg = 0;
-        unsigned xoff[PB];       // byte offset of this lane's pixel in a channel row, or TDC_OOB
-        const auto setup = [&](int u) {
-            mg = tdc_div(u, a.div_npg1);
-            pg = u - mg * n_pg;
-            kg = 0;
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                const int q = 16 * (pg * PB + pb) + l16;
-                const int qh = tdc_div(q, a.div_QW), qw = q - qh * a.QW;
-                const int h = h0 + qh, w = w0 + qw;
-                const bool ok = q < a.Q && h >= 0 && h < a.H && w >= 0 && w < a.W;
-                xoff[pb] = ok ? (unsigned)(h * a.W + w) * (NHWC ? 4u * a.C : 4u) : TDC_OOB;
-            }
-        };
-        auto next = [&](tdc_f4(&av)[MB1], tdc_f4(&bv)[PB]) {
-            const unsigned dead = kg < a.KG1 ? 0u : TDC_OOB;
-#pragma unroll
-            for (int mb = 0; mb < MB1; ++mb)
-                av[mb] = tdc_buf_load4(urs, ((unsigned)((mg * MB1 + mb) * a.KG1 + kg) * 1024u + lane * 16u) | dead);
-            if (NHWC) {
-                const int c = 16 * kg + 4 * g;
-                const unsigned cbad = c < a.C ? dead : TDC_OOB;
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb)
-                    bv[pb] = tdc_buf_load4(xrs, (xoff[pb] + 4u * c) | cbad | (xoff[pb] & TDC_OOB));
-            } else {
-                // channels past C lie beyond the descriptor and read as 0 by themselves
-                const unsigned c0 = (unsigned)(16 * kg + 4 * g) * HW * 4u;
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb) {
-                    const unsigned o = (c0 + xoff[pb]) | dead | (xoff[pb] & TDC_OOB);
-                    bv[pb] = (tdc_f4){tdc_buf_load(xrs, o), tdc_buf_load(xrs, o + 4u * HW), tdc_buf_load(xrs, o + 8u * HW),
-                                      tdc_buf_load(xrs, o + 12u * HW)};
-                }
-            }
-            ++kg;
-        };
-        TdcPipe<MB1, PB, U> pipe;
-        int u = wave;
-        if (u < n_units) {
-            setup(u);
-            pipe.start(next);          // in flight while the weights are copied
-        }
+        TdcS1Geom sg;
+        sg.x_img = a.x + (size_t)b * a.C * HW; sg.uin_p = a.uin_p;
+        sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
+        sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
+        sg.div_QW = a.div_QW; sg.div_npg = a.div_npg1;
+        TdcStage1<MB1, PB, (MB1 * PB >= 8 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);   // k-groups per operand buffer
+        s1.prefetch();
         TDC_PROBE(1);
-        if (WLDS) {
-            // core and U_out: global -> registers -> LDS, 8 x 16 bytes per thread and round
-            constexpr int CH = 8;
-            const tdc_f4 *__restrict__ src[2] = {reinterpret_cast<const tdc_f4 *>(a.core_p),
-                                                 reinterpret_cast<const tdc_f4 *>(a.uout_p)};
-            tdc_f4 *dst[2] = {wC, wO};
-            const int cnt[2] = {a.w_core4, a.w_uout4};
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-                for (int base = threadIdx.x; base < cnt[t]; base += CH * blockDim.x) {
-                    tdc_f4 tmp[CH];
-#pragma unroll
-                    for (int c = 0; c < CH; ++c) tmp[c] = src[t][min(base + c * (int)blockDim.x, cnt[t] - 1)];
-#pragma unroll
-                    for (int c = 0; c < CH; ++c) {
-                        const int i = base + c * blockDim.x;
-                        if (i < cnt[t]) dst[t][i] = tmp[c];
-                    }
-                }
-        }
+        // core and U_out -> LDS: the first round's loads are issued here, behind the first stage-1
+        // operands, and stored after stage 1
+        const tdc_f4 *__restrict__ core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
+        const tdc_f4 *__restrict__ uout4 = reinterpret_cast<const tdc_f4 *>(a.uout_p);
+        TdcWeightCopy<8> wc;
+        if (WLDS) wc.load(core4, a.w_core4, uout4, a.w_uout4, 0);
         TDC_PROBE(2);
-        for (; u < n_units; u += nw) {
-            if (u != wave) {
-                setup(u);
-                pipe.start(next);
+        s1.run(z1s);
+        if (WLDS) {
+            const int n = a.w_core4 + a.w_uout4, round = 8 * (int)blockDim.x;
+            wc.store(wC, n, 0);
+            for (int base = round; base < n; base += round) {
+                wc.load(core4, a.w_core4, uout4, a.w_uout4, base);
+                wc.store(wC, n, base);
             }
-            tdc_f4 acc[MB1][PB];
-            pipe.run(acc, a.KG1, next);
-#pragma unroll
-            for (int mb = 0; mb < MB1; ++mb)
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb)
-                    if (pg * PB + pb < a.QB)
-                        z1s[tdc_cell(mg * MB1 + mb, g, a.pitch1, 16 * (pg * PB + pb) + l16)] = acc[mb][pb];
         }
     }
     TDC_PROBE(3);

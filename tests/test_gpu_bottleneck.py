@@ -5,6 +5,7 @@ import sys
 import numpy as np
 import pytest
 
+from paper_2211_03715_amd import binding as B
 from paper_2211_03715_amd.bottleneck import TuckerBottleneck, make_block_weights
 from parity_util import assert_parity
 
@@ -20,19 +21,22 @@ def _oracle_block(orc, blk, w, x):
     return orc.apply_epilogue(y3, w["b3"], x, True)
 
 
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
 @pytest.mark.parametrize("shape", [(1, 64, 16, 14, 14, 8, 8), (2, 48, 24, 9, 11, 16, 20), (1, 256, 64, 56, 56, 16, 16)],
                          ids=lambda s: "b%d_c%d_m%d_%dx%d_r%d-%d" % s)
-def test_bottleneck_eager_and_graph(orc, shape):
+def test_bottleneck_eager_and_graph(orc, shape, layout):
     import torch
     batch, C, M, H, W, R1, R2 = shape
-    print("[case] bottleneck", shape, flush=True)
+    print("[case] bottleneck", shape, "layout", layout, flush=True)
     sys.stdout.flush()
     w = make_block_weights(C, M, R1, R2, 11)
-    blk = TuckerBottleneck(batch, C, M, H, W, R1, R2, w)
+    blk = TuckerBottleneck(batch, C, M, H, W, R1, R2, w, layout=layout)
+    perm = (lambda a: np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1)))) if layout == B.LAYOUT_NHWC else (lambda a: a)
     try:
         rng = np.random.default_rng(5)
         xs = [rng.standard_normal((batch, C, H, W), dtype=np.float32) for _ in range(3)]
-        wants = [_oracle_block(orc, blk, w, x) for x in xs]
+        wants = [perm(_oracle_block(orc, blk, w, x)) for x in xs]       # the oracle works in NCHW
+        xs = [perm(x) for x in xs]
         x_dev = torch.from_numpy(xs[0]).to(blk.dev)
         got = blk(x_dev)
         torch.cuda.synchronize()
