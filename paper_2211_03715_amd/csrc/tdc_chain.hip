@@ -151,6 +151,7 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
             pipe.start(next);
             pipe.run(acc2, KG2, next);
         }
+        TDC_PROBE(5);
         // ---- stage 3.  NCHW: D[pixel 4*g + i][channel l16] = sum_d2 z2[d2][pixel] * U_out[d2][channel];
         //      NHWC: D[channel 4*g + i][pixel l16], the same products with the operands unswapped
         unsigned yq[PB][4];      // NCHW: byte offset of pixel 4*g + i of block pb in one channel plane, or TDC_OOB
