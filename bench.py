@@ -270,6 +270,30 @@ def main():
         "null_sync_us": null_sync_us,
         "sum_layer_latency_us": sum(p["latency_us"] for p in per_layer),
     }
+    if layout == B.LAYOUT_NCHW and not args.brief:
+        # the same step with pixel-major activations (tdc_shape.layout = 1): reported beside the NCHW figure
+        n_convs, n_x, n_y = [], [], []
+        for L, conv, x in zip(layers, convs, xs):
+            c2 = TuckerConv2d(L, 0, B.make_tuning(variant=variant) if variant else None, layout=B.LAYOUT_NHWC)
+            c2.pack(*conv._weights)
+            n_convs.append(c2)
+            n_x.append(x.permute(0, 2, 3, 1).contiguous())
+            n_y.append(torch.empty(c2.out_shape(), device=dev, dtype=torch.float32))
+        n_launch = [c.bind(x, y) for c, x, y in zip(n_convs, n_x, n_y)]
+
+        def n_step():
+            for launch in n_launch:
+                launch()
+
+        for _ in range(args.warmup):
+            n_step()
+        n_sec = _time_events(n_step, args.steps, torch)
+        out["nhwc"] = {"value": total_flops / n_sec / 1e9, "unit": "GFLOP/s", "ms_per_step": n_sec * 1e3,
+                       "layers": [{"layer": L.name(), "plan": c.describe(), "latency_us": _time_events(l, iters, torch) * 1e6}
+                                  for L, c, l in zip(layers, n_convs, n_launch)]}
+        torch.cuda.synchronize()
+        for c in n_convs:
+            c.close()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
         if not args.brief:

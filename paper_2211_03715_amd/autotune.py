@@ -84,16 +84,18 @@ def _time(launch, iters: int) -> float:
 
 
 def autotune(L: Layer, device: int = 0, iters: int = 200, variants=("fused", "chain", "split", "merged", "fused_merged"),
-             seed: int = 1, progress=None) -> Dict:
+             seed: int = 1, progress=None, layout: int = B.LAYOUT_NCHW) -> Dict:
     """Times the selector's pick and every candidate.  Returns {"auto": row, "best": row, "by_variant":
     {name: best row}, "rows": all rows sorted by latency}; a row is {us, plan, tuning}."""
     import torch
     dev = torch.device("cuda", device)
     t = {k: torch.from_numpy(v).to(dev) for k, v in make_inputs(L, seed).items()}
-    y = torch.empty((L.batch, L.N, L.Ho, L.Wo), device=dev, dtype=torch.float32)
+    if layout == B.LAYOUT_NHWC:
+        t["x"] = t["x"].permute(0, 2, 3, 1).contiguous()
+    y = torch.empty(L.batch * L.N * L.Ho * L.Wo, device=dev, dtype=torch.float32)
 
     def run(tuning):
-        conv = TuckerConv2d(L, device, tuning)
+        conv = TuckerConv2d(L, device, tuning, layout=layout)
         try:
             conv.pack(t["U_in"], t["core"], t["U_out"])
             us = _time(conv.bind(t["x"], y), iters)
@@ -155,6 +157,7 @@ def main(argv=None) -> int:
     ap.add_argument("--config", type=int, nargs="*", default=[2])
     ap.add_argument("--iters", type=int, default=200)
     ap.add_argument("--variants", nargs="*", default=["fused", "chain", "split", "merged", "fused_merged"])
+    ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"])
     ap.add_argument("--out", default=None, help="JSON with every timed tuning")
     args = ap.parse_args(argv)
     import torch
@@ -169,7 +172,8 @@ def main(argv=None) -> int:
             if L.name() in seen:
                 continue
             seen.add(L.name())
-            r = autotune(L, 0, args.iters if L.batch == 1 else max(50, args.iters // 4), tuple(args.variants))
+            r = autotune(L, 0, args.iters if L.batch == 1 else max(50, args.iters // 4), tuple(args.variants),
+                         layout=B.LAYOUT_NHWC if args.layout == "nhwc" else B.LAYOUT_NCHW)
             results.append(r)
             print("%-46s %9.2f %9.2f %6.1f%%  %s   (model chose: %s)" % (
                 L.name(), r["auto"]["us"], r["best"]["us"], 100.0 * (r["auto"]["us"] / r["best"]["us"] - 1.0), r["best"]["plan"],

@@ -35,7 +35,27 @@ struct FusedCoef {
     double s2_kg_lds = 0.0186, s2_kg_glb = 0.0356;
     double s3_unit = 0.3151, s3_kg_lds = 0.0806, s3_kg_glb = 0.0875, s3_mfma = 0.2474;
     double w_kb = 0.0340;         // per KiB of weights copied into LDS, per co-resident workgroup
+    // throughput regime only: stage-2 MFMAs, MB moved per CU by layout, NCHW row segments per CU (thousands)
+    double s2_mfma = 0.0;
+    double x_mb[2] = {0.0, 0.0}, y_mb[2] = {0.0, 0.0};   // [NCHW, NHWC]
+    double x_rows = 0.0, y_rows = 0.0;
 };
+
+// The same form refitted on ~7400 tunings of the batch-8 and batch-32 layers in both activation
+// layouts (median relative error 8%): there the bytes a CU moves and, in NCHW, the number of row
+// segments they come in decide between tilings.
+FusedCoef fused_throughput_coef()
+{
+    FusedCoef c;
+    c.launch = 3.2282;
+    c.s1_unit = 0.0; c.s1_kg = 0.0580; c.s1_mfma = 0.0432;
+    c.s2_kg_lds = 0.0308; c.s2_kg_glb = 0.0951; c.s2_mfma = 0.0129;
+    c.s3_unit = 0.2993; c.s3_kg_lds = 0.0826; c.s3_kg_glb = 0.0; c.s3_mfma = 0.1262;
+    c.w_kb = 0.0252;
+    c.x_mb[0] = 47.4064; c.x_mb[1] = 24.8735; c.y_mb[0] = 35.1973; c.y_mb[1] = 42.2936;
+    c.x_rows = 0.8812; c.y_rows = 2.3714;
+    return c;
+}
 
 // One GEMM launch of SPLIT, MERGED or DENSE.  Fitted to ~2500 stage tunings of the batch-1 layers
 // (median relative error 5%, the picked tuning within 10% of the best one timed): a launch
@@ -71,9 +91,12 @@ double fused_us(const FusedCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, 
     const bool wl = g.weights_in_lds;
     const double w_kb = wl ? (double)(d.NB2 * KG2 + d.NB3 * KG3) : 0.0;
     double t = r1 * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * mb1 * pb * share));
-    t += r2 * KG2 * (wl ? c.s2_kg_lds : c.s2_kg_glb);
+    t += r2 * KG2 * ((wl ? c.s2_kg_lds : c.s2_kg_glb) + c.s2_mfma * mb2 * pb * share);
     t += r3 * (c.s3_unit + KG3 * ((wl ? c.s3_kg_lds : c.s3_kg_glb) + c.s3_mfma * mb3 * pb * share));
     t += c.w_kb * w_kb * per_cu;
+    const int lay = d.nhwc ? 1 : 0;
+    t += per_cu * (c.x_mb[lay] * g.QB * 16.0 * d.C * 4e-6 + c.y_mb[lay] * g.PBk * 16.0 * d.N * 4e-6);
+    if (!d.nhwc) t += per_cu * (c.x_rows * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
     return c.launch + rounds * t;
 }
 
@@ -84,7 +107,8 @@ struct FusedChoice {
 
 FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &forced)
 {
-    const FusedCoef c;
+    const bool throughput = (long)d.B * d.Ho * d.Wo >= 16L * dev.cus;
+    const FusedCoef c = throughput ? fused_throughput_coef() : FusedCoef();
     FusedChoice best;
     const int th_lo = forced.tile_h ? forced.tile_h : 1, th_hi = forced.tile_h ? forced.tile_h : std::min(d.Ho, 16);
     const int tw_lo = forced.tile_w ? forced.tile_w : 1, tw_hi = forced.tile_w ? forced.tile_w : std::min(d.Wo, 32);
@@ -94,7 +118,7 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
             if (!forced.tile_w && tw < std::min(d.Wo, 4)) continue;   // keep rows long enough to coalesce
             const TdcFusedGeom g = tdc_fused_geometry(d, th, tw, dev.lds_per_wg);
             if ((long)g.lds_bytes > dev.lds_per_wg) continue;
-            for (int nw : {1, 2, 4, 8}) {
+            for (int nw : {8, 4, 2, 1}) {   // at equal estimate the first wins: more wavefronts hide more latency
                 if (forced.waves[0] && nw != forced.waves[0]) continue;
                 for (int pb : {1, 2})
                     for (int mb1 : kMb)
@@ -122,18 +146,19 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 // groups: rounds23 * (KG2 * (kg + blk2 * NB2*PB*share) + NB3 * (nb + blk3 * NB2*PB*share)).  This
 // variant serves the throughput regime, so the estimate also charges the bytes a CU pulls and
 // pushes (input tile incl. halo, output tile) and the scalar-store path taken when tile or image
-// width is not a multiple of 4, and the number of output row segments a CU writes (tiles that span
-// whole image rows store longer runs).  Fitted to ~2600 tunings of the batch-8/32 layers (median
-// relative error 11%).
+// width is not a multiple of 4, and, in NCHW, the number of row segments a CU reads and writes
+// (tiles that span whole image rows move longer runs).  Fitted to ~5200 tunings of the batch-8/32
+// layers in both activation layouts (median relative error 8%).
 struct ChainCoef {
-    double launch = 1.0626;
-    double s1_unit = 0.0, s1_kg = 0.2896, s1_mfma = 0.1063;
-    double kg2_glb = 0.1124, blk2 = 0.0;
-    double nb3_lds = 0.1759, blk3 = 0.0475;
-    double w_kb = 0.0431;
-    double x_mb = 11.5236, y_mb = 13.0568;   // per MB per CU
-    double y_rows = 4.2918;                  // per 1000 output row segments (tile rows x channels) per CU
-    double novec = 0.2391;                   // per output-channel block and pixel block stored with 4-byte stores
+    double launch = 1.9182;
+    double s1_unit = 0.0, s1_kg = 0.0967, s1_mfma = 0.1085;
+    double kg2_glb = 0.1693, blk2 = 0.0;
+    double nb3_lds = 0.2773, blk3 = 0.0457;
+    double w_kb = 0.0369;
+    double x_mb[2] = {6.3970, 11.0397};      // per MB per CU, [NCHW, NHWC]
+    double y_mb = 37.4415;
+    double x_rows = 0.5420, y_rows = 2.9268; // NCHW: per 1000 row segments (tile rows x channels) per CU, in and out
+    double novec = 0.1746;                   // per output-channel block and pixel block stored with 4-byte stores
 };
 
 double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw, int mb1,
@@ -149,12 +174,13 @@ double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, 
     const double share = std::max(1.0, per_cu * nw / 4.0);
     const bool wl = g.weights_in_lds;
     const double w_kb = wl ? (double)(d.NB2 * KG2 + d.NB3 * d.NB2) : 0.0;
-    const bool vec = g.TW % 4 == 0 && d.Wo % 4 == 0;
+    const bool vec = d.nhwc || (g.TW % 4 == 0 && d.Wo % 4 == 0);
     double t = r1 * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * mb1 * pb * share));
     t += r23 * (KG2 * ((wl ? 0.0 : c.kg2_glb) + c.blk2 * d.NB2 * pb * share) +
                 d.NB3 * ((wl ? c.nb3_lds : 0.0) + c.blk3 * d.NB2 * pb * share + (vec ? 0.0 : c.novec * pb)));
     t += c.w_kb * w_kb * per_cu;
-    t += per_cu * (c.x_mb * g.QB * 16.0 * d.C * 4e-6 + c.y_mb * g.PBk * 16.0 * d.N * 4e-6 + c.y_rows * g.TH * d.N * 1e-3);
+    t += per_cu * (c.x_mb[d.nhwc ? 1 : 0] * g.QB * 16.0 * d.C * 4e-6 + c.y_mb * g.PBk * 16.0 * d.N * 4e-6);
+    if (!d.nhwc) t += per_cu * (c.x_rows * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
     return c.launch + rounds * t;
 }
 
@@ -167,11 +193,11 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
     for (int th = th_lo; th <= th_hi; ++th)
         for (int tw = tw_lo; tw <= tw_hi; ++tw) {
             if (th * tw > 512) continue;
-            // rows of at least 16 pixels (64 bytes), and whole 16-byte quads where the image allows them
-            if (!forced.tile_w && (tw < std::min(d.Wo, 16) || (d.Wo % 4 == 0 && tw % 4))) continue;
+            // NCHW: whole 16-byte quads where the image allows them (NHWC stores are 16 bytes whatever the tile)
+            if (!forced.tile_w && !d.nhwc && d.Wo % 4 == 0 && tw % 4) continue;
             const TdcFusedGeom g = tdc_chain_geometry(d, th, tw, dev.lds_per_wg);
             if ((long)g.lds_bytes > dev.lds_per_wg) continue;
-            for (int nw : {1, 2, 4, 8}) {
+            for (int nw : {8, 4, 2, 1}) {   // at equal estimate the first wins: more wavefronts hide more latency
                 if (forced.waves[0] && nw != forced.waves[0]) continue;
                 for (int pb : {1, 2})
                     for (int mb1 : kMb) {

@@ -93,7 +93,10 @@ def test_selector_fills_a_launchable_tuning_for_every_workload():
     for cfg in range(1, 6):
         for L in config_layers(cfg):
             t = B.tdc_select_tuning(B.make_shape(**L.asdict()))
-            assert B.tdc_select_tuning(B.make_shape(**L.asdict(), layout=B.LAYOUT_NHWC)).as_dict() == t.as_dict()
+            n = B.tdc_select_tuning(B.make_shape(**L.asdict(), layout=B.LAYOUT_NHWC)).as_dict()
+            assert n["variant"] in ("split", "fused", "chain", "merged", "fused_merged"), n
+            if L.batch == 1:
+                assert n == t.as_dict()        # the latency-regime models do not depend on the layout
             d = t.as_dict()
             assert d["variant"] in ("split", "fused", "chain", "merged", "fused_merged"), d
             assert all(1 <= w <= 8 for w in d["waves"]) and all(1 <= m <= 8 for m in d["mb"])
