@@ -270,6 +270,25 @@ def main():
         "null_sync_us": null_sync_us,
         "sum_layer_latency_us": sum(p["latency_us"] for p in per_layer),
     }
+    if not args.brief:
+        # the same step replayed from a HIP graph (captured once; no memset nodes: the launch path records none)
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            cap = [conv.bind(x, y) for conv, x, y in zip(convs, xs, ys)]     # launchers carry their stream
+            for launch in cap:
+                launch()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for launch in cap:
+                    launch()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(20):
+            graph.replay()
+        out["graph_replay_us_per_step"] = _time_events(graph.replay, max(200, min(2000, args.steps)), torch) * 1e6
+        torch.cuda.synchronize()
+        del graph
     if layout == B.LAYOUT_NCHW and not args.brief:
         # the same step with pixel-major activations (tdc_shape.layout = 1): reported beside the NCHW figure
         n_convs, n_x, n_y = [], [], []
