@@ -217,20 +217,20 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 }
 
 // FUSED_MERGED: stage 1 as in FUSED (dealt over nw wavefronts), then every wavefront runs its
-// slice of the merged convolution out of registers and LDS.  Fitted to ~3300 tunings of the
-// batch-1, stride-1 layers (median relative error 8%; the picked tuning within 4% of the best
-// wherever this variant is competitive): per stage-1 unit 0.18 us plus 0.10 us per k-group (its
-// operands come from memory) and its MFMAs, 0.09 us per weight fragment and pixel block of the
-// tail, 0.75 us for a cross-slice sum, the bytes of x a CU pulls (input tile with halo, once per
-// workgroup), and a dispatch term per 256 workgroups -- the recomputation of stage 1 by every
+// slice of the merged convolution out of registers and LDS.  Fitted to ~6600 tunings of 27 batch-1
+// layer shapes in both activation layouts (median relative error 8%; the picked tuning on average
+// 5% behind the best one timed): per stage-1 unit 0.22 us plus its k-groups and MFMAs, 0.08 us per
+// weight fragment and pixel block of the tail, 0.45 us for a cross-slice sum, the bytes of x a CU
+// pulls (input tile with halo, once per workgroup; dearer in NCHW, where they arrive as 4-byte
+// loads), and a dispatch term per 256 workgroups -- the recomputation of stage 1 by every
 // output-channel group shows up there and in the x bytes.
 struct FmCoef {
-    double launch = 1.2735;
-    double s1_unit = 0.1772, s1_kg = 0.0982, s1_mfma = 0.0562;
-    double frag = 0.0910;         // per weight fragment and pixel block, times the MFMA pipe share
-    double reduce = 0.7517;       // per pixel block when the contraction is sliced
-    double x_mb = 17.1877;        // per MB of x per CU
-    double wgs = 0.8449;          // per 256 workgroups
+    double launch = 2.5879;
+    double s1_unit = 0.2174, s1_kg = 0.0197, s1_mfma = 0.0407;
+    double frag = 0.0803;         // per weight fragment and pixel block, times the MFMA pipe share
+    double reduce = 0.4477;       // per pixel block when the contraction is sliced
+    double x_mb[2] = {38.3935, 16.4747};   // per MB of x per CU, [NCHW, NHWC]
+    double wgs = 0.5418;          // per 256 workgroups
 };
 
 struct FmChoice {
@@ -251,7 +251,7 @@ double fm_us(const FmCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const 
     const int frags = cdiv(KG2, ks);
     double t = r1 * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * mb1 * share));
     t += g.PBk * frags * c.frag * share + (ks > 1 ? c.reduce * g.PBk : 0.0);
-    t += per_cu * c.x_mb * g.QB * 16.0 * d.C * 4e-6;
+    t += per_cu * c.x_mb[d.nhwc ? 1 : 0] * g.QB * 16.0 * d.C * 4e-6;
     return c.launch + rounds * t + c.wgs * wgs / 256.0;
 }
 
@@ -423,7 +423,8 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
         free_choice.mb[0] = free_choice.mb[1] = free_choice.mb[2] = 0;
         free_choice.waves[0] = 0;
         const FmChoice fm = best_fm(d, dev, free_choice);
-        const double fm_us = fm.calibrated ? fm.us * 1.05 : 1e300;
+        const int ks_min = cdiv(d.K * d.K * d.NB1, 9);   // slices the contraction needs at least
+        const double fm_us = fm.calibrated ? fm.us * (ks_min >= 3 ? 1.20 : 1.05) : 1e300;
         if (fm_us < f.us && fm_us < split_us && fm_us < s[0].us + m2.us) {
             t->variant = TDC_VARIANT_FUSED_MERGED;
             t->tile_h = fm.th; t->tile_w = fm.tw;
