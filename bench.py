@@ -141,7 +141,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default: the ResNet-18-shaped sweep)")
-    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged", "fused_merged"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"],
                     help="activation layout (default NCHW, the layout the metric's workload is stated in)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the per-layer oracle times")
@@ -166,7 +166,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     variant = {"auto": B.VARIANT_AUTO, "naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT,
-               "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN, "merged": B.VARIANT_MERGED}[args.variant]
+               "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN, "merged": B.VARIANT_MERGED,
+               "fused_merged": B.VARIANT_FUSED_MERGED}[args.variant]
 
     layout = B.LAYOUT_NHWC if args.layout == "nhwc" else B.LAYOUT_NCHW
     layers = config_layers(args.config)

@@ -12,11 +12,10 @@
 // per tile, and share >= 1 is the number of wavefronts that time-share one of the CU's four
 // MFMA pipes.  A workgroup round over the chip repeats ceil(WGs / (CUs * resident)) times and
 // one dependent launch adds a constant.  The coefficients (microseconds) were fitted by
-// non-negative least squares to exhaustive sweeps on MI355X (about 6000 fused, 4700 chain and
-// 2500 single-GEMM tunings over the batch-1 layers and the batch-8/32 variants; median relative
-// error 5-12%); they read as: a launch ~2.6-3.6 us when timed back to back, one memory
-// round trip ~1.26 us (the unit cost of stage 1, whose operands come from HBM/L2), ~0.02-0.08 us
-// per k-group of issue overhead, and a store-bound stage 3.
+// non-negative least squares to exhaustive sweeps on MI355X, separately for the latency regime
+// (batch 1: one-launch and GEMM kernels, ~2500-6600 tunings per model) and the throughput regime
+// (batch 8/32: fused and chain kernels in both activation layouts, ~12600 tunings); median
+// relative errors 5-12%.  Each coefficient struct below says what its terms stand for.
 #include <algorithm>
 #include <climits>
 #include <cmath>
