@@ -180,3 +180,33 @@ def test_nhwc_refusals():
         torch.cuda.synchronize()
     finally:
         B.tdc_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
+def test_large_batch_sampled_images(orc, layout):
+    """A batch far beyond the workloads' (200 images, 20 M elements each way): images are independent, so
+    a few sampled images are compared with the oracle's result for that image alone."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    from dataclasses import replace
+    layer = Layer(200, 128, 128, 28, 28, 32, 32)
+    one = replace(layer, batch=1)
+    _announce("large batch", layer.name(), "layout", layout)
+    inputs = make_inputs(layer, 2025)
+    dev = torch.device("cuda:0")
+    x = inputs["x"] if layout == B.LAYOUT_NCHW else nhwc(inputs["x"])
+    t = {k: torch.from_numpy(x if k == "x" else v).to(dev) for k, v in inputs.items()}
+    conv = TuckerConv2d(layer, 0, None, layout=layout)
+    try:
+        conv.pack(t["U_in"], t["core"], t["U_out"])
+        y = torch.full(conv.out_shape(), float("nan"), device=dev)
+        conv(t["x"], y)
+        torch.cuda.synchronize()
+        assert torch.isfinite(y).all()
+        got = y.cpu().numpy()
+        for b in (0, 1, 99, 198, 199):
+            want, _ = orc.conv_factored(orc.Shape(**one.asdict()), inputs["x"][b:b + 1], inputs["U_in"], inputs["core"], inputs["U_out"])
+            want = want if layout == B.LAYOUT_NCHW else nhwc(want)
+            assert_parity(got[b:b + 1], want, "image %d of 200 [%s]" % (b, conv.describe()))
+    finally:
+        conv.close()
