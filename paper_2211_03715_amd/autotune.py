@@ -8,6 +8,7 @@ launchable runs) and compares the best with what the selector's closed-form mode
 
     python -m paper_2211_03715_amd.autotune --config 2            # table: model pick vs best found
     best = autotune(layer)["best"]["tuning"]                      # a tuning to pass to TuckerConv2d
+    python -m paper_2211_03715_amd.autotune --analyse sweep.json  # no GPU: the paper's two-step tile rule on a saved sweep
 
 Stage tunings of the SPLIT and MERGED variants are independent of one another (their kernels run
 back to back), so those are searched one stage at a time around the selector's choice; that is
@@ -152,6 +153,72 @@ def autotune(L: Layer, device: int = 0, iters: int = 200, variants=("fused", "ch
     return {"layer": L.name(), "auto": auto, "best": rows[0], "by_variant": by_variant, "rows": rows}
 
 
+def paper_tile_rule(L: Layer, rows: List[Dict], cus: int = 256, top: float = 0.05) -> Dict:
+    """The paper's tile selection (sections 5.3-5.5) applied to the FUSED kernel's tilings of one layer.
+
+    Step 1, computation latency: waves of thread blocks over the chip times the latency of one block,
+    the block's FLOPs (halo positions included, as the paper counts them) over its share of the peak.
+    Here a block is a workgroup, the chip holds `cus` x resident of them at once, and a workgroup of
+    nw wavefronts can use min(nw, 4) / 4 of its CU's MFMA rate.  Step 2, data movement: among the
+    tilings within the best `top` fraction of step 1, the one that moves the fewest global bytes
+    (input tile with halo and all weights once per workgroup, the output once).
+    `rows` are timed FUSED tunings ({us, tuning, plan}); returns the row the rule selects."""
+    fused = [r for r in rows if r["tuning"]["variant"] == "fused"]
+    if not fused:
+        return {}
+    scored = []
+    for r in fused:
+        t = r["tuning"]
+        th, tw, nw = t["tile_h"], t["tile_w"], t["waves"][0]
+        qh, qw = (th - 1) * L.stride + L.K, (tw - 1) * L.stride + L.K
+        wgs = -(-L.Ho // th) * -(-L.Wo // tw) * L.batch
+        lds = int(r["plan"].split("lds=")[1].split("B")[0])
+        resident = max(1, min(160 * 1024 // max(lds, 1), 32 // nw, 8))
+        flops_blk = 2.0 * (qh * qw * L.C * L.R1 + th * tw * (L.K * L.K * L.R1 * L.R2 + L.R2 * L.N))
+        blk_peak = 157.3e12 / cus * min(nw, 4) / 4.0 / resident
+        comp = -(-wgs // (cus * resident)) * flops_blk / blk_peak
+        volume = 4.0 * (wgs * (qh * qw * L.C + L.C * L.R1 + L.R1 * L.R2 * L.K * L.K + L.R2 * L.N) + L.batch * L.N * L.Ho * L.Wo)
+        scored.append((comp, volume, r))
+    scored.sort(key=lambda x: x[0])
+    keep = scored[:max(1, int(round(top * len(scored))))]
+    # tilings that tie with the last one kept belong to the same class
+    keep += [x for x in scored[len(keep):] if x[0] <= keep[-1][0] * (1 + 1e-9)]
+    return min(keep, key=lambda x: x[1])[2]
+
+
+def analyse(path: str) -> int:
+    """Offline: on a sweep saved with --out, compare the paper's two-step rule and this library's
+    closed-form model as selectors of FUSED tilings, each against the best FUSED tuning timed."""
+    with open(path) as f:
+        results = json.load(f)
+    layers = {L.name(): L for cfg in range(1, 6) for L in config_layers(cfg)}
+    print("%-44s %9s %22s %22s" % ("layer (FUSED tunings only)", "best us", "paper's rule: us (gap)", "this model: us (gap)"))
+    gaps_p, gaps_m = [], []
+    for res in results:
+        L = layers[res["layer"]]
+        fused = [r for r in res["rows"] if r["tuning"]["variant"] == "fused"]
+        if not fused:
+            continue
+        best = min(r["us"] for r in fused)
+        rule = paper_tile_rule(L, res["rows"])
+        mine = B.tdc_select_tuning(B.make_shape(**L.asdict()), tuning=B.make_tuning(variant=B.VARIANT_FUSED)).as_dict()
+        same = [r for r in fused if all(r["tuning"][k] == mine[k] for k in ("tile_h", "tile_w", "mb", "pb")) and
+                r["tuning"]["waves"][0] == mine["waves"][0]]
+        gp = rule["us"] / best - 1.0
+        gaps_p.append(gp)
+        cell = "not in the sweep"
+        if same:
+            gm = same[0]["us"] / best - 1.0
+            gaps_m.append(gm)
+            cell = "%6.2f (%4.1f%%)" % (same[0]["us"], 100 * gm)
+        print("%-44s %9.2f %15.2f (%4.1f%%) %22s" % (L.name(), best, rule["us"], 100 * gp, cell))
+    print("paper's rule behind the best FUSED tuning: mean %.1f%%, max %.1f%%" % (100 * sum(gaps_p) / len(gaps_p), 100 * max(gaps_p)))
+    if gaps_m:
+        print("this library's model (on the %d layers whose pick was timed): mean %.1f%%, max %.1f%%" % (
+            len(gaps_m), 100 * sum(gaps_m) / len(gaps_m), 100 * max(gaps_m)))
+    return 0
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--config", type=int, nargs="*", default=[2])
@@ -159,7 +226,11 @@ def main(argv=None) -> int:
     ap.add_argument("--variants", nargs="*", default=["fused", "chain", "split", "merged", "fused_merged"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"])
     ap.add_argument("--out", default=None, help="JSON with every timed tuning")
+    ap.add_argument("--analyse", default=None, metavar="JSON", help="no GPU: the paper's two-step tile rule on a sweep saved with --out")
     args = ap.parse_args(argv)
+    if args.analyse:
+        B.load()
+        return analyse(args.analyse)
     import torch
     if not torch.cuda.is_available():
         sys.exit("autotune needs a GPU")

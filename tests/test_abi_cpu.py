@@ -184,3 +184,28 @@ int main() {
     subprocess.run([cxx, "-O2", "-I", inc, str(src), "-o", str(exe)], check=True)
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout[-2000:]
+
+
+def test_paper_tile_rule_orders_by_computation_then_by_data_movement():
+    """Host logic of the offline analysis: the paper's rule keeps the tilings of least computation latency
+    (waves x per-block latency, halo included) and among those takes the one that moves the fewest bytes."""
+    from paper_2211_03715_amd.autotune import paper_tile_rule
+    from paper_2211_03715_amd.workloads import Layer
+    L = Layer(1, 64, 64, 56, 56, 16, 16)
+
+    def row(th, tw, nw, lds, us):
+        return {"us": us, "plan": "fused tile=%dx%d lds=%dB" % (th, tw, lds),
+                "tuning": {"variant": "fused", "tile_h": th, "tile_w": tw, "waves": [nw] * 3, "mb": [1, 1, 1], "pb": [1, 1, 1]}}
+
+    # one resident workgroup per CU (100 KB of LDS).  7x8 and 8x7 tiles: 56 workgroups, one wave of blocks,
+    # the same halo area -> the same computation latency and the same traffic.  14x8: 28 workgroups, also one
+    # wave, but each block has about twice the FLOPs -> more computation latency, fewer bytes moved.
+    rows = [row(7, 8, 4, 100000, 3.0), row(8, 7, 4, 100000, 2.0), row(14, 8, 4, 100000, 1.0)]
+    assert paper_tile_rule(L, rows, top=0.05)["tuning"]["tile_h"] in (7, 8)       # step 1 decides, whatever the timings
+    pick = paper_tile_rule(L, rows, top=1.0)                                      # all kept: step 2 decides
+    assert (pick["tuning"]["tile_h"], pick["tuning"]["tile_w"]) == (14, 8)
+    # two waves of blocks double the latency: 1x8 tiles (392 workgroups) lose to 2x8 tiles (196) of twice the block size
+    # only if a block's latency less than doubles -- it does (halo rows 3 -> 4), so step 1 prefers 2x8
+    rows = [row(1, 8, 4, 100000, 1.0), row(2, 8, 4, 100000, 2.0)]
+    assert paper_tile_rule(L, rows, top=0.05)["tuning"]["tile_h"] == 2
+    assert paper_tile_rule(L, [r for r in rows if r["tuning"]["variant"] != "fused"]) == {}
