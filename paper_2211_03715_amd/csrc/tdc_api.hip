@@ -1,7 +1,9 @@
 // C ABI of libtdc.so: plans, validation, weight re-layout bookkeeping and launch dispatch.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "tdc_internal.h"
 
@@ -185,6 +187,32 @@ void describe(tdc_plan &p)
 
 }  // namespace
 
+hipError_t tdc_allow_lds(const void *fn, size_t bytes)
+{
+    if (bytes <= 48 * 1024) return hipSuccess;
+    struct Granted {
+        const void *fn;
+        int device;
+        size_t bytes;
+    };
+    static std::mutex lock;
+    static std::vector<Granted> table;
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> hold(lock);
+    for (Granted &g : table)
+        if (g.fn == fn && g.device == device) {
+            if (g.bytes >= bytes) return hipSuccess;
+            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e == hipSuccess) g.bytes = bytes;
+            return e;
+        }
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) table.push_back(Granted{fn, device, bytes});
+    return e;
+}
+
 extern "C" {
 
 int tdc_version(void) { return 100; }
@@ -290,6 +318,22 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
         (void)hipGetLastError();
         tdc_plan_destroy(p);
         return TDC_ERR_ALLOC;
+    }
+    // whatever a first launch would have to set up, now: a conv call may be the first thing a capturing stream sees
+    {
+        const TdcEpi none{nullptr, nullptr, 0};
+        hipError_t e = hipSuccess;
+        if (p->tuning.variant == TDC_VARIANT_FUSED)
+            e = tdc_launch_fused(d, p->tuning, p->geom, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, none, true);
+        else if (p->tuning.variant == TDC_VARIANT_CHAIN)
+            e = tdc_launch_chain(d, p->tuning, p->geom, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, none, true);
+        else if (p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
+            e = tdc_launch_fm(d, p->tuning, p->geom, nullptr, nullptr, nullptr, nullptr, nullptr, none, true);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            tdc_plan_destroy(p);
+            return TDC_ERR_HIP;
+        }
     }
     describe(*p);
     *out = p;

@@ -286,7 +286,7 @@ TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int ld
 
 hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
-                            const float *uout_p, float *y, const TdcEpi &epi)
+                            const float *uout_p, float *y, const TdcEpi &epi, bool prepare_only)
 {
     ChainArgs a;
     a.epi = epi;
@@ -306,11 +306,10 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_LAUNCH(N_, P_, W_, L_)                                                                     \
     {                                                                                                  \
-        if (g.lds_bytes > 48 * 1024) {                                                                 \
-            hipError_t e = hipFuncSetAttribute((const void *)tdc_chain_kernel<N_, P_, W_, L_>,         \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,             \
-                                               (int)g.lds_bytes);                                      \
+        {                                                                                              \
+            hipError_t e = tdc_allow_lds((const void *)tdc_chain_kernel<N_, P_, W_, L_>, g.lds_bytes);    \
             if (e != hipSuccess) return e;                                                             \
+            if (prepare_only) return hipSuccess;                                                       \
         }                                                                                              \
         hipLaunchKernelGGL((tdc_chain_kernel<N_, P_, W_, L_>), grid, block, g.lds_bytes, s, a);        \
         return hipGetLastError();                                                                      \

@@ -221,7 +221,7 @@ TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, i
 }
 
 hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s, const float *x,
-                         const float *uin_p, const float *wm_p, float *y, const TdcEpi &epi)
+                         const float *uin_p, const float *wm_p, float *y, const TdcEpi &epi, bool prepare_only)
 {
     FmArgs a;
     a.epi = epi;
@@ -242,12 +242,11 @@ hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGe
     dim3 grid((unsigned)(a.tiles * (d.NB3 / a.NBG)), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_FM_LAUNCH(M_, P_, L_)                                                                  \
     {                                                                                              \
-        if (g.lds_bytes > 48 * 1024) {                                                             \
-            hipError_t e = hipFuncSetAttribute((const void *)tdc_fm_kernel<M_, P_, L_>,            \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,         \
-                                               (int)g.lds_bytes);                                  \
-            if (e != hipSuccess) return e;                                                         \
-        }                                                                                          \
+        {                                                                                              \
+            hipError_t e = tdc_allow_lds((const void *)tdc_fm_kernel<M_, P_, L_>, g.lds_bytes);    \
+            if (e != hipSuccess) return e;                                                             \
+            if (prepare_only) return hipSuccess;                                                       \
+        }                                                                                              \
         hipLaunchKernelGGL((tdc_fm_kernel<M_, P_, L_>), grid, block, g.lds_bytes, s, a);           \
         return hipGetLastError();                                                                  \
     }

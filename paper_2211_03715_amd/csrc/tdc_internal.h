@@ -41,6 +41,11 @@ struct TdcDims {
     int nhwc;            // activations x, y (and an epilogue's residual) are [B][H][W][channels]; C % 4 == N % 4 == 0
 };
 
+// Raises the dynamic-LDS limit of kernel `fn` to at least `bytes` on the current device.  The HIP
+// attribute call is made once per kernel, device and size (a table remembers what was granted),
+// so a launch path may call this every time; nothing is done for sizes the default limit covers.
+hipError_t tdc_allow_lds(const void *fn, size_t bytes);
+
 // ---- weight re-layout (tdc_pack.hip)
 hipError_t tdc_launch_pack(const TdcDims &d, hipStream_t s, const float *U_in, const float *core,
                            const float *U_out, float *uin_p, float *core_p, float *uout_p);
@@ -70,6 +75,9 @@ hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s
 hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
                              const float *uin_p, const float *wm_p, float *z1, float *y, const TdcEpi &epi);
 
+// The one-launch kernels' launchers take `prepare_only`: do what must precede a first launch (raise the
+// kernel's LDS limit) and return without launching, so that plan creation can get it out of the way
+// of a later stream capture.
 // ---- fused MFMA kernel (tdc_fused.hip)
 struct TdcFusedGeom {
     int TH, TW;          // output tile
@@ -84,14 +92,14 @@ bool tdc_fused_unit_supported(int mb1, int mb2, int mb3, int pb);
 TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit);
 hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
-                            const float *uout_p, float *y, const TdcEpi &epi);
+                            const float *uout_p, float *y, const TdcEpi &epi, bool prepare_only = false);
 
 // ---- fused MFMA kernel with stages 2 and 3 chained in registers (tdc_chain.hip)
 bool tdc_chain_supported(int nb2, int mb1, int pb);
 TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit);
 hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
-                            const float *uout_p, float *y, const TdcEpi &epi);
+                            const float *uout_p, float *y, const TdcEpi &epi, bool prepare_only = false);
 
 // ---- one-launch kernel: stage 1 into LDS, then the merged stage-2/3 convolution (tdc_fm.hip).
 // Tuning fields: tile_h, tile_w, waves[0], mb[0] = stage-1 register tile, mb[1] = output-channel
@@ -99,7 +107,7 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
 bool tdc_fm_supported(const TdcDims &d, int tile_h, int tile_w, int nw, int mb1, int nbg);
 TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int nbg);
 hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s, const float *x,
-                         const float *uin_p, const float *wm_p, float *y, const TdcEpi &epi);
+                         const float *uin_p, const float *wm_p, float *y, const TdcEpi &epi, bool prepare_only = false);
 
 // ---- selector (tdc_select.cpp): fills every zero field of `t`
 struct TdcDeviceInfo {

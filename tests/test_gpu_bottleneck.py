@@ -58,3 +58,42 @@ def test_bottleneck_eager_and_graph(orc, shape, layout):
                 assert_parity(eager.cpu().numpy(), want, "eager between replays")
     finally:
         blk.close()
+
+
+@pytest.mark.parametrize("variant", [B.VARIANT_FUSED, B.VARIANT_CHAIN], ids=["fused", "chain"])
+def test_large_lds_kernels_under_graph_capture(orc, variant):
+    """The throughput kernels ask for more dynamic LDS than the default limit; that request must not disturb
+    a capture (it is made before the first launch and remembered), and every replay must match the oracle."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    from paper_2211_03715_amd.workloads import Layer, make_inputs
+    layer = Layer(8, 128, 128, 28, 28, 32, 32)
+    print("[case] graph capture, large LDS", layer.name(), variant, flush=True)
+    sys.stdout.flush()
+    dev = torch.device("cuda:0")
+    sets = [make_inputs(layer, seed) for seed in (31, 32)]
+    sets[1] = dict(sets[0], x=sets[1]["x"])          # one set of weights (the packed one), two inputs
+    wants = [orc.conv_factored(orc.Shape(**layer.asdict()), **inp)[0] for inp in sets]
+    t = {k: torch.from_numpy(v).to(dev) for k, v in sets[0].items()}
+    conv = TuckerConv2d(layer, 0, B.make_tuning(variant=variant, tile_h=4, tile_w=28, waves=(8, 8, 8)))
+    try:
+        assert "lds=" in conv.describe() and int(conv.describe().split("lds=")[1].split("B")[0]) > 48 * 1024
+        conv.pack(t["U_in"], t["core"], t["U_out"])
+        x_static = torch.empty_like(t["x"])
+        y = torch.full(conv.out_shape(), float("nan"), device=dev)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):          # the very first launch of this plan is the captured one
+            conv.bind(x_static, y)()
+        for rep in range(3):
+            for inp, want in zip(sets, wants):
+                x_static.copy_(torch.from_numpy(inp["x"]).to(dev))
+                y.fill_(float("nan"))
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                assert_parity(y.cpu().numpy(), want, "replay %d [%s]" % (rep, conv.describe()))
+                eager = conv(x_static)
+                torch.cuda.synchronize()
+                assert torch.equal(eager, y)
+    finally:
+        conv.close()
