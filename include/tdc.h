@@ -12,14 +12,16 @@
  *
  * All tensor arguments are DEVICE pointers to contiguous fp32 arrays, at least
  * 16-byte aligned, resident on the plan's device:
- *   x      [batch][C][H][W]          input, NCHW
+ *   x      [batch][C][H][W]          input (layout 0, NCHW; layout 1: [batch][H][W][C])
  *   U_in   [C][R1]                   U1(c,d1)
  *   core   [R1][R2][K][K]            core(d1,d2,r,s)  (mode 1 contracts with U_in,
  *                                    mode 2 with U_out; cross-correlation, no flip)
  *   U_out  [R2][N]                   U2(d2,n) as Eq. 4 uses it
- *   y      [batch][N][Ho][Wo]        output, NCHW, Ho = floor((H+2*pad-K)/stride)+1
+ *   y      [batch][N][Ho][Wo]        output (layout 1: [batch][Ho][Wo][N]),
+ *                                    Ho = floor((H+2*pad-K)/stride)+1
  * Zero padding `pad` and `stride` apply to the core convolution; stage 1 runs on
- * every input pixel.  There is no bias or activation: the layer is linear in x.
+ * every input pixel.  tdc_conv_tucker2 applies no bias or activation: the layer is
+ * linear in x.  The _ex entry points add an optional fused epilogue (see tdc_epilogue).
  *
  * Ownership: the caller owns x, the weights, y and the stream.  The library
  * never frees or reallocates them.  A plan owns its workspace (intermediates
@@ -27,9 +29,10 @@
  * overwritten; x and y must not overlap.  A plan may be used by one stream at
  * a time (its workspace is not re-entrant).
  *
- * Asynchrony: tdc_conv_tucker2 and tdc_plan_pack_weights only enqueue work on
- * the given stream (NULL = the default stream) and return; they never
- * synchronise with the host and never allocate.
+ * Asynchrony: the conv and pack entry points only enqueue work on the given
+ * stream (NULL = the default stream) and return; they never synchronise with
+ * the host and never allocate, and a conv call with re-laid-out weights enqueues
+ * nothing but its kernels, so it may be captured into a HIP graph.
  *
  * Errors: every function returns a tdc_status (0 = success, negative =
  * failure).  Nothing aborts, throws or prints.
