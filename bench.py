@@ -237,6 +237,8 @@ def main():
     null_us = _time_events(lambda: null_fn(null_stream), 2000, torch) * 1e6
     null_sync_us = _time_sync(lambda: null_fn(null_stream), 200, torch) * 1e6
 
+    for row in per_layer:
+        row["null_launch_us"] = null_us          # the floor any launch pays, beside every latency
     dom = max(range(len(layers)), key=lambda i: per_layer[i]["latency_us"])
     Ld, pd = layers[dom], per_layer[dom]
     sec = pd["latency_us"] * 1e-6
@@ -319,6 +321,8 @@ def main():
         if not args.brief:
             for row, L, inp in zip(per_layer, layers, host_inputs):
                 row["oracle_us"] = oracle_layer_times(L, inp)
+                # a reported baseline, not a target: the oracle on one image, all host threads, against the layer per image
+                row["speedup_vs_oracle"] = row["oracle_us"]["factored_all"] * L.batch / row["latency_us"]
     if args.copy_mib > 0:
         src = torch.empty(args.copy_mib * 262144, device=dev, dtype=torch.float32).normal_()
         dst = torch.empty_like(src)
