@@ -221,6 +221,36 @@ def test_linearity_and_batch_independence_on_gpu(orc):
         assert np.array_equal(y2, 2.0 * yb), "scaling x by 2 must scale y by exactly 2"
 
 
+def test_two_plans_on_two_streams(orc):
+    """Calls only enqueue on the stream they are given: two layers with plans of their own run on two
+    non-default streams at once, repeatedly, and each matches the oracle (no hidden use of the default stream,
+    no workspace shared between plans)."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    dev = torch.device("cuda:0")
+    cases = []
+    for layer, variant, seed in ((Layer(1, 256, 256, 14, 14, 64, 64), B.VARIANT_MERGED, 5),
+                                 (Layer(2, 64, 64, 28, 28, 16, 16), B.VARIANT_SPLIT, 6)):
+        _announce("streams", layer.name(), variant)
+        inputs = make_inputs(layer, seed)
+        t = {k: torch.from_numpy(v).to(dev) for k, v in inputs.items()}
+        conv = TuckerConv2d(layer, 0, B.make_tuning(variant=variant))
+        conv.pack(t["U_in"], t["core"], t["U_out"])
+        y = torch.full(conv.out_shape(), float("nan"), device=dev)
+        cases.append((conv, t, y, _oracle(orc, layer, inputs), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    try:
+        for _ in range(20):
+            for conv, t, y, _, stream in cases:
+                conv(t["x"], y, stream=stream)
+        for conv, t, y, want, stream in cases:
+            stream.synchronize()
+            assert_parity(y.cpu().numpy(), want, conv.describe())
+    finally:
+        for conv, *_ in cases:
+            conv.close()
+
+
 def test_error_paths_on_device():
     import ctypes
     import torch
