@@ -204,7 +204,7 @@ def main():
     iters = max(200, min(2000, args.steps))
     per_layer = []
     for i, (L, conv, launch) in enumerate(zip(layers, convs, launchers)):
-        for _ in range(20):
+        for _ in range(200):                      # clocks and caches settled before the timed launches
             launch()
         sec = _time_events(launch, iters, torch)
         bound, t_roof, t_hbm, t_mfma = R.roofline(L)
