@@ -222,6 +222,8 @@ def analyse(path: str) -> int:
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--config", type=int, nargs="*", default=[2])
+    ap.add_argument("--shapes", nargs="*", default=[], metavar="B,C,N,H,W,R1,R2[,K,stride,pad]",
+                    help="layers of one's own instead of --config, e.g. 1,96,96,28,28,24,24")
     ap.add_argument("--iters", type=int, default=200)
     ap.add_argument("--variants", nargs="*", default=["fused", "chain", "split", "merged", "fused_merged"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"])
@@ -237,9 +239,11 @@ def main(argv=None) -> int:
     B.load()
     results = []
     print("%-46s %9s %9s %7s  %s" % ("layer", "model us", "best us", "gap", "best plan"), flush=True)
-    for cfg in args.config:
+    groups = [[Layer(*[int(v) for v in spec.split(",")]) for spec in args.shapes]] if args.shapes else \
+             [config_layers(cfg) for cfg in args.config]
+    for layers in groups:
         seen = set()
-        for L in config_layers(cfg):
+        for L in layers:
             if L.name() in seen:
                 continue
             seen.add(L.name())
