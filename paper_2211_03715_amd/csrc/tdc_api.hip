@@ -98,6 +98,7 @@ TdcDims make_dims(const tdc_shape &s)
     d.NB1 = (s.R1 + 15) / 16; d.NB2 = (s.R2 + 15) / 16; d.NB3 = (s.N + 15) / 16;
     d.KG1 = (s.C + 15) / 16;
     d.nhwc = s.layout == 1;
+    d.s1_runs = 0;       // decided with the variant, see tdc_plan_create_tuned
     return d;
 }
 
@@ -269,6 +270,13 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     p->device = device;
     if (forced) p->tuning = *forced;
     rc = tdc_select(p->dims, dev, &p->tuning, &p->model_us);
+    // The throughput kernels read NCHW activations in 16-byte runs where the rows allow it.  (Not the
+    // latency regime: a run-major unit is 64 pixels, and the small tiles chosen there would mostly pad it --
+    // measured 0.4 to 2.6 us slower per batch-1 layer.)
+    if (rc == TDC_OK && !p->dims.nhwc && p->dims.W % 4 == 0 &&
+        (long)p->dims.B * p->dims.Ho * p->dims.Wo >= 16L * dev.cus &&
+        (p->tuning.variant == TDC_VARIANT_FUSED || p->tuning.variant == TDC_VARIANT_CHAIN))
+        p->dims.s1_runs = 1;
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)
         p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_CHAIN)
@@ -420,6 +428,7 @@ int tdc_conv_tucker2_ex(tdc_plan *p, void *hip_stream, const float *x, const flo
     if (!same_shape(*shape, p->shape)) return TDC_ERR_SHAPE_MISMATCH;
     if (p->tuning.variant == TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
     if (p->dims.nhwc && misaligned16(x, y, epi.residual)) return TDC_ERR_UNSUPPORTED;
+    if (p->dims.s1_runs && misaligned16(x, nullptr, nullptr)) return TDC_ERR_UNSUPPORTED;
     DeviceGuard guard(p->device);
     if (!guard.ok) return TDC_ERR_HIP;
     hipStream_t s = (hipStream_t)hip_stream;

@@ -33,6 +33,8 @@ struct ChainArgs {
     int pitch1;             // LDS row pitch of the z1 tile, in 16-byte cells
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
     int mb1;                // stage-1 register tile height (1, 2 or 4 channel blocks)
+    int QH, RPR, n_sb;      // run-major stage 1: tile rows, runs per row, 64-pixel blocks of runs
+    TdcDiv div_RPR, div_nsb;
     int vec;                // 1: tile width, image width and tile origin are multiples of 4 -> 16-byte stores
     TdcEpi epi;
     TdcDiv div_tiles_x, div_QW, div_TW, div_npg1;   // launch-time constant divisors (npg1: stage-1 pixel groups)
@@ -51,7 +53,7 @@ __device__ __forceinline__ void tdc_buf_store4(tdc_rsrc r, unsigned byte_off, td
 
 // Stage 1 (Eq. 2) for the whole workgroup: z1 tile = U_in^T x into LDS cells, and the weights of
 // stages 2 and 3 into LDS when they fit (their first loads travel while stage 1 computes).
-template <int MB1, int PB, bool NHWC>
+template <int MB1, int PB, int LAY>
 __device__ __forceinline__ void chain_stage1(const ChainArgs &a, tdc_f4 *__restrict__ z1s, int lane, int wave, int nw,
                                              int b, int h0, int w0, tdc_f4 *__restrict__ wC, bool copy_weights)
 {
@@ -60,26 +62,37 @@ __device__ __forceinline__ void chain_stage1(const ChainArgs &a, tdc_f4 *__restr
     sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
     sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
     sg.div_QW = a.div_QW; sg.div_npg = a.div_npg1;
-    TdcStage1<MB1, PB, (MB1 * PB >= 8 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);   // k-groups per operand buffer
-    s1.prefetch();
+    sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR; sg.div_nsb = a.div_nsb;
     const tdc_f4 *__restrict__ core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
     const tdc_f4 *__restrict__ uout4 = reinterpret_cast<const tdc_f4 *>(a.uout_p);
-    TdcWeightCopy<8> wc;
-    if (copy_weights) wc.load(core4, a.w_core4, uout4, a.w_uout4, 0);
-    s1.run(z1s);
-    if (copy_weights) {
-        const int n = a.w_core4 + a.w_uout4, round = 8 * (int)blockDim.x;
-        wc.store(wC, n, 0);
-        for (int base = round; base < n; base += round) {
-            wc.load(core4, a.w_core4, uout4, a.w_uout4, base);
-            wc.store(wC, n, base);
+    const auto stage1 = [&](auto &s1) {
+        s1.prefetch();
+        TdcWeightCopy<8> wc;
+        if (copy_weights) wc.load(core4, a.w_core4, uout4, a.w_uout4, 0);
+        s1.zero_outside(z1s);
+        s1.run(z1s);
+        if (copy_weights) {
+            const int n = a.w_core4 + a.w_uout4, round = 8 * (int)blockDim.x;
+            wc.store(wC, n, 0);
+            for (int base = round; base < n; base += round) {
+                wc.load(core4, a.w_core4, uout4, a.w_uout4, base);
+                wc.store(wC, n, base);
+            }
         }
+    };
+    if constexpr (LAY == TDC_LAY_NCHW_RUNS) {
+        TdcStage1R<MB1, (MB1 >= 4 ? 1 : 2)> s1(sg, lane, wave, nw);
+        stage1(s1);
+    } else {
+        TdcStage1<MB1, PB, (MB1 * PB >= 8 ? 2 : 4), LAY == TDC_LAY_NHWC> s1(sg, lane, wave, nw);   // k-groups per operand buffer
+        stage1(s1);
     }
 }
 
-template <int NB2, int PB, bool WLDS, bool NHWC>
+template <int NB2, int PB, bool WLDS, int LAY>
 __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
 {
+    constexpr bool NHWC = LAY == TDC_LAY_NHWC;
     extern __shared__ tdc_f4 lds4[];
     tdc_f4 *__restrict__ z1s = lds4;                                  // [NB1][4][pitch1]
     tdc_f4 *__restrict__ wC = z1s + (size_t)4 * a.NB1 * a.pitch1;     // packed core   (WLDS)
@@ -95,9 +108,9 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
     TDC_PROBE(0);
     // ------------------------------------------------------------------ stage 1 (Eq. 2)
     {
-        if (a.mb1 == 4) chain_stage1<4, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
-        else if (a.mb1 == 2) chain_stage1<2, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
-        else chain_stage1<1, PB, NHWC>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
+        if (a.mb1 == 4) chain_stage1<4, PB, LAY>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
+        else if (a.mb1 == 2) chain_stage1<2, PB, LAY>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
+        else chain_stage1<1, PB, LAY>(a, z1s, lane, wave, nw, b, h0, w0, wC, WLDS);
     }
     TDC_PROBE(3);
     __syncthreads();
@@ -300,6 +313,11 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.w_core4 = (int)(tdc_packed_floats_core(d) / 4);
     a.w_uout4 = (int)(tdc_packed_floats_uout(d) / 4);
     a.mb1 = t.mb[0];
+    a.QH = g.QH;
+    a.RPR = tdc_runs_per_row(d.W, d.Wo, g.TW, d.K, d.stride, d.pad);
+    a.n_sb = (g.QH * a.RPR + 15) / 16;
+    a.div_RPR = tdc_make_div((unsigned)a.RPR); a.div_nsb = tdc_make_div((unsigned)a.n_sb);
+    const int lay = d.nhwc ? TDC_LAY_NHWC : d.s1_runs ? TDC_LAY_NCHW_RUNS : TDC_LAY_NCHW;
     a.vec = (g.TW % 4 == 0 && d.Wo % 4 == 0) ? 1 : 0;
     a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
     a.div_TW = tdc_make_div((unsigned)g.TW); a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
@@ -316,7 +334,9 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     }
 #define TDC_LAYOUT(N_, P_, W_)                                                                         \
     {                                                                                                  \
-        if (d.nhwc) TDC_LAUNCH(N_, P_, W_, true) else TDC_LAUNCH(N_, P_, W_, false)                    \
+        if (lay == TDC_LAY_NHWC) TDC_LAUNCH(N_, P_, W_, TDC_LAY_NHWC)                                  \
+        else if (lay == TDC_LAY_NCHW_RUNS) TDC_LAUNCH(N_, P_, W_, TDC_LAY_NCHW_RUNS)                   \
+        else TDC_LAUNCH(N_, P_, W_, TDC_LAY_NCHW)                                                      \
     }
 #define TDC_X(N_)                                                                                      \
     if (d.NB2 == N_) {                                                                                 \

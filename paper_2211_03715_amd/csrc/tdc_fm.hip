@@ -37,11 +37,14 @@ struct FmArgs {
     int kg_q, kg_r;         // KG2 = KS * kg_q + kg_r: the first kg_r slices take kg_q + 1 k-groups
     TdcEpi epi;
     TdcDiv div_tiles, div_tiles_x, div_NBG, div_QB, div_QW, div_TW, div_NB1, div_K;   // constant divisors
+    int QH, RPR, n_sb;      // run-major stage 1: tile rows, runs per row, 64-pixel blocks of runs
+    TdcDiv div_RPR, div_nsb;
 };
 
-template <int MB1, int PBK, bool NHWC>
+template <int MB1, int PBK, int LAY>
 __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
 {
+    constexpr bool NHWC = LAY == TDC_LAY_NHWC;
     extern __shared__ tdc_f4 lds4[];
     tdc_f4 *__restrict__ z1s = lds4;                                   // [NB1][4][pitch1]
     tdc_f4 *__restrict__ red = z1s + (size_t)4 * a.NB1 * a.pitch1;     // [wave][PBK][64]   (KS > 1)
@@ -71,18 +74,26 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
         sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
         sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
         sg.div_QW = a.div_QW; sg.div_npg = a.div_QB;
-        TdcStage1<MB1, 1, (MB1 >= 4 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);
-        s1.prefetch();
-        // The weight fragments of stage 2+3 go out right behind the first stage-1 operands: loads
-        // return in order, so stage 1 can start as soon as its own data is there while these are
-        // still in flight; a dead fragment (past the slice) reads as zero.
-        {
+        sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR; sg.div_nsb = a.div_nsb;
+        const auto stage1 = [&](auto &s1) {
+            s1.prefetch();
+            // The weight fragments of stage 2+3 go out right behind the first stage-1 operands: loads
+            // return in order, so stage 1 can start as soon as its own data is there while these are
+            // still in flight; a dead fragment (past the slice) reads as zero.
             const tdc_rsrc wrs = tdc_make_rsrc(a.wm_p + (size_t)nb * KG2 * 256, (unsigned)KG2 * 1024u);
 #pragma unroll
             for (int f = 0; f < FM_FR; ++f)
                 wfrag[f] = tdc_buf_load4(wrs, ((unsigned)(kg0 + f) * 1024u + lane * 16u) | (kg0 + f < kg1 ? 0u : TDC_OOB));
+            s1.zero_outside(z1s);
+            s1.run(z1s);
+        };
+        if constexpr (LAY == TDC_LAY_NCHW_RUNS) {
+            TdcStage1R<MB1, (MB1 >= 4 ? 1 : 2)> s1(sg, lane, wave, nw);
+            stage1(s1);
+        } else {
+            TdcStage1<MB1, 1, (MB1 >= 4 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);
+            stage1(s1);
         }
-        s1.run(z1s);
     }
     TDC_PROBE(2);
     __syncthreads();
@@ -239,6 +250,11 @@ hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGe
     a.div_NBG = tdc_make_div((unsigned)a.NBG); a.div_QB = tdc_make_div((unsigned)a.QB);
     a.div_QW = tdc_make_div((unsigned)a.QW); a.div_TW = tdc_make_div((unsigned)a.TW);
     a.div_NB1 = tdc_make_div((unsigned)a.NB1); a.div_K = tdc_make_div((unsigned)a.K);
+    a.QH = g.QH;
+    a.RPR = tdc_runs_per_row(d.W, d.Wo, g.TW, d.K, d.stride, d.pad);
+    a.n_sb = (g.QH * a.RPR + 15) / 16;
+    a.div_RPR = tdc_make_div((unsigned)a.RPR); a.div_nsb = tdc_make_div((unsigned)a.n_sb);
+    const int lay = d.nhwc ? TDC_LAY_NHWC : d.s1_runs ? TDC_LAY_NCHW_RUNS : TDC_LAY_NCHW;
     dim3 grid((unsigned)(a.tiles * (d.NB3 / a.NBG)), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_FM_LAUNCH(M_, P_, L_)                                                                  \
     {                                                                                              \
@@ -252,7 +268,9 @@ hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGe
     }
 #define TDC_FM_CASE(M_, P_)                                                                        \
     if (t.mb[0] == M_ && g.PBk == P_) {                                                            \
-        if (d.nhwc) TDC_FM_LAUNCH(M_, P_, true) else TDC_FM_LAUNCH(M_, P_, false)                  \
+        if (lay == TDC_LAY_NHWC) TDC_FM_LAUNCH(M_, P_, TDC_LAY_NHWC)                               \
+        else if (lay == TDC_LAY_NCHW_RUNS) TDC_FM_LAUNCH(M_, P_, TDC_LAY_NCHW_RUNS)                \
+        else TDC_FM_LAUNCH(M_, P_, TDC_LAY_NCHW)                                                   \
     }
     TDC_FM_CASE(1, 1) TDC_FM_CASE(1, 2) TDC_FM_CASE(1, 3) TDC_FM_CASE(1, 4)
     TDC_FM_CASE(2, 1) TDC_FM_CASE(2, 2) TDC_FM_CASE(2, 3) TDC_FM_CASE(2, 4)

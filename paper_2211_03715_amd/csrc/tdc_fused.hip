@@ -42,6 +42,8 @@ struct FusedArgs {
     int tiles_x;
     int pitch1, pitch2;     // LDS row pitches of the z1 / z2 tiles, in 16-byte units
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
+    int QH, RPR, n_sb;      // run-major stage 1: tile rows, runs per row, 64-pixel blocks of runs
+    TdcDiv div_RPR, div_nsb;
     TdcEpi epi;
     TdcDiv div_tiles_x, div_QW, div_TW, div_npg1, div_npg2;   // launch-time constant divisors (pixel groups of stage 1 / stages 2, 3)
 };
@@ -51,9 +53,10 @@ struct FusedArgs {
 // exactly the B operand of the next stage for k-group cb (see tdc_mfma.h).
 __device__ __forceinline__ int tdc_cell(int cb, int g, int pitch, int col) { return (cb * 4 + g) * pitch + col; }
 
-template <int MB1, int MB2, int MB3, int PB, bool WLDS, bool NHWC>
+template <int MB1, int MB2, int MB3, int PB, bool WLDS, int LAY>
 __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
 {
+    constexpr bool NHWC = LAY == TDC_LAY_NHWC;
     extern __shared__ tdc_f4 lds4[];
     tdc_f4 *__restrict__ z1s = lds4;                                  // [NB1][4][pitch1]
     tdc_f4 *__restrict__ z2s = z1s + (size_t)4 * a.NB1 * a.pitch1;    // [NB2][4][pitch2]
@@ -76,24 +79,34 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
         sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
         sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
         sg.div_QW = a.div_QW; sg.div_npg = a.div_npg1;
-        TdcStage1<MB1, PB, (MB1 * PB >= 8 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);   // k-groups per operand buffer
-        s1.prefetch();
-        TDC_PROBE(1);
-        // core and U_out -> LDS: the first round's loads are issued here, behind the first stage-1
-        // operands, and stored after stage 1
+        sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR; sg.div_nsb = a.div_nsb;
         const tdc_f4 *__restrict__ core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
         const tdc_f4 *__restrict__ uout4 = reinterpret_cast<const tdc_f4 *>(a.uout_p);
-        TdcWeightCopy<8> wc;
-        if (WLDS) wc.load(core4, a.w_core4, uout4, a.w_uout4, 0);
-        TDC_PROBE(2);
-        s1.run(z1s);
-        if (WLDS) {
-            const int n = a.w_core4 + a.w_uout4, round = 8 * (int)blockDim.x;
-            wc.store(wC, n, 0);
-            for (int base = round; base < n; base += round) {
-                wc.load(core4, a.w_core4, uout4, a.w_uout4, base);
-                wc.store(wC, n, base);
+        const auto stage1 = [&](auto &s1) {
+            s1.prefetch();
+            TDC_PROBE(1);
+            // core and U_out -> LDS: the first round's loads are issued here, behind the first stage-1
+            // operands, and stored after stage 1
+            TdcWeightCopy<8> wc;
+            if (WLDS) wc.load(core4, a.w_core4, uout4, a.w_uout4, 0);
+            TDC_PROBE(2);
+            s1.zero_outside(z1s);
+            s1.run(z1s);
+            if (WLDS) {
+                const int n = a.w_core4 + a.w_uout4, round = 8 * (int)blockDim.x;
+                wc.store(wC, n, 0);
+                for (int base = round; base < n; base += round) {
+                    wc.load(core4, a.w_core4, uout4, a.w_uout4, base);
+                    wc.store(wC, n, base);
+                }
             }
+        };
+        if constexpr (LAY == TDC_LAY_NCHW_RUNS) {
+            TdcStage1R<MB1, (MB1 >= 4 ? 1 : 2)> s1(sg, lane, wave, nw);
+            stage1(s1);
+        } else {
+            TdcStage1<MB1, PB, (MB1 * PB >= 8 ? 2 : 4), NHWC> s1(sg, lane, wave, nw);   // k-groups per operand buffer
+            stage1(s1);
         }
     }
     TDC_PROBE(3);
@@ -278,6 +291,11 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.div_TW = tdc_make_div((unsigned)g.TW);
     a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
     a.div_npg2 = tdc_make_div((unsigned)((g.PBk + t.pb[0] - 1) / t.pb[0]));
+    a.QH = g.QH;
+    a.RPR = tdc_runs_per_row(d.W, d.Wo, g.TW, d.K, d.stride, d.pad);
+    a.n_sb = (g.QH * a.RPR + 15) / 16;
+    a.div_RPR = tdc_make_div((unsigned)a.RPR); a.div_nsb = tdc_make_div((unsigned)a.n_sb);
+    const int lay = d.nhwc ? TDC_LAY_NHWC : d.s1_runs ? TDC_LAY_NCHW_RUNS : TDC_LAY_NCHW;
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_LAUNCH(A_, B_, C_, D_, W_, L_)                                                             \
     {                                                                                                  \
@@ -292,9 +310,13 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
 #define TDC_X(A_, B_, C_, D_)                                                                          \
     if (t.mb[0] == A_ && t.mb[1] == B_ && t.mb[2] == C_ && t.pb[0] == D_) {                            \
         if (g.weights_in_lds) {                                                                        \
-            if (d.nhwc) TDC_LAUNCH(A_, B_, C_, D_, true, true) else TDC_LAUNCH(A_, B_, C_, D_, true, false)    \
+            if (lay == TDC_LAY_NHWC) TDC_LAUNCH(A_, B_, C_, D_, true, TDC_LAY_NHWC)                    \
+            else if (lay == TDC_LAY_NCHW_RUNS) TDC_LAUNCH(A_, B_, C_, D_, true, TDC_LAY_NCHW_RUNS)     \
+            else TDC_LAUNCH(A_, B_, C_, D_, true, TDC_LAY_NCHW)                                        \
         } else {                                                                                       \
-            if (d.nhwc) TDC_LAUNCH(A_, B_, C_, D_, false, true) else TDC_LAUNCH(A_, B_, C_, D_, false, false)  \
+            if (lay == TDC_LAY_NHWC) TDC_LAUNCH(A_, B_, C_, D_, false, TDC_LAY_NHWC)                   \
+            else if (lay == TDC_LAY_NCHW_RUNS) TDC_LAUNCH(A_, B_, C_, D_, false, TDC_LAY_NCHW_RUNS)    \
+            else TDC_LAUNCH(A_, B_, C_, D_, false, TDC_LAY_NCHW)                                       \
         }                                                                                              \
     }
     TDC_FUSED_MENU(TDC_X)

@@ -39,6 +39,8 @@ struct TdcDims {
     int NB1, NB2, NB3;   // 16-blocks of the padded R1, R2, N
     int KG1;             // ceil(C/16)
     int nhwc;            // activations x, y (and an epilogue's residual) are [B][H][W][channels]; C % 4 == N % 4 == 0
+    int s1_runs;         // NCHW one-launch kernels read x in 16-byte runs of four pixels (W % 4 == 0, x 16-byte
+                         // aligned); U_in is then re-laid-out with k order 4*j + lane/16 instead of 4*(lane/16) + j
 };
 
 // Raises the dynamic-LDS limit of kernel `fn` to at least `bytes` on the current device.  The HIP

@@ -27,6 +27,7 @@ __global__ void pack_uin_kernel(TdcDims d, const float *__restrict__ U_in, float
     if (e >= total) return;
     int mb, kg, k16, m;
     unpack_index(e, d.KG1, mb, kg, k16, m);
+    if (d.s1_runs) k16 = 4 * (k16 & 3) + (k16 >> 2);      // component j of lane group g holds channel 4*j + g
     const int c = 16 * kg + k16;
     out[e] = (c < d.C && m < d.R1) ? U_in[(size_t)c * d.R1 + m] : 0.f;
 }

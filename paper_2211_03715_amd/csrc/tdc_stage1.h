@@ -24,6 +24,9 @@ struct TdcS1Geom {
     int h0, w0;             // image coordinates of the tile's first pixel (may be negative)
     int pitch1;             // z1 tile row pitch in LDS, in cells
     TdcDiv div_QW, div_npg; // npg = ceil(QB / PB)
+    // run-major form (TdcStage1R): tile rows, aligned 4-pixel runs per row, 64-pixel blocks of runs
+    int QH, RPR, n_sb;
+    TdcDiv div_RPR, div_nsb;
 };
 
 template <int MB1, int PB, int U, bool NHWC>
@@ -108,6 +111,8 @@ struct TdcStage1 {
 
     // Issue the loads of the wavefront's first buffer; call well ahead of run().
     __device__ __forceinline__ void prefetch() { fetch0(); }
+    // every cell of the tile is produced by a unit (pixels outside the image read x = 0)
+    __device__ __forceinline__ void zero_outside(tdc_f4 *) const {}
 
     // All units of this wavefront; the finished z1 blocks go to their LDS cells.
     __device__ __forceinline__ void run(tdc_f4 *__restrict__ z1s)
@@ -152,6 +157,153 @@ struct TdcStage1 {
     }
 };
 
+// Stage 1 for NCHW activations with 16-byte loads ("run-major").  In NCHW a lane's four B-operand
+// values of the form above are four channels of one pixel, 4 bytes each at channel stride: many
+// small requests, partly used cache lines.  Here a lane owns a RUN of four consecutive pixels of a
+// tile row instead, aligned to 4 in image coordinates (the image width is a multiple of 4, so a run
+// is inside the image or outside it as a whole), and loads it with one 16-byte load per channel:
+//   lane (g, l16), k-group kg, q = 0..3:  b[q] = x[channel 16*kg + 4*q + g][run l16, pixels 0..3]
+// The four MFMAs of (q, t) contract over the four channels 4*q + g and accumulate pixel t of the run
+// into accumulator t, so a unit is 16 runs = 64 pixels and four accumulators per channel block; the
+// U_in fragments come re-laid-out with the matching k order (lane (g, l16), component q = channel
+// 16*kg + 4*q + g).  The accumulator of (channel block, t) is, per lane, the z1 cell of pixel t of the
+// lane's run; cells of tile columns that lie outside the image are never produced by a run and are
+// zeroed by zero_outside() instead.
+template <int MB1, int U>
+struct TdcStage1R {
+    const TdcS1Geom &s;
+    tdc_rsrc xrs, urs;
+    int lane, g, l16, wave, nw;
+    int n_units, wa;        // wa: image column of the first run of a row (a multiple of 4, >= 0)
+    int fu, fkg, fmg, slots;
+    unsigned xoff;          // byte offset of this lane's run within a channel plane, or TDC_OOB
+    tdc_f4 a0[U][MB1], a1[U][MB1], b0[U][4], b1[U][4];
+
+    __device__ __forceinline__ TdcStage1R(const TdcS1Geom &geom, int lane_, int wave_, int nw_) : s(geom)
+    {
+        lane = lane_; g = lane_ >> 4; l16 = lane_ & 15; wave = wave_; nw = nw_;
+        const int HW = s.H * s.W;
+        xrs = tdc_make_rsrc(s.x_img, (unsigned)s.C * HW * 4u);
+        urs = tdc_make_rsrc(s.uin_p, (unsigned)s.NB1 * s.KG1 * 1024u);
+        n_units = s.n_sb * (s.NB1 / MB1);
+        slots = (s.KG1 + U - 1) / U * U;
+        wa = s.w0 > 0 ? (s.w0 & ~3) : 0;
+        fu = wave;
+        place();
+    }
+
+    // Tile cells whose image column is outside [0, W): all rows, all channel planes.  Disjoint from
+    // what the runs write, so no barrier is needed between the two.
+    __device__ __forceinline__ void zero_outside(tdc_f4 *__restrict__ z1s) const
+    {
+        const int left = s.w0 < 0 ? -s.w0 : 0;                               // columns qw < left
+        const int right = max(s.w0 + s.QW - s.W, 0);                          // columns qw >= QW - right
+        const int per_row = left + right, planes = 4 * s.NB1;
+        const int total = per_row * s.QH * planes;
+        for (int e = threadIdx.x; e < total; e += blockDim.x) {
+            const int c = e % per_row, r = (e / per_row) % s.QH, pl = e / (per_row * s.QH);
+            const int qw = c < left ? c : s.QW - right + (c - left);
+            z1s[pl * s.pitch1 + r * s.QW + qw] = tdc_f4_zero();
+        }
+    }
+
+    __device__ __forceinline__ void place()
+    {
+        fkg = 0;
+        const bool live = fu < n_units;
+        fmg = live ? tdc_div(fu, s.div_nsb) : 0;
+        const int sb = fu - fmg * s.n_sb;
+        const int rho = 16 * sb + l16;
+        const int qh = tdc_div(rho, s.div_RPR), rc = rho - qh * s.RPR;
+        const int h = s.h0 + qh, col = wa + 4 * rc;
+        const bool ok = live && qh < s.QH && h >= 0 && h < s.H && col < s.W;
+        xoff = ok ? (unsigned)(h * s.W + col) * 4u : TDC_OOB;
+    }
+
+    __device__ __forceinline__ void fetch_group(tdc_f4 (&av)[MB1], tdc_f4 (&bv)[4])
+    {
+        const unsigned dead = (fkg < s.KG1 && fu < n_units) ? 0u : TDC_OOB;
+#pragma unroll
+        for (int mb = 0; mb < MB1; ++mb)
+            av[mb] = tdc_buf_load4(urs, ((unsigned)((fmg * MB1 + mb) * s.KG1 + fkg) * 1024u + lane * 16u) | dead);
+        // channels past C lie beyond the descriptor and read as 0 by themselves
+        const unsigned HW4 = (unsigned)(s.H * s.W) * 4u;
+        const unsigned o = ((unsigned)(16 * fkg + g) * HW4 + xoff) | dead | (xoff & TDC_OOB);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bv[q] = tdc_buf_load4(xrs, o + (unsigned)(4 * q) * HW4);
+        if (++fkg == slots) {
+            fu += nw;
+            place();
+        }
+    }
+
+    __device__ __forceinline__ void fetch0()
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) fetch_group(a0[u], b0[u]);
+    }
+    __device__ __forceinline__ void fetch1()
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) fetch_group(a1[u], b1[u]);
+    }
+    __device__ __forceinline__ void prefetch() { fetch0(); }
+
+    __device__ __forceinline__ void run(tdc_f4 *__restrict__ z1s)
+    {
+        const int spu = slots / U;
+        const int mine = wave < n_units ? (n_units - wave + nw - 1) / nw : 0;
+        const int total = mine * spu;
+        int cu = wave, cb = 0;
+        tdc_f4 acc[MB1][4];
+        const auto clear = [&]() {
+#pragma unroll
+            for (int mb = 0; mb < MB1; ++mb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[mb][t] = tdc_f4_zero();
+        };
+        const auto mma = [&](const tdc_f4 (&av)[MB1], const tdc_f4 (&bv)[4]) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int mb = 0; mb < MB1; ++mb) acc[mb][t] = tdc_mfma(av[mb][q], bv[q][t], acc[mb][t]);
+        };
+        const auto finish_buffer = [&]() {
+            if (++cb < spu) return;
+            const int mg = tdc_div(cu, s.div_nsb), sb = cu - mg * s.n_sb;
+            const int rho = 16 * sb + l16;
+            const int qh = tdc_div(rho, s.div_RPR), rc = rho - qh * s.RPR;
+            const int qw0 = wa + 4 * rc - s.w0;            // tile column of the run's first pixel (may be < 0)
+            if (qh < s.QH) {
+#pragma unroll
+                for (int mb = 0; mb < MB1; ++mb)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (qw0 + t >= 0 && qw0 + t < s.QW)
+                            z1s[((mg * MB1 + mb) * 4 + g) * s.pitch1 + qh * s.QW + qw0 + t] = acc[mb][t];
+            }
+            cu += nw;
+            cb = 0;
+            clear();
+        };
+        clear();
+        for (int i = 0; i < total; i += 2) {
+            fetch1();
+#pragma unroll
+            for (int u = 0; u < U; ++u) mma(a0[u], b0[u]);
+            finish_buffer();
+            fetch0();
+            if (i + 1 < total) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) mma(a1[u], b1[u]);
+                finish_buffer();
+            }
+        }
+    }
+};
+
 // Copy of the packed core and U_out arrays (adjacent in LDS) into LDS, CH 16-byte pieces per thread
 // and round.  load() and store() are separate so that the first round's loads can be issued before
 // stage 1 and stored after it: they then travel while stage 1 computes.
@@ -178,5 +330,22 @@ struct TdcWeightCopy {
         }
     }
 };
+
+// Layouts a one-launch kernel is compiled for: how x is read and y is written.
+enum { TDC_LAY_NCHW = 0, TDC_LAY_NHWC = 1, TDC_LAY_NCHW_RUNS = 2 };   // RUNS: NCHW with the run-major stage 1
+
+// Host side of the run-major form: runs per tile row (the most any tile column needs) for output tiles TW wide.
+inline int tdc_runs_per_row(int W, int Wo, int TW, int K, int stride, int pad)
+{
+    const int QW = (TW - 1) * stride + K;
+    int rpr = 1;
+    for (int j0 = 0; j0 < Wo; j0 += TW) {
+        const int w0 = j0 * stride - pad, wa = w0 > 0 ? (w0 & ~3) : 0;
+        const int end = w0 + QW < W ? w0 + QW : W;
+        const int runs = (end - wa + 3) / 4;
+        rpr = runs > rpr ? runs : rpr;
+    }
+    return rpr;
+}
 
 #endif

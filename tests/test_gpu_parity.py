@@ -221,6 +221,44 @@ def test_linearity_and_batch_independence_on_gpu(orc):
         assert np.array_equal(y2, 2.0 * yb), "scaling x by 2 must scale y by exactly 2"
 
 
+RUN_MAJOR_LAYERS = [
+    Layer(40, 20, 24, 12, 16, 17, 33),            # ragged channels and ranks, image 12 x 16
+    Layer(24, 33, 18, 24, 40, 8, 40, 3, 2, 1),    # stride 2
+    Layer(64, 16, 16, 12, 12, 16, 16, 3, 1, 0),   # no padding: no column outside the image
+    Layer(40, 8, 8, 12, 16, 5, 3, 5, 1, 2),       # 5x5 core, two columns of padding each side
+    Layer(70, 12, 10, 8, 8, 4, 6, 1, 1, 0),       # 1x1 core
+    Layer(1100, 4, 4, 2, 4, 2, 2, 3, 1, 1),       # an image of one run per row
+]
+RUN_MAJOR_TUNINGS = [
+    dict(variant=B.VARIANT_FUSED, tile_h=3, tile_w=5, waves=(4, 4, 4), mb=(1, 1, 1), pb=(1, 1, 1)),     # tiles start off the 4-grid
+    dict(variant=B.VARIANT_FUSED, tile_h=2, tile_w=16, waves=(8, 8, 8), mb=(1, 1, 1), pb=(2, 2, 2)),
+    dict(variant=B.VARIANT_CHAIN, tile_h=4, tile_w=7, waves=(2, 2, 2), mb=(1, 1, 1), pb=(1, 1, 1)),
+    dict(variant=B.VARIANT_CHAIN, tile_h=12, tile_w=4, waves=(8, 8, 8), mb=(1, 1, 1), pb=(2, 2, 2)),
+    dict(variant=B.VARIANT_FUSED),
+    dict(variant=B.VARIANT_CHAIN),
+]
+
+
+@pytest.mark.parametrize("tuning", RUN_MAJOR_TUNINGS, ids=lambda t: "%s_%dx%d" % (
+    "fused" if t["variant"] == B.VARIANT_FUSED else "chain", t.get("tile_h", 0), t.get("tile_w", 0)))
+@pytest.mark.parametrize("layer", RUN_MAJOR_LAYERS, ids=lambda l: l.name())
+def test_run_major_stage1_shapes(orc, layer, tuning):
+    """In the throughput regime (batch x output pixels fill the chip) the fused and chain kernels read NCHW
+    rows whose width is a multiple of 4 in 16-byte runs: ragged shapes and tiles that start off the 4-pixel
+    grid, at batch sizes that select that path."""
+    assert layer.batch * layer.Ho * layer.Wo >= 4096 and layer.W % 4 == 0
+    _announce("run-major", layer.name(), tuning)
+    inputs = make_inputs(layer, 909)
+    want = _oracle(orc, layer, inputs)
+    try:
+        got, desc = run_gpu(layer, inputs, B.make_tuning(**tuning))
+    except B.TdcError as e:
+        if e.status == B.TDC_ERR_BAD_TUNING and "tile_h" in tuning:
+            pytest.skip("tile does not fit this layer")          # the library said so, nothing ran
+        raise
+    assert_parity(got, want, "%s [%s]" % (layer.name(), desc))
+
+
 def test_two_plans_on_two_streams(orc):
     """Calls only enqueue on the stream they are given: two layers with plans of their own run on two
     non-default streams at once, repeatedly, and each matches the oracle (no hidden use of the default stream,
