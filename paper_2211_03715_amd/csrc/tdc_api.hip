@@ -270,11 +270,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     p->device = device;
     if (forced) p->tuning = *forced;
     rc = tdc_select(p->dims, dev, &p->tuning, &p->model_us);
-    // The throughput kernels read NCHW activations in 16-byte runs where the rows allow it.  (Not the
-    // latency regime: a run-major unit is 64 pixels, and the small tiles chosen there would mostly pad it --
-    // measured 0.4 to 2.6 us slower per batch-1 layer.)
-    if (rc == TDC_OK && !p->dims.nhwc && p->dims.W % 4 == 0 &&
-        (long)p->dims.B * p->dims.Ho * p->dims.Wo >= 16L * dev.cus &&
+    if (rc == TDC_OK && tdc_runs_apply(p->dims, dev.cus) &&
         (p->tuning.variant == TDC_VARIANT_FUSED || p->tuning.variant == TDC_VARIANT_CHAIN))
         p->dims.s1_runs = 1;
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)

@@ -111,6 +111,28 @@ TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, i
 hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s, const float *x,
                          const float *uin_p, const float *wm_p, float *y, const TdcEpi &epi, bool prepare_only = false);
 
+// Run-major stage 1 of the NCHW one-launch kernels (a lane loads four consecutive pixels of a row, aligned
+// to 4 in image coordinates, with one 16-byte load).  FUSED and CHAIN plans use it in the throughput
+// regime where the rows allow it (not in the latency regime: a run-major unit is 64 pixels, and the small
+// tiles chosen there would mostly pad it -- measured 0.4 to 2.6 us slower per batch-1 layer).
+inline bool tdc_runs_apply(const TdcDims &d, int cus)
+{
+    return !d.nhwc && d.W % 4 == 0 && (long)d.B * d.Ho * d.Wo >= 16L * cus;
+}
+// Runs per tile row (the most any tile column needs) for output tiles TW wide.
+inline int tdc_runs_per_row(int W, int Wo, int TW, int K, int stride, int pad)
+{
+    const int QW = (TW - 1) * stride + K;
+    int rpr = 1;
+    for (int j0 = 0; j0 < Wo; j0 += TW) {
+        const int w0 = j0 * stride - pad, wa = w0 > 0 ? (w0 & ~3) : 0;
+        const int end = w0 + QW < W ? w0 + QW : W;
+        const int runs = (end - wa + 3) / 4;
+        rpr = runs > rpr ? runs : rpr;
+    }
+    return rpr;
+}
+
 // ---- selector (tdc_select.cpp): fills every zero field of `t`
 struct TdcDeviceInfo {
     int cus;             // compute units

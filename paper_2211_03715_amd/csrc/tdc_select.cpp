@@ -28,31 +28,46 @@ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 constexpr int kWavesPerCu = 32;   // 8 per SIMD
 
+// Workgroups of `nw` wavefronts one compute unit holds at a time: as many as LDS allows, and as the
+// vector registers allow -- `wps` wavefronts per SIMD (512 registers per lane and SIMD, divided by what
+// the kernel instance uses), four SIMDs.  The throughput kernels use 140-250 registers, so a compute unit
+// holds 8 to 12 of their wavefronts, not the 32 the hardware has slots for; tunings timed with 8-wavefront
+// workgroups show it: a second workgroup per compute unit waits for the first to finish.
+inline int resident_wgs(const TdcDeviceInfo &dev, size_t lds_bytes, int nw, int wps)
+{
+    return std::max(1, std::min({(int)(dev.lds_per_wg / std::max<size_t>(lds_bytes, 1)), 4 * wps / nw, 8}));
+}
+
 struct FusedCoef {
     double launch = 3.5583;
     double s1_unit = 1.2599, s1_kg = 0.0435, s1_mfma = 0.0751;
     double s2_kg_lds = 0.0186, s2_kg_glb = 0.0356;
     double s3_unit = 0.3151, s3_kg_lds = 0.0806, s3_kg_glb = 0.0875, s3_mfma = 0.2474;
     double w_kb = 0.0340;         // per KiB of weights copied into LDS, per co-resident workgroup
-    // throughput regime only: stage-2 MFMAs, MB moved per CU by layout, NCHW row segments per CU (thousands)
+    // throughput regime only: stage-2 MFMAs, MB moved per CU by layout, NCHW row segments per CU (thousands),
+    // and the run-major form of stage 1 (64-pixel units, one 16-byte load per channel and run)
     double s2_mfma = 0.0;
-    double x_mb[2] = {0.0, 0.0}, y_mb[2] = {0.0, 0.0};   // [NCHW, NHWC]
+    double s1r_unit = 0.0, s1r_kg = 0.0, s1r_mfma = 0.0;
+    double x_mb[3] = {0.0, 0.0, 0.0}, y_mb[2] = {0.0, 0.0};   // x: [NCHW, NHWC, NCHW in runs], y: [NCHW, NHWC]
     double x_rows = 0.0, y_rows = 0.0;
+    bool by_registers = false;    // residency from the register footprint of the unit (throughput fit) or from wavefront slots
 };
 
-// The same form refitted on ~7400 tunings of the batch-8 and batch-32 layers in both activation
-// layouts (median relative error 8%): there the bytes a CU moves and, in NCHW, the number of row
-// segments they come in decide between tilings.
+// The same form refitted on ~17500 tunings of eight batch-8 to batch-64 layers (median relative error
+// 9%), the NCHW ones timed with both forms of stage 1: there the bytes a CU moves and, in NCHW, the
+// number of row segments they come in decide between tilings.
 FusedCoef fused_throughput_coef()
 {
     FusedCoef c;
-    c.launch = 3.2282;
-    c.s1_unit = 0.0; c.s1_kg = 0.0580; c.s1_mfma = 0.0432;
-    c.s2_kg_lds = 0.0308; c.s2_kg_glb = 0.0951; c.s2_mfma = 0.0129;
-    c.s3_unit = 0.2993; c.s3_kg_lds = 0.0826; c.s3_kg_glb = 0.0; c.s3_mfma = 0.1262;
-    c.w_kb = 0.0252;
-    c.x_mb[0] = 47.4064; c.x_mb[1] = 24.8735; c.y_mb[0] = 35.1973; c.y_mb[1] = 42.2936;
-    c.x_rows = 0.8812; c.y_rows = 2.3714;
+    c.launch = 4.1622;
+    c.s1_unit = 0.4289; c.s1_kg = 0.0492; c.s1_mfma = 0.0288;
+    c.s1r_unit = 0.2708; c.s1r_kg = 0.3399; c.s1r_mfma = 0.0028;
+    c.s2_kg_lds = 0.0402; c.s2_kg_glb = 0.0992; c.s2_mfma = 0.0229;
+    c.s3_unit = 0.2002; c.s3_kg_lds = 0.0733; c.s3_kg_glb = 0.0; c.s3_mfma = 0.1458;
+    c.w_kb = 0.0222;
+    c.x_mb[0] = 12.4128; c.x_mb[1] = 6.1156; c.x_mb[2] = 6.5838; c.y_mb[0] = 60.5491; c.y_mb[1] = 29.7202;
+    c.x_rows = 0.4209; c.y_rows = 2.5605;
+    c.by_registers = true;
     return c;
 }
 
@@ -75,27 +90,42 @@ struct StageCoef {
 
 const int kMb[3] = {1, 2, 4};
 
-double fused_us(const FusedCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw,
+// Stage 1 of a one-launch kernel: rounds per wavefront, MFMA quads per k-group and unit, MB of x pulled
+// per workgroup -- in the run-major form (`runs`) a unit is 16 runs of 4 pixels for mb1 channel blocks.
+struct Stage1Work {
+    int rounds, quads;
+    double x_mb;
+};
+Stage1Work stage1_work(const TdcDims &d, const TdcFusedGeom &g, bool runs, int nw, int mb1, int pb)
+{
+    if (!runs) return {cdiv(cdiv(g.QB, pb) * (d.NB1 / mb1), nw), mb1 * pb, g.QB * 16.0 * d.C * 4e-6};
+    const int rpr = tdc_runs_per_row(d.W, d.Wo, g.TW, d.K, d.stride, d.pad);
+    return {cdiv(cdiv(g.QH * rpr, 16) * (d.NB1 / mb1), nw), 4 * mb1, g.QH * rpr * 16.0 * d.C * 1e-6};
+}
+
+double fused_us(const FusedCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, bool runs, int nw,
                 int mb1, int mb2, int mb3, int pb)
 {
     const int KG2 = d.K * d.K * d.NB1, KG3 = d.NB2;
-    const int r1 = cdiv(cdiv(g.QB, pb) * (d.NB1 / mb1), nw);
+    const Stage1Work s1 = stage1_work(d, g, runs, nw, mb1, pb);
     const int r2 = cdiv(cdiv(g.PBk, pb) * (d.NB2 / mb2), nw);
     const int r3 = cdiv(cdiv(g.PBk, pb) * (d.NB3 / mb3), nw);
     const long wgs = (long)g.tiles_x * g.tiles_y * d.B;
-    const int resident = std::max(1, std::min({(int)(dev.lds_per_wg / std::max<size_t>(g.lds_bytes, 1)), kWavesPerCu / nw, 8}));
+    // register tiles of 1, 2, 4+ blocks leave room for 4, 3, 2 wavefronts per SIMD (kernel resource usage of the instances)
+    const int unit = mb1 * pb, wps = !c.by_registers ? kWavesPerCu / 4 : unit == 1 ? 4 : unit == 2 ? 3 : 2;
+    const int resident = resident_wgs(dev, g.lds_bytes, nw, wps);
     const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
     const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
     const double share = std::max(1.0, per_cu * nw / 4.0);
     const bool wl = g.weights_in_lds;
     const double w_kb = wl ? (double)(d.NB2 * KG2 + d.NB3 * KG3) : 0.0;
-    double t = r1 * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * mb1 * pb * share));
+    double t = runs ? s1.rounds * (c.s1r_unit + d.KG1 * (c.s1r_kg + c.s1r_mfma * s1.quads * share))
+                    : s1.rounds * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * s1.quads * share));
     t += r2 * KG2 * ((wl ? c.s2_kg_lds : c.s2_kg_glb) + c.s2_mfma * mb2 * pb * share);
     t += r3 * (c.s3_unit + KG3 * ((wl ? c.s3_kg_lds : c.s3_kg_glb) + c.s3_mfma * mb3 * pb * share));
     t += c.w_kb * w_kb * per_cu;
-    const int lay = d.nhwc ? 1 : 0;
-    t += per_cu * (c.x_mb[lay] * g.QB * 16.0 * d.C * 4e-6 + c.y_mb[lay] * g.PBk * 16.0 * d.N * 4e-6);
-    if (!d.nhwc) t += per_cu * (c.x_rows * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
+    t += per_cu * (c.x_mb[d.nhwc ? 1 : runs ? 2 : 0] * s1.x_mb + c.y_mb[d.nhwc ? 1 : 0] * g.PBk * 16.0 * d.N * 4e-6);
+    if (!d.nhwc) t += per_cu * ((runs ? 0.0 : c.x_rows) * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
     return c.launch + rounds * t;
 }
 
@@ -108,6 +138,7 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 {
     const bool throughput = (long)d.B * d.Ho * d.Wo >= 16L * dev.cus;
     const FusedCoef c = throughput ? fused_throughput_coef() : FusedCoef();
+    const bool runs = tdc_runs_apply(d, dev.cus);
     FusedChoice best;
     const int th_lo = forced.tile_h ? forced.tile_h : 1, th_hi = forced.tile_h ? forced.tile_h : std::min(d.Ho, 16);
     const int tw_lo = forced.tile_w ? forced.tile_w : 1, tw_hi = forced.tile_w ? forced.tile_w : std::min(d.Wo, 32);
@@ -129,7 +160,7 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
                                 if (forced.pb[0] && pb != forced.pb[0]) continue;
                                 if (d.NB1 % mb1 || d.NB2 % mb2 || d.NB3 % mb3) continue;   // whole register tiles only
                                 if (!tdc_fused_unit_supported(mb1, mb2, mb3, pb)) continue;
-                                const double us = fused_us(c, d, dev, g, nw, mb1, mb2, mb3, pb);
+                                const double us = fused_us(c, d, dev, g, runs, nw, mb1, mb2, mb3, pb);
                                 if (us < best.us) {
                                     best.us = us;
                                     best.th = th; best.tw = tw; best.nw = nw;
@@ -146,47 +177,52 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 // variant serves the throughput regime, so the estimate also charges the bytes a CU pulls and
 // pushes (input tile incl. halo, output tile) and the scalar-store path taken when tile or image
 // width is not a multiple of 4, and, in NCHW, the number of row segments a CU reads and writes
-// (tiles that span whole image rows move longer runs).  Fitted to ~5200 tunings of the batch-8/32
-// layers in both activation layouts (median relative error 8%).
+// (tiles that span whole image rows move longer runs).  Fitted to ~12600 tunings of eight batch-8 to
+// batch-64 layers, the NCHW ones timed with both forms of stage 1 (median relative error 9%).
 struct ChainCoef {
-    double launch = 1.9182;
-    double s1_unit = 0.0, s1_kg = 0.0967, s1_mfma = 0.1085;
-    double kg2_glb = 0.1693, blk2 = 0.0;
-    double nb3_lds = 0.2773, blk3 = 0.0457;
-    double w_kb = 0.0369;
-    double x_mb[2] = {6.3970, 11.0397};      // per MB per CU, [NCHW, NHWC]
-    double y_mb = 37.4415;
-    double x_rows = 0.5420, y_rows = 2.9268; // NCHW: per 1000 row segments (tile rows x channels) per CU, in and out
-    double novec = 0.1746;                   // per output-channel block and pixel block stored with 4-byte stores
+    double launch = 3.6918;
+    double s1_unit = 0.5859, s1_kg = 0.0211, s1_mfma = 0.0906;
+    double s1r_unit = 0.2783, s1r_kg = 0.3798, s1r_mfma = 0.0096;   // run-major stage 1
+    double kg2_lds = 0.0298, kg2_glb = 0.2335, blk2 = 0.0141;
+    double nb3_lds = 0.2690, blk3 = 0.0402;
+    double w_kb = 0.0235;
+    double x_mb[3] = {6.4658, 0.0, 15.9944}; // per MB per CU, [NCHW, NHWC, NCHW in runs]
+    double y_mb = 32.4026;
+    double x_rows = 0.2683, y_rows = 2.9056; // NCHW: per 1000 row segments (tile rows x channels) per CU, in (4-byte loads only) and out
+    double novec = 0.1707;                   // per output-channel block and pixel block stored with 4-byte stores
 };
 
-double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw, int mb1,
-                int pb)
+double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, bool runs, int nw,
+                int mb1, int pb, int *cu_waves)
 {
     const int KG2 = d.K * d.K * d.NB1;
-    const int r1 = cdiv(cdiv(g.QB, pb) * (d.NB1 / mb1), nw);
+    const Stage1Work s1 = stage1_work(d, g, runs, nw, mb1, pb);
     const int r23 = cdiv(cdiv(g.PBk, pb), nw);
     const long wgs = (long)g.tiles_x * g.tiles_y * d.B;
-    const int resident = std::max(1, std::min({(int)(dev.lds_per_wg / std::max<size_t>(g.lds_bytes, 1)), kWavesPerCu / nw, 8}));
+    const int resident = resident_wgs(dev, g.lds_bytes, nw, 2);   // 170-250 registers: two wavefronts per SIMD
     const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
+    *cu_waves = per_cu * nw;
     const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
     const double share = std::max(1.0, per_cu * nw / 4.0);
     const bool wl = g.weights_in_lds;
     const double w_kb = wl ? (double)(d.NB2 * KG2 + d.NB3 * d.NB2) : 0.0;
     const bool vec = d.nhwc || (g.TW % 4 == 0 && d.Wo % 4 == 0);
-    double t = r1 * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * mb1 * pb * share));
-    t += r23 * (KG2 * ((wl ? 0.0 : c.kg2_glb) + c.blk2 * d.NB2 * pb * share) +
+    double t = runs ? s1.rounds * (c.s1r_unit + d.KG1 * (c.s1r_kg + c.s1r_mfma * s1.quads * share))
+                    : s1.rounds * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * s1.quads * share));
+    t += r23 * (KG2 * ((wl ? c.kg2_lds : c.kg2_glb) + c.blk2 * d.NB2 * pb * share) +
                 d.NB3 * ((wl ? c.nb3_lds : 0.0) + c.blk3 * d.NB2 * pb * share + (vec ? 0.0 : c.novec * pb)));
     t += c.w_kb * w_kb * per_cu;
-    t += per_cu * (c.x_mb[d.nhwc ? 1 : 0] * g.QB * 16.0 * d.C * 4e-6 + c.y_mb * g.PBk * 16.0 * d.N * 4e-6);
-    if (!d.nhwc) t += per_cu * (c.x_rows * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
+    t += per_cu * (c.x_mb[d.nhwc ? 1 : runs ? 2 : 0] * s1.x_mb + c.y_mb * g.PBk * 16.0 * d.N * 4e-6);
+    if (!d.nhwc) t += per_cu * ((runs ? 0.0 : c.x_rows) * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
     return c.launch + rounds * t;
 }
 
 FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &forced)
 {
     const ChainCoef c;
+    const bool runs = tdc_runs_apply(d, dev.cus);
     FusedChoice best;
+    int best_cu_waves = 0;
     const int th_lo = forced.tile_h ? forced.tile_h : 1, th_hi = forced.tile_h ? forced.tile_h : std::min(d.Ho, 16);
     const int tw_lo = forced.tile_w ? forced.tile_w : 1, tw_hi = forced.tile_w ? forced.tile_w : std::min(d.Wo, 32);
     for (int th = th_lo; th <= th_hi; ++th)
@@ -196,15 +232,22 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
             if (!forced.tile_w && !d.nhwc && d.Wo % 4 == 0 && tw % 4) continue;
             const TdcFusedGeom g = tdc_chain_geometry(d, th, tw, dev.lds_per_wg);
             if ((long)g.lds_bytes > dev.lds_per_wg) continue;
-            for (int nw : {8, 4, 2, 1}) {   // at equal estimate the first wins: more wavefronts hide more latency
+            // The estimate is the same for one 8-wavefront workgroup per CU run twice and for two 4-wavefront ones run
+            // together, and for 8 wavefronts with 16-pixel units against 4 with 32-pixel units.  Measured, more
+            // wavefronts on the CU win, and at equal numbers the smaller workgroups (they fall out of step and
+            // overlap their memory and arithmetic phases): ties go to more wavefronts, then to workgroups of 4.
+            for (int nw : {4, 8, 2, 1}) {
                 if (forced.waves[0] && nw != forced.waves[0]) continue;
                 for (int pb : {1, 2})
                     for (int mb1 : kMb) {
                         if (forced.mb[0] && mb1 != forced.mb[0]) continue;
                         if (forced.pb[0] && pb != forced.pb[0]) continue;
                         if (d.NB1 % mb1 || !tdc_chain_supported(d.NB2, mb1, pb)) continue;
-                        const double us = chain_us(c, d, dev, g, nw, mb1, pb);
-                        if (us < best.us) {
+                        int cu_waves = 0;
+                        const double us = chain_us(c, d, dev, g, runs, nw, mb1, pb, &cu_waves);
+                        const bool tie = std::fabs(us - best.us) <= 1e-9 * us;
+                        if ((!tie && us < best.us) || (tie && cu_waves > best_cu_waves)) {
+                            best_cu_waves = cu_waves;
                             best.us = us;
                             best.th = th; best.tw = tw; best.nw = nw;
                             best.mb1 = mb1; best.mb2 = 1; best.mb3 = 1; best.pb = pb;

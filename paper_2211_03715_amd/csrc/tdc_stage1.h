@@ -200,7 +200,7 @@ struct TdcStage1R {
         const int right = max(s.w0 + s.QW - s.W, 0);                          // columns qw >= QW - right
         const int per_row = left + right, planes = 4 * s.NB1;
         const int total = per_row * s.QH * planes;
-        for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        for (int e = 64 * wave + lane; e < total; e += 64 * nw) {
             const int c = e % per_row, r = (e / per_row) % s.QH, pl = e / (per_row * s.QH);
             const int qw = c < left ? c : s.QW - right + (c - left);
             z1s[pl * s.pitch1 + r * s.QW + qw] = tdc_f4_zero();
@@ -333,19 +333,5 @@ struct TdcWeightCopy {
 
 // Layouts a one-launch kernel is compiled for: how x is read and y is written.
 enum { TDC_LAY_NCHW = 0, TDC_LAY_NHWC = 1, TDC_LAY_NCHW_RUNS = 2 };   // RUNS: NCHW with the run-major stage 1
-
-// Host side of the run-major form: runs per tile row (the most any tile column needs) for output tiles TW wide.
-inline int tdc_runs_per_row(int W, int Wo, int TW, int K, int stride, int pad)
-{
-    const int QW = (TW - 1) * stride + K;
-    int rpr = 1;
-    for (int j0 = 0; j0 < Wo; j0 += TW) {
-        const int w0 = j0 * stride - pad, wa = w0 > 0 ? (w0 & ~3) : 0;
-        const int end = w0 + QW < W ? w0 + QW : W;
-        const int runs = (end - wa + 3) / 4;
-        rpr = runs > rpr ? runs : rpr;
-    }
-    return rpr;
-}
 
 #endif
