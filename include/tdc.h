@@ -64,7 +64,9 @@ typedef enum tdc_status {
  * y[batch][N][Ho][Wo]; 1 = NHWC, x[batch][H][W][C] and y[batch][Ho][Wo][N] (the pixel-major
  * order the paper writes its tensors in, section 3); an epilogue's residual is laid out like y.
  * NHWC moves channels four at a time: C and N must be multiples of 4 and x, y and the residual
- * 16-byte aligned, else TDC_ERR_UNSUPPORTED.  Weights have one layout, whatever the activations'. */
+ * 16-byte aligned, else TDC_ERR_UNSUPPORTED.  NCHW plans for large batches read rows whose width is
+ * a multiple of 4 sixteen bytes at a time and return TDC_ERR_UNSUPPORTED for an x that is not 16-byte
+ * aligned.  Weights have one layout, whatever the activations'. */
 typedef struct tdc_shape {
     int32_t batch, C, N, H, W;
     int32_t R1, R2, K;
