@@ -259,6 +259,35 @@ def test_run_major_stage1_shapes(orc, layer, tuning):
     assert_parity(got, want, "%s [%s]" % (layer.name(), desc))
 
 
+def test_run_major_refuses_misaligned_x(orc):
+    """A plan that reads NCHW rows sixteen bytes at a time refuses an x that is not 16-byte aligned (status, nothing
+    launched); the same plan on the aligned buffer matches the oracle."""
+    import torch
+    layer = RUN_MAJOR_LAYERS[0]
+    _announce("run-major misaligned x", layer.name())
+    lib = B.load()
+    inputs = make_inputs(layer, 911)
+    want = _oracle(orc, layer, inputs)
+    t = {k: torch.from_numpy(v).cuda() for k, v in inputs.items()}
+    n_x = t["x"].numel()
+    xbuf = torch.zeros(n_x + 4, device="cuda")
+    xbuf[:n_x] = t["x"].reshape(-1)
+    y = torch.full((layer.batch, layer.N, layer.Ho, layer.Wo), float("nan"), device="cuda")
+    s = B.make_shape(**layer.asdict())
+    st = torch.cuda.current_stream().cuda_stream
+    plan = B.tdc_plan_create(s, 0, B.make_tuning(variant=B.VARIANT_CHAIN))
+    p = lambda a: a.data_ptr()
+    try:
+        assert lib.tdc_conv_tucker2(plan, st, p(xbuf) + 4, p(t["U_in"]), p(t["core"]), p(t["U_out"]), p(y), s) == B.TDC_ERR_UNSUPPORTED
+        torch.cuda.synchronize()
+        assert bool(torch.isnan(y).all())                      # nothing was written
+        assert lib.tdc_conv_tucker2(plan, st, p(xbuf), p(t["U_in"]), p(t["core"]), p(t["U_out"]), p(y), s) == B.TDC_OK
+        torch.cuda.synchronize()
+        assert_parity(y.cpu().numpy(), want, "run-major, aligned call after a refused one")
+    finally:
+        B.tdc_plan_destroy(plan)
+
+
 def test_two_plans_on_two_streams(orc):
     """Calls only enqueue on the stream they are given: two layers with plans of their own run on two
     non-default streams at once, repeatedly, and each matches the oracle (no hidden use of the default stream,
