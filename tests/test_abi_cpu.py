@@ -122,6 +122,28 @@ def test_selector_respects_forced_fields_and_rejects_misfits():
         B.tdc_select_tuning(s, tuning=B.make_tuning(variant=9))
 
 
+def test_selector_throughput_regime_counts_residency_by_registers():
+    """Where the pixels alone fill the chip the choice is between FUSED and CHAIN, and the estimate counts the
+    workgroups a compute unit holds by the kernels' register footprint (8 wavefronts of the chain kernel, not
+    32): on a layer with two large tiles per compute unit, one 8-wavefront workgroup run twice and two
+    4-wavefront ones run together get the same estimate, and the tie goes to the pair -- the tuning the sweeps
+    found faster."""
+    for layout in (B.LAYOUT_NCHW, B.LAYOUT_NHWC):
+        s = B.make_shape(64, 64, 64, 56, 56, 16, 16, layout=layout)
+        d = B.tdc_select_tuning(s, tuning=B.make_tuning(variant=B.VARIANT_CHAIN)).as_dict()
+        tiles = -(-56 // d["tile_h"]) * -(-56 // d["tile_w"]) * 64
+        assert tiles > 256 and d["waves"][0] == 4, d            # more tiles than compute units: pairs of 4 wavefronts
+        assert B.tdc_select_tuning(s).as_dict()["variant"] in ("fused", "chain")
+    # one tile per compute unit: the whole CU goes to one 8-wavefront workgroup
+    d = B.tdc_select_tuning(B.make_shape(32, 128, 128, 28, 28, 32, 32), tuning=B.make_tuning(variant=B.VARIANT_CHAIN)).as_dict()
+    assert -(-28 // d["tile_h"]) * -(-28 // d["tile_w"]) * 32 <= 256 and d["waves"][0] == 8, d
+    # NCHW rows that are read in 16-byte runs get tiles whose width is a multiple of 4
+    d = B.tdc_select_tuning(B.make_shape(32, 128, 256, 56, 56, 32, 64, 3, 2, 1)).as_dict()
+    assert d["variant"] == "chain" and d["tile_w"] % 4 == 0, d
+    # below the threshold (batch x output pixels < 16 per compute unit) neither the chain kernel nor that rule applies
+    assert B.tdc_select_tuning(B.make_shape(1, 128, 128, 28, 28, 32, 32)).as_dict()["variant"] != "chain"
+
+
 def test_selector_handles_the_dense_layer():
     lib = B.load()
     for cfg in (2, 4):
