@@ -59,7 +59,9 @@ typedef enum tdc_status {
 } tdc_status;
 
 /* Layer geometry.  Supported domain: square K in 1..7; stride in 1..4; pad in 0..K-1; any
- * positive batch, C, N, H, W, R1, R2 for which every tensor has fewer than 2^31 elements.
+ * positive batch (at most 65535), C, N, H, W, R1, R2 for which every tensor has fewer than 2^31
+ * elements and one image of x or y (channels rounded up to 16) is smaller than 2 GiB; outside it
+ * tdc_plan_create returns TDC_ERR_UNSUPPORTED.
  * layout selects how the activations are stored: 0 = NCHW, x[batch][C][H][W] and
  * y[batch][N][Ho][Wo]; 1 = NHWC, x[batch][H][W][C] and y[batch][Ho][Wo][N] (the pixel-major
  * order the paper writes its tensors in, section 3); an epilogue's residual is laid out like y.

@@ -71,6 +71,7 @@ int validate(const tdc_shape &s)
     // one image of any activation and each re-laid-out weight array must fit a 2 GiB buffer descriptor
     const double lim4 = (double)lim / 4;
     if ((double)cp * s.H * s.W >= lim4 || (double)r1p * s.H * s.W >= lim4 || (double)r2p * Ho * Wo >= lim4) return TDC_ERR_UNSUPPORTED;
+    if ((double)np * Ho * Wo >= lim4) return TDC_ERR_UNSUPPORTED;
     if ((double)cp * r1p >= lim4 || (double)r1p * r2p * s.K * s.K >= lim4 || (double)r2p * np >= lim4) return TDC_ERR_UNSUPPORTED;
     if (s.batch > 65535) return TDC_ERR_UNSUPPORTED;   // images ride in the grid's y dimension
     return TDC_OK;

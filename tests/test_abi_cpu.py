@@ -76,7 +76,9 @@ def test_validation_happens_before_any_device_call():
                    B.make_shape(1, 6, 4, 8, 8, 2, 2, layout=B.LAYOUT_NHWC), B.make_shape(1, 4, 6, 8, 8, 2, 2, layout=B.LAYOUT_NHWC),
                    B.make_shape(1, 4, 4, 8, 8, 2, 2, K=9, pad=4),
                    B.make_shape(1, 4, 4, 8, 8, 2, 2, stride=5), B.make_shape(1, 4, 4, 8, 8, 2, 2, K=3, pad=3),
-                   B.make_shape(4096, 1024, 4, 1024, 1024, 2, 2)]
+                   B.make_shape(4096, 1024, 4, 1024, 1024, 2, 2),
+                   B.make_shape(1, 8, 600, 1024, 1024, 2, 2),       # one output image of 2.3 GiB: more than a buffer descriptor spans
+                   B.make_shape(1, 600, 8, 1024, 1024, 2, 2)]       # the same for one input image
     for s in unsupported:
         rc, plan = _create(s)
         assert rc == B.TDC_ERR_UNSUPPORTED and not plan.value
