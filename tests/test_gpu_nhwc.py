@@ -210,3 +210,50 @@ def test_large_batch_sampled_images(orc, layout):
             assert_parity(got[b:b + 1], want, "image %d of 200 [%s]" % (b, conv.describe()))
     finally:
         conv.close()
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
+def test_one_image_at_the_size_limit(orc, layout):
+    """The largest image the library accepts: 16 channels of 4096 x 8188 pixels, 2.146 GB each way, just under the
+    2 GiB one buffer descriptor spans (byte offsets inside an image then use nearly all of 31 bits).  The
+    convolution is local, so windows of the output -- the four corners, tile seams in the middle, the last rows --
+    are compared with the oracle run on the matching crop of x (rows and columns next to a cut edge are left out:
+    the oracle pads the crop with zeros there, the image does not)."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    layer = Layer(1, 16, 16, 4096, 8188, 8, 8)
+    assert B.tdc_select_tuning(B.make_shape(**layer.asdict(), layout=layout)).variant in (B.VARIANT_FUSED, B.VARIANT_CHAIN)
+    with pytest.raises(B.TdcError) as err:              # four more columns and an image no longer fits
+        B.tdc_plan_create(B.make_shape(1, 16, 16, 4096, 8192, 8, 8, layout=layout), 0)
+    assert err.value.status == B.TDC_ERR_UNSUPPORTED
+    _announce("one image at the size limit", layer.name(), "layout", layout)
+    inputs = make_inputs(layer, 4096)
+    dev = torch.device("cuda:0")
+    x_dev = torch.from_numpy(inputs["x"]).to(dev)
+    if layout == B.LAYOUT_NHWC:
+        x_dev = x_dev.permute(0, 2, 3, 1).contiguous()
+    t = {k: torch.from_numpy(v).to(dev) for k, v in inputs.items() if k != "x"}
+    conv = TuckerConv2d(layer, 0, None, layout=layout)
+    try:
+        conv.pack(t["U_in"], t["core"], t["U_out"])
+        y = torch.full(conv.out_shape(), float("nan"), device=dev)
+        conv(x_dev, y)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(y).all()), "some outputs were never written"
+        H, W = layer.H, layer.W
+        windows = [(0, 40, 0, 72), (0, 40, W - 72, W), (H - 40, H, 0, 72), (H - 40, H, W - 72, W),
+                   (2030, 2070, 4070, 4142), (H - 24, H, 3000, 3064), (1000, 1024, W - 64, W)]
+        for (r0, r1, c0, c1) in windows:
+            crop = np.ascontiguousarray(inputs["x"][:, :, r0:r1, c0:c1])
+            small = Layer(1, layer.C, layer.N, r1 - r0, c1 - c0, layer.R1, layer.R2)
+            want, _ = orc.conv_factored(orc.Shape(**small.asdict()), crop, inputs["U_in"], inputs["core"], inputs["U_out"])
+            a, b = (1 if r0 > 0 else 0), (1 if r1 < H else 0)          # rows / columns spoiled by the cut
+            c, d = (1 if c0 > 0 else 0), (1 if c1 < W else 0)
+            want = want[:, :, a:want.shape[2] - b, c:want.shape[3] - d]
+            if layout == B.LAYOUT_NCHW:
+                got = y[:, :, r0 + a:r1 - b, c0 + c:c1 - d].cpu().numpy()
+            else:
+                got = y[:, r0 + a:r1 - b, c0 + c:c1 - d, :].permute(0, 3, 1, 2).contiguous().cpu().numpy()
+            assert_parity(got, want, "window rows %d:%d cols %d:%d [%s]" % (r0, r1, c0, c1, conv.describe()))
+    finally:
+        conv.close()
