@@ -28,6 +28,8 @@ SMALL = [
     Layer(1, 8, 8, 11, 13, 5, 3, 5, 1, 2),      # 5x5 core
     Layer(1, 4, 4, 1, 1, 1, 1, 1, 1, 0),        # a single pixel
     Layer(1, 40, 24, 16, 16, 32, 48, 3, 2, 1),
+    Layer(1, 12, 12, 15, 17, 6, 5, 7, 1, 3),    # 7x7 core: the largest stencil the library takes
+    Layer(2, 8, 8, 18, 21, 4, 7, 7, 4, 6),      # ... with the largest stride (4) and padding (K - 1)
 ]
 
 

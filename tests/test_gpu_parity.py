@@ -40,6 +40,8 @@ SMALL = [
     Layer(1, 3, 2, 1, 1, 1, 1, 1, 1, 0),        # a single pixel
     Layer(1, 4, 4, 3, 3, 2, 2, 3, 1, 1),        # image smaller than any tile
     Layer(1, 40, 24, 16, 16, 32, 48, 3, 2, 1),
+    Layer(1, 10, 12, 15, 17, 6, 5, 7, 1, 3),    # 7x7 core: the largest stencil the library takes
+    Layer(2, 9, 6, 18, 21, 4, 7, 7, 4, 6),      # ... with the largest stride (4) and padding (K - 1)
 ]
 
 
