@@ -223,6 +223,7 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
     const bool runs = tdc_runs_apply(d, dev.cus);
     FusedChoice best;
     int best_cu_waves = 0;
+    long best_x_pixels = 0;
     const int th_lo = forced.tile_h ? forced.tile_h : 1, th_hi = forced.tile_h ? forced.tile_h : std::min(d.Ho, 16);
     const int tw_lo = forced.tile_w ? forced.tile_w : 1, tw_hi = forced.tile_w ? forced.tile_w : std::min(d.Wo, 32);
     for (int th = th_lo; th <= th_hi; ++th)
@@ -235,7 +236,8 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
             // The estimate is the same for one 8-wavefront workgroup per CU run twice and for two 4-wavefront ones run
             // together, and for 8 wavefronts with 16-pixel units against 4 with 32-pixel units.  Measured, more
             // wavefronts on the CU win, and at equal numbers the smaller workgroups (they fall out of step and
-            // overlap their memory and arithmetic phases): ties go to more wavefronts, then to workgroups of 4.
+            // overlap their memory and arithmetic phases): ties go to more wavefronts, then to the tiling that reads the
+            // fewest input pixels (the smallest halo overhead), then to workgroups of 4.
             for (int nw : {4, 8, 2, 1}) {
                 if (forced.waves[0] && nw != forced.waves[0]) continue;
                 for (int pb : {1, 2})
@@ -246,8 +248,11 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
                         int cu_waves = 0;
                         const double us = chain_us(c, d, dev, g, runs, nw, mb1, pb, &cu_waves);
                         const bool tie = std::fabs(us - best.us) <= 1e-9 * us;
-                        if ((!tie && us < best.us) || (tie && cu_waves > best_cu_waves)) {
+                        const long x_pixels = (long)g.tiles_x * g.tiles_y * g.Q;      // input pixels read per image, halos included
+                        if ((!tie && us < best.us) || (tie && cu_waves > best_cu_waves) ||
+                            (tie && cu_waves == best_cu_waves && x_pixels < best_x_pixels)) {
                             best_cu_waves = cu_waves;
+                            best_x_pixels = x_pixels;
                             best.us = us;
                             best.th = th; best.tw = tw; best.nw = nw;
                             best.mb1 = mb1; best.mb2 = 1; best.mb3 = 1; best.pb = pb;
