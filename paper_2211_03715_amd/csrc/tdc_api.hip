@@ -277,7 +277,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED)
         p->geom = tdc_fused_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_CHAIN)
-        p->geom = tdc_chain_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, dev.lds_per_wg);
+        p->geom = tdc_chain_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, p->tuning.waves[0], p->tuning.pb[0], dev.lds_per_wg);
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
         p->geom = tdc_fm_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, p->tuning.waves[0], p->tuning.mb[1]);
     if (rc == TDC_OK) rc = check_tuning(*p, dev);
@@ -366,7 +366,7 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED)
         tmp.geom = tdc_fused_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_CHAIN)
-        tmp.geom = tdc_chain_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, dev.lds_per_wg);
+        tmp.geom = tdc_chain_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, tmp.tuning.waves[0], tmp.tuning.pb[0], dev.lds_per_wg);
     if (rc == TDC_OK && tmp.tuning.variant == TDC_VARIANT_FUSED_MERGED)
         tmp.geom = tdc_fm_geometry(tmp.dims, tmp.tuning.tile_h, tmp.tuning.tile_w, tmp.tuning.waves[0], tmp.tuning.mb[1]);
     if (rc == TDC_OK) rc = check_tuning(tmp, dev);

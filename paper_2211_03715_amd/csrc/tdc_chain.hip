@@ -276,7 +276,7 @@ bool tdc_chain_supported(int nb2, int mb1, int pb)
     return false;
 }
 
-TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit)
+TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int pb, int lds_limit)
 {
     TdcFusedGeom g;
     g.TH = tile_h;
@@ -292,7 +292,13 @@ TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int ld
     g.pitch2 = 0;
     const size_t tiles = (size_t)16 * d.NB1 * g.pitch1 * sizeof(float);
     const size_t weights = (tdc_packed_floats_core(d) + tdc_packed_floats_uout(d)) * sizeof(float);
-    g.weights_in_lds = tiles + weights <= (size_t)lds_limit;
+    // The packed core and U_out go into LDS when they fit and a wavefront has more than one group of pixel
+    // blocks to run them over.  With a single group every fragment is used once per wavefront: staging it
+    // through LDS only adds the copy and the wait for it (measured 5-10% slower on batch-8 to batch-32 layers
+    // of rank 24 and 32 than streaming the fragments from L2 two k-groups ahead).
+    const int groups_per_wave = ((g.PBk + pb - 1) / pb + nw - 1) / nw;
+    g.weights_fit = tiles + weights <= (size_t)lds_limit;
+    g.weights_in_lds = g.weights_fit && groups_per_wave > 1;
     g.lds_bytes = tiles + (g.weights_in_lds ? weights : 0);
     return g;
 }

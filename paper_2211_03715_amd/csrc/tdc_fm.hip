@@ -226,6 +226,7 @@ TdcFusedGeom tdc_fm_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, i
     g.pitch1 = 16 * g.QB + 4;
     g.pitch2 = 0;
     g.weights_in_lds = false;
+    g.weights_fit = false;
     const int ks = nbg > 0 ? nw / nbg : 1;
     g.lds_bytes = (size_t)16 * d.NB1 * g.pitch1 * sizeof(float) + (ks > 1 ? (size_t)nw * g.PBk * 1024 : 0);
     return g;

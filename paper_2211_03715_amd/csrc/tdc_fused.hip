@@ -268,6 +268,7 @@ TdcFusedGeom tdc_fused_geometry(const TdcDims &d, int tile_h, int tile_w, int ld
     const size_t tiles = ((size_t)16 * d.NB1 * g.pitch1 + (size_t)16 * d.NB2 * g.pitch2) * sizeof(float);
     const size_t weights = (tdc_packed_floats_core(d) + tdc_packed_floats_uout(d)) * sizeof(float);
     g.weights_in_lds = tiles + weights <= (size_t)lds_limit;
+    g.weights_fit = g.weights_in_lds;
     g.lds_bytes = tiles + (g.weights_in_lds ? weights : 0);
     return g;
 }

@@ -88,6 +88,7 @@ struct TdcFusedGeom {
     int tiles_x, tiles_y;
     int pitch1, pitch2;  // LDS row pitches (floats) of the z1 and z2 tiles
     bool weights_in_lds; // core and U_out are copied into LDS by every workgroup
+    bool weights_fit;    // ... or would fit there (CHAIN streams them all the same when a wavefront uses them once)
     size_t lds_bytes;
 };
 bool tdc_fused_unit_supported(int mb1, int mb2, int mb3, int pb);
@@ -98,7 +99,7 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
 
 // ---- fused MFMA kernel with stages 2 and 3 chained in registers (tdc_chain.hip)
 bool tdc_chain_supported(int nb2, int mb1, int pb);
-TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int lds_limit);
+TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int pb, int lds_limit);
 hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,
                             const float *x, const float *uin_p, const float *core_p,
                             const float *uout_p, float *y, const TdcEpi &epi, bool prepare_only = false);

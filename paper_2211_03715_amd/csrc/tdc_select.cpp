@@ -199,12 +199,17 @@ double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, 
     const Stage1Work s1 = stage1_work(d, g, runs, nw, mb1, pb);
     const int r23 = cdiv(cdiv(g.PBk, pb), nw);
     const long wgs = (long)g.tiles_x * g.tiles_y * d.B;
-    const int resident = resident_wgs(dev, g.lds_bytes, nw, 2);   // 170-250 registers: two wavefronts per SIMD
+    // Weights that fit in LDS are priced as staged there even where the kernel streams them instead (one group of
+    // pixel blocks per wavefront): the coefficients were fitted on staged runs, and streaming is the cheaper of
+    // the two in that case, so the ranking holds.
+    const bool wl = g.weights_fit;
+    const size_t w_bytes = (size_t)(d.NB2 * KG2 + d.NB3 * d.NB2) * 1024;
+    const size_t lds_as_staged = g.lds_bytes + (g.weights_fit && !g.weights_in_lds ? w_bytes : 0);
+    const int resident = resident_wgs(dev, lds_as_staged, nw, 2);   // 170-250 registers: two wavefronts per SIMD
     const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
     *cu_waves = per_cu * nw;
     const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
     const double share = std::max(1.0, per_cu * nw / 4.0);
-    const bool wl = g.weights_in_lds;
     const double w_kb = wl ? (double)(d.NB2 * KG2 + d.NB3 * d.NB2) : 0.0;
     const bool vec = d.nhwc || (g.TW % 4 == 0 && d.Wo % 4 == 0);
     double t = runs ? s1.rounds * (c.s1r_unit + d.KG1 * (c.s1r_kg + c.s1r_mfma * s1.quads * share))
@@ -231,8 +236,6 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
             if (th * tw > 512) continue;
             // NCHW: whole 16-byte quads where the image allows them (NHWC stores are 16 bytes whatever the tile)
             if (!forced.tile_w && !d.nhwc && d.Wo % 4 == 0 && tw % 4) continue;
-            const TdcFusedGeom g = tdc_chain_geometry(d, th, tw, dev.lds_per_wg);
-            if ((long)g.lds_bytes > dev.lds_per_wg) continue;
             // The estimate is the same for one 8-wavefront workgroup per CU run twice and for two 4-wavefront ones run
             // together, and for 8 wavefronts with 16-pixel units against 4 with 32-pixel units.  Measured, more
             // wavefronts on the CU win, and at equal numbers the smaller workgroups (they fall out of step and
@@ -240,10 +243,12 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
             // fewest input pixels (the smallest halo overhead), then to workgroups of 4.
             for (int nw : {4, 8, 2, 1}) {
                 if (forced.waves[0] && nw != forced.waves[0]) continue;
-                for (int pb : {1, 2})
+                for (int pb : {1, 2}) {
+                    if (forced.pb[0] && pb != forced.pb[0]) continue;
+                    const TdcFusedGeom g = tdc_chain_geometry(d, th, tw, nw, pb, dev.lds_per_wg);
+                    if ((long)g.lds_bytes > dev.lds_per_wg) continue;
                     for (int mb1 : kMb) {
                         if (forced.mb[0] && mb1 != forced.mb[0]) continue;
-                        if (forced.pb[0] && pb != forced.pb[0]) continue;
                         if (d.NB1 % mb1 || !tdc_chain_supported(d.NB2, mb1, pb)) continue;
                         int cu_waves = 0;
                         const double us = chain_us(c, d, dev, g, runs, nw, mb1, pb, &cu_waves);
@@ -258,6 +263,7 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
                             best.mb1 = mb1; best.mb2 = 1; best.mb3 = 1; best.pb = pb;
                         }
                     }
+                }
             }
         }
     return best;

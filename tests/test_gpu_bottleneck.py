@@ -75,7 +75,8 @@ def test_large_lds_kernels_under_graph_capture(orc, variant):
     sets[1] = dict(sets[0], x=sets[1]["x"])          # one set of weights (the packed one), two inputs
     wants = [orc.conv_factored(orc.Shape(**layer.asdict()), **inp)[0] for inp in sets]
     t = {k: torch.from_numpy(v).to(dev) for k, v in sets[0].items()}
-    conv = TuckerConv2d(layer, 0, B.make_tuning(variant=variant, tile_h=4, tile_w=28, waves=(8, 8, 8)))
+    conv = TuckerConv2d(layer, 0, B.make_tuning(variant=variant, tile_h=4, tile_w=28, waves=(4, 4, 4), mb=(1, 1, 1),
+                                              pb=(1, 1, 1)))   # two groups of pixel blocks per wavefront: the chain kernel stages its weights in LDS
     try:
         assert "lds=" in conv.describe() and int(conv.describe().split("lds=")[1].split("B")[0]) > 48 * 1024
         conv.pack(t["U_in"], t["core"], t["U_out"])
