@@ -14,8 +14,9 @@
 // one dependent launch adds a constant.  The coefficients (microseconds) were fitted by
 // non-negative least squares to exhaustive sweeps on MI355X, separately for the latency regime
 // (batch 1: one-launch and GEMM kernels, ~2500-6600 tunings per model) and the throughput regime
-// (batch 8/32: fused and chain kernels in both activation layouts, ~12600 tunings); median
-// relative errors 5-12%.  Each coefficient struct below says what its terms stand for.
+// (eight batch-1 to batch-64 layers: fused and chain kernels in both activation layouts and both
+// forms of stage 1, ~30000 tunings); median relative errors 5-12%.  Each coefficient struct below
+// says what its terms stand for.
 #include <algorithm>
 #include <climits>
 #include <cmath>
