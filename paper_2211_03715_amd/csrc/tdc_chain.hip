@@ -17,6 +17,8 @@
 // The paper's kernel keeps one output channel per thread and the R x S weights of the current
 // input channel in registers (section 5.2); here the register-resident object is the whole
 // R2-channel column of z2 for 16 or 32 pixels, which is what lets the 1x1 expansion ride along.
+#include <type_traits>
+
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
 #include "tdc_stage1.h"
@@ -194,7 +196,13 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
                 else u[kg] = tdc_buf_load4(ors, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
             }
         };
-        const auto emit = [&](int nb, const tdc_f4(&u)[NB2]) {
+        // `with_epi` is a compile-time flag: the loop over output blocks exists twice, with and without the epilogue.
+        // The epilogue loads (bias, shortcut) put vector-memory loads into the loop, and the waits the compiler
+        // then needs before reusing their registers count the y stores of the previous block as well (stores and
+        // loads share one in-order counter): every block would wait for the stores of the one before it.  The
+        // plain loop has stores only and never waits on them.
+        const auto emit = [&](auto with_epi, int nb, const tdc_f4(&u)[NB2]) {
+            constexpr bool EPI = decltype(with_epi)::value;
             tdc_f4 acc3[PB];
 #pragma unroll
             for (int pb = 0; pb < PB; ++pb) acc3[pb] = tdc_f4_zero();
@@ -209,13 +217,16 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
                 const int n = 16 * nb + 4 * g;
 #pragma unroll
                 for (int pb = 0; pb < PB; ++pb)
-                    if (ypix[pb] >= 0 && n < a.N)
-                        tdc_store_nhwc(a.y, a.epi, acc3[pb], n, ((size_t)b * P2 + ypix[pb]) * a.N + n);
+                    if (ypix[pb] >= 0 && n < a.N) {
+                        const size_t cell = ((size_t)b * P2 + ypix[pb]) * a.N + n;
+                        if constexpr (EPI) tdc_store_nhwc(a.y, a.epi, acc3[pb], n, cell);
+                        else *reinterpret_cast<tdc_f4 *>(a.y + cell) = acc3[pb];
+                    }
                 return;
             }
             // channels past N lie beyond the descriptor: the hardware drops those stores
             const unsigned plane = (unsigned)(16 * nb + l16) * P2 * 4u;
-            if (a.epi.bias || a.epi.residual || a.epi.relu) {
+            if constexpr (EPI) {
                 // this lane holds channel 16*nb + l16 at the four pixels 4*g + i of every block
                 const int n = 16 * nb + l16;
                 const float bias = (a.epi.bias && n < a.N) ? a.epi.bias[n] : 0.f;
@@ -240,25 +251,29 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
                 }
             }
         };
-        fetch(0, ua[0]);
-        if constexpr (D3 == 3) {
-            fetch(1, ua[1]);
-            for (int nb = 0; nb < a.NB3; nb += 3) {
-                fetch(nb + 2, ua[2]);
-                emit(nb, ua[0]);
-                fetch(nb + 3, ua[0]);
-                if (nb + 1 < a.NB3) emit(nb + 1, ua[1]);
-                fetch(nb + 4, ua[1]);
-                if (nb + 2 < a.NB3) emit(nb + 2, ua[2]);
+        const auto stage3 = [&](auto with_epi) {
+            fetch(0, ua[0]);
+            if constexpr (D3 == 3) {
+                fetch(1, ua[1]);
+                for (int nb = 0; nb < a.NB3; nb += 3) {
+                    fetch(nb + 2, ua[2]);
+                    emit(with_epi, nb, ua[0]);
+                    fetch(nb + 3, ua[0]);
+                    if (nb + 1 < a.NB3) emit(with_epi, nb + 1, ua[1]);
+                    fetch(nb + 4, ua[1]);
+                    if (nb + 2 < a.NB3) emit(with_epi, nb + 2, ua[2]);
+                }
+            } else {
+                for (int nb = 0; nb < a.NB3; nb += 2) {
+                    fetch(nb + 1, ua[1]);
+                    emit(with_epi, nb, ua[0]);
+                    fetch(nb + 2, ua[0]);
+                    if (nb + 1 < a.NB3) emit(with_epi, nb + 1, ua[1]);
+                }
             }
-        } else {
-            for (int nb = 0; nb < a.NB3; nb += 2) {
-                fetch(nb + 1, ua[1]);
-                emit(nb, ua[0]);
-                fetch(nb + 2, ua[0]);
-                if (nb + 1 < a.NB3) emit(nb + 1, ua[1]);
-            }
-        }
+        };
+        if (a.epi.bias || a.epi.residual || a.epi.relu) stage3(std::true_type{});
+        else stage3(std::false_type{});
     }
     TDC_PROBE(7);
 }

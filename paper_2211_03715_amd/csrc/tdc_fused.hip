@@ -27,6 +27,8 @@
 // and U_out weights into LDS while those loads are in flight (template flag WLDS; when the
 // weights do not fit, stages 2 and 3 stream them from L2 through the same register pipeline).
 // After that, stages 2 and 3 touch only LDS.
+#include <type_traits>
+
 #include "tdc_internal.h"
 #include "tdc_mfma.h"
 #include "tdc_stage1.h"
@@ -176,57 +178,69 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
         const int P2 = a.Ho * a.Wo;
         float *__restrict__ yb = a.y + (size_t)b * a.N * P2;
         const tdc_rsrc wrs = tdc_make_rsrc(a.uout_p, (unsigned)a.w_uout4 * 16u);
-        for (int u = wave; u < n_pg * n_mg; u += nw) {
-            const int mg = tdc_div(u, a.div_npg2), pg = u - mg * n_pg;
-            int yoff[PB], col[PB];
-            bool ok[PB];
-#pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                const int p = 16 * (pg * PB + pb) + l16;
-                const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
-                const int i = i0 + ph, j = j0 + pw;
-                ok[pb] = p < a.P && i < a.Ho && j < a.Wo;
-                yoff[pb] = i * a.Wo + j;
-                col[pb] = g * a.pitch2 + min(16 * (pg * PB + pb), 16 * (a.PBk - 1)) + l16;
-            }
-            int kg = 0;
-            auto next = [&](tdc_f4(&av)[MB3], tdc_f4(&bv)[PB]) {
-                const bool live = kg < a.NB2;
-                const int kgc = live ? kg : 0;
-#pragma unroll
-                for (int mb = 0; mb < MB3; ++mb) {
-                    const int frag = (mg * MB3 + mb) * a.NB2 + kg;
-                    if (WLDS) av[mb] = wO[(live ? frag : 0) * 64 + lane];
-                    else av[mb] = tdc_buf_load4(wrs, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
-                }
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb) bv[pb] = z2s[kgc * 4 * a.pitch2 + col[pb]];
-                ++kg;
-            };
-            TdcPipe<MB3, PB, U> pipe;
-            tdc_f4 acc[MB3][PB];
-            pipe.start(next);
-            pipe.run(acc, a.NB2, next);
-#pragma unroll
-            for (int mb = 0; mb < MB3; ++mb)
+        // The loop over register tiles exists twice, with and without the epilogue: the epilogue's loads (bias,
+        // shortcut) would put waits on the vector-memory counter into it, and that counter also holds the y stores
+        // of the previous tile.  The plain loop stores and moves on.
+        const auto stage3 = [&](auto with_epi) {
+            constexpr bool EPI = decltype(with_epi)::value;
+            for (int u = wave; u < n_pg * n_mg; u += nw) {
+                const int mg = tdc_div(u, a.div_npg2), pg = u - mg * n_pg;
+                int yoff[PB], col[PB];
+                bool ok[PB];
 #pragma unroll
                 for (int pb = 0; pb < PB; ++pb) {
-                    if (NHWC) {
-                        const int n = 16 * (mg * MB3 + mb) + 4 * g;
-                        if (ok[pb] && n < a.N)
-                            tdc_store_nhwc(a.y, a.epi, acc[mb][pb], n, ((size_t)b * P2 + yoff[pb]) * a.N + n);
-                        continue;
+                    const int p = 16 * (pg * PB + pb) + l16;
+                    const int ph = tdc_div(p, a.div_TW), pw = p - ph * a.TW;
+                    const int i = i0 + ph, j = j0 + pw;
+                    ok[pb] = p < a.P && i < a.Ho && j < a.Wo;
+                    yoff[pb] = i * a.Wo + j;
+                    col[pb] = g * a.pitch2 + min(16 * (pg * PB + pb), 16 * (a.PBk - 1)) + l16;
+                }
+                int kg = 0;
+                auto next = [&](tdc_f4(&av)[MB3], tdc_f4(&bv)[PB]) {
+                    const bool live = kg < a.NB2;
+                    const int kgc = live ? kg : 0;
+#pragma unroll
+                    for (int mb = 0; mb < MB3; ++mb) {
+                        const int frag = (mg * MB3 + mb) * a.NB2 + kg;
+                        if (WLDS) av[mb] = wO[(live ? frag : 0) * 64 + lane];
+                        else av[mb] = tdc_buf_load4(wrs, ((unsigned)frag * 1024u + lane * 16u) | (live ? 0u : TDC_OOB));
                     }
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int n = 16 * (mg * MB3 + mb) + 4 * g + i;
-                        if (ok[pb] && n < a.N) {
-                            const size_t idx = (size_t)n * P2 + yoff[pb];
-                            yb[idx] = tdc_apply_epilogue(a.epi, acc[mb][pb][i], n, (size_t)b * a.N * P2 + idx);
+                    for (int pb = 0; pb < PB; ++pb) bv[pb] = z2s[kgc * 4 * a.pitch2 + col[pb]];
+                    ++kg;
+                };
+                TdcPipe<MB3, PB, U> pipe;
+                tdc_f4 acc[MB3][PB];
+                pipe.start(next);
+                pipe.run(acc, a.NB2, next);
+#pragma unroll
+                for (int mb = 0; mb < MB3; ++mb)
+#pragma unroll
+                    for (int pb = 0; pb < PB; ++pb) {
+                        if (NHWC) {
+                            const int n = 16 * (mg * MB3 + mb) + 4 * g;
+                            if (ok[pb] && n < a.N) {
+                                const size_t cell = ((size_t)b * P2 + yoff[pb]) * a.N + n;
+                                if constexpr (EPI) tdc_store_nhwc(a.y, a.epi, acc[mb][pb], n, cell);
+                                else *reinterpret_cast<tdc_f4 *>(a.y + cell) = acc[mb][pb];
+                            }
+                            continue;
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int n = 16 * (mg * MB3 + mb) + 4 * g + i;
+                            if (ok[pb] && n < a.N) {
+                                const size_t idx = (size_t)n * P2 + yoff[pb];
+                                if constexpr (EPI) yb[idx] = tdc_apply_epilogue(a.epi, acc[mb][pb][i], n, (size_t)b * a.N * P2 + idx);
+                                else yb[idx] = acc[mb][pb][i];
+                            }
                         }
                     }
-                }
-        }
+            }
+        };
+        if (a.epi.bias || a.epi.residual || a.epi.relu) stage3(std::true_type{});
+        else stage3(std::false_type{});
     }
     TDC_PROBE(7);
 }
