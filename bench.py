@@ -202,11 +202,15 @@ def main():
 
     # per-layer: events around back-to-back launches of that layer alone, on the launch stream
     iters = max(200, min(2000, args.steps))
-    per_layer = []
-    for i, (L, conv, launch) in enumerate(zip(layers, convs, launchers)):
+    # (all layers first, before the slower side measurements below leave the GPU idle between launches)
+    queued = []
+    for launch in launchers:
         for _ in range(200):                      # clocks and caches settled before the timed launches
             launch()
-        sec = _time_events(launch, iters, torch)
+        queued.append(_time_events(launch, iters, torch))
+    per_layer = []
+    for i, (L, conv, launch) in enumerate(zip(layers, convs, launchers)):
+        sec = queued[i]
         bound, t_roof, t_hbm, t_mfma = R.roofline(L)
         row = {
             "layer": L.name(), "plan": conv.describe(), "kernels": conv.kernel_count(),

@@ -50,10 +50,13 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
     tdc_f4 *__restrict__ red = z1s + (size_t)4 * a.NB1 * a.pitch1;     // [wave][PBK][64]   (KS > 1)
 
     TDC_PROBE(0);
+    unsigned bd = blockDim.x;
+    TdcDiv div_tiles = a.div_tiles;
+    TDC_FETCH_NOW(TDC_OUTS("+s"(bd), "+s"(div_tiles.m)), "s"(a.x), "s"(a.uin_p), "s"(a.wm_p), "s"(div_tiles.sh1), "s"(div_tiles.sh2));
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = (int)(bd >> 6);
     const int g = lane >> 4, l16 = lane & 15;
-    const int ng = tdc_div(blockIdx.x, a.div_tiles), tile = blockIdx.x - ng * a.tiles, b = blockIdx.y;
+    const int ng = tdc_div(blockIdx.x, div_tiles), tile = blockIdx.x - ng * a.tiles, b = blockIdx.y;
     const int ty = tdc_div(tile, a.div_tiles_x), tx = tile - ty * a.tiles_x;
     const int i0 = ty * a.TH, j0 = tx * a.TW;
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;

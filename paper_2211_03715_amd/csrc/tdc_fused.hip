@@ -65,10 +65,18 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
     tdc_f4 *__restrict__ wC = z2s + (size_t)4 * a.NB2 * a.pitch2;     // packed core   (WLDS)
     tdc_f4 *__restrict__ wO = wC + a.w_core4;                         // packed U_out  (WLDS)
 
+    // every argument stage 1 needs, in one round of scalar loads (see TDC_FETCH_NOW)
+    unsigned bd = blockDim.x;
+    TdcDiv div_tiles_x = a.div_tiles_x;
+    TDC_FETCH_NOW(TDC_OUTS("+s"(bd), "+s"(div_tiles_x.m)), "s"(a.x), "s"(a.uin_p), "s"(a.core_p), "s"(a.uout_p), "s"(a.y), "s"(a.C), "s"(a.H), "s"(a.W),
+                  "s"(a.stride), "s"(a.pad), "s"(a.NB1), "s"(a.KG1), "s"(a.TH), "s"(a.TW), "s"(a.QW), "s"(a.Q), "s"(a.QB), "s"(a.tiles_x),
+                  "s"(a.pitch1), "s"(a.w_core4), "s"(a.w_uout4), "s"(a.QH), "s"(a.RPR), "s"(a.n_sb), "s"(a.div_RPR.m), "s"(a.div_RPR.sh1),
+                  "s"(a.div_RPR.sh2), "s"(a.div_nsb.m), "s"(a.div_nsb.sh1), "s"(a.div_nsb.sh2), "s"(div_tiles_x.sh1), "s"(div_tiles_x.sh2),
+                  "s"(a.div_QW.m), "s"(a.div_QW.sh1), "s"(a.div_QW.sh2), "s"(a.div_npg1.m), "s"(a.div_npg1.sh1), "s"(a.div_npg1.sh2));
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = (int)(bd >> 6);
     const int g = lane >> 4, l16 = lane & 15;
-    const int ty = tdc_div(blockIdx.x, a.div_tiles_x), tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
+    const int ty = tdc_div(blockIdx.x, div_tiles_x), tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
     const int i0 = ty * a.TH, j0 = tx * a.TW;                   // first output pixel of the tile
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;  // first input pixel (may be < 0)
     const int HW = a.H * a.W;

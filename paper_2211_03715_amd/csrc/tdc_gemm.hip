@@ -136,12 +136,18 @@ template <int MODE, int ACT, int MB, int PB, int U>
 __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
 {
     extern __shared__ float red[];
+    unsigned bd = blockDim.x, gd = gridDim.x;
+    TdcDiv div_inner = a.div_inner;
+    TDC_FETCH_NOW(TDC_OUTS("+s"(bd), "+s"(gd), "+s"(div_inner.m)), "s"(a.act), "s"(a.wp), "s"(a.out), "s"(a.act_rows),
+                  "s"(a.act_rows_valid), "s"(a.out_layout), "s"(a.act_pix), "s"(a.out_pix), "s"(a.KG), "s"(a.NBk), "s"(a.n_pgroups),
+                  "s"(a.n_mgroups), "s"(a.pg_major), "s"(a.kg_q), "s"(a.kg_r), "s"(div_inner.sh1), "s"(div_inner.sh2), "s"(a.div_Wo.m),
+                  "s"(a.div_Wo.sh1), "s"(a.div_Wo.sh2), "s"(a.H), "s"(a.W), "s"(a.Wo), "s"(a.stride), "s"(a.pad));
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = (int)(bd >> 6);
     const int g = lane >> 4, l16 = lane & 15;
-    const int lb = tdc_logical_block(blockIdx.x, gridDim.x);
+    const int lb = tdc_logical_block(blockIdx.x, (int)gd);
     const int inner = a.pg_major ? a.n_mgroups : a.n_pgroups;   // one division on the way to the first load
-    const int hi = tdc_div(lb, a.div_inner), lo = lb - hi * inner;
+    const int hi = tdc_div(lb, div_inner), lo = lb - hi * inner;
     const int pg = a.pg_major ? hi : lo, mg = a.pg_major ? lo : hi;
     const int b = blockIdx.y;
 

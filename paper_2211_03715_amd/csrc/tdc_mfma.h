@@ -75,6 +75,18 @@ __device__ __forceinline__ void tdc_store_nhwc(float *__restrict__ y, const TdcE
     *reinterpret_cast<tdc_f4 *>(y + cell) = v;
 }
 
+// Kernel arguments arrive through scalar loads that the compiler issues where a value is first needed.  A
+// prologue that needs some arguments for its tile arithmetic and others (the pointers, the block size) for
+// its first vector load then makes two or three DEPENDENT scalar-memory round trips before that load -- at
+// kernel durations of a few microseconds a measurable part of the whole.  TDC_FETCH_NOW(outs, ins) is one
+// empty asm statement: `ins` ("s"(x), "s"(y), ...) are the arguments the prologue will need, which must all
+// be in scalar registers at that one point; `outs` ("+s"(v), ...) are a few values that everything in the
+// prologue is computed from (block size, grid size, the first divisor), passed through the statement so
+// that none of that arithmetic can be scheduled in front of it.  All argument loads are then issued together
+// at the top of the kernel and cost one round trip.
+#define TDC_FETCH_NOW(outs, ...) asm volatile("" : outs : __VA_ARGS__)
+#define TDC_OUTS(...) __VA_ARGS__
+
 __device__ __forceinline__ int tdc_div(int x, const TdcDiv &d)
 {
     return (int)tdc_div_from_hi((unsigned)x, __umulhi(d.m, (unsigned)x), d);
