@@ -18,6 +18,8 @@ weights already resident in HBM.  Prints ONE JSON line.
                (the CPU oracle's three-stage and dense paths, all host threads and one thread)
   roofline     the same for the dominant (slowest) layer's kernel
   null_launch_us  an empty kernel timed the same way: the floor any batch-1 layer sits on
+  throughput_regime  the batch-32 128->256 stride-2 layer (config 4) timed the same way, against the
+               fp32 MFMA peak: a side figure, not part of value
   cpu_baseline the CPU oracle (three-stage, fp64) timed on the host cores on the same sweep
 """
 from __future__ import annotations
@@ -320,6 +322,27 @@ def main():
         torch.cuda.synchronize()
         for c in n_convs:
             c.close()
+    if args.config == 2 and variant == 0 and not args.brief:
+        # beside the latency-bound headline: the one layer of config 4 whose batch fills the chip, against the
+        # same fp32 MFMA peak (a reported side figure; `value` and `roofline` above are the batch-1 sweep's)
+        Lt = config_layers(4)[2]
+        inp = make_inputs(Lt, layer_seed(4, 2))
+        t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
+        ct = TuckerConv2d(Lt, 0, None, layout=layout)
+        ct.pack(t["U_in"], t["core"], t["U_out"])
+        xt = t["x"].permute(0, 2, 3, 1).contiguous() if layout == B.LAYOUT_NHWC else t["x"]
+        yt = torch.empty(ct.out_shape(), device=dev, dtype=torch.float32)
+        lt = ct.bind(xt, yt)
+        for _ in range(200):
+            lt()
+        t_sec = _time_events(lt, 500, torch)
+        out["throughput_regime"] = {
+            "layer": Lt.name(), "plan": ct.describe(), "latency_us": t_sec * 1e6,
+            "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / t_sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12,
+                         "unit": "TFLOP/s", "frac": R.flops(Lt) / t_sec / R.FP32_MFMA_PEAK}}
+        torch.cuda.synchronize()
+        ct.close()
+        del xt, yt, t
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
         if not args.brief:
