@@ -55,7 +55,9 @@ typedef enum tdc_status {
     TDC_ERR_UNSUPPORTED = -4,     /* valid layer outside the supported domain (see below)     */
     TDC_ERR_ALLOC = -5,           /* device or host allocation failed                         */
     TDC_ERR_HIP = -6,             /* a HIP runtime call or a kernel launch failed             */
-    TDC_ERR_BAD_TUNING = -7       /* a forced tuning does not fit the shape or the hardware   */
+    TDC_ERR_BAD_TUNING = -7,      /* a forced tuning does not fit the shape or the hardware   */
+    TDC_ERR_TOO_LARGE = -8        /* tdc_conv_tucker2_static: the layer needs more scratch memory than
+                                     TDC_STATIC_SCRATCH_BYTES                                  */
 } tdc_status;
 
 /* Layer geometry.  Supported domain: square K in 1..7; stride in 1..4; pad in 0..K-1; any
@@ -168,6 +170,29 @@ int tdc_conv_dense(tdc_plan *plan, void *hip_stream, const float *x, const float
                    const tdc_shape *shape);
 int tdc_conv_dense_ex(tdc_plan *plan, void *hip_stream, const float *x, const float *W, float *y,
                       const tdc_shape *shape, const tdc_epilogue *epilogue);
+
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same result as tdc_conv_tucker2 on a plan of variant
+ * TDC_VARIANT_SPLIT (three fp32-MFMA GEMM kernels behind the weight re-layout), but without a plan:
+ * the re-laid-out weights and the intermediates z1, z2 live in one device array of
+ * TDC_STATIC_SCRATCH_BYTES that is part of the library's code object, so every GPU the library
+ * runs on holds that much until the process ends.  The call enqueues six kernels on `hip_stream`
+ * and returns; it calls no hipMalloc / hipFree and no allocating library routine, and never
+ * synchronises.  It runs on the calling thread's CURRENT device, which must be the device of the
+ * stream and of all five tensors.
+ * Scratch needed, in floats, each term rounded up to a multiple of 64:
+ *     16*ceil(R1/16) * 16*ceil(C/16)  +  16*ceil(R2/16) * K*K * 16*ceil(R1/16)  +  16*ceil(N/16) * 16*ceil(R2/16)
+ *   + batch * 16*ceil(R1/16) * H*W    +  batch * 16*ceil(R2/16) * Ho*Wo;
+ * a layer that needs more returns TDC_ERR_TOO_LARGE and enqueues nothing.  Other errors as for
+ * tdc_plan_create and tdc_conv_tucker2 (NHWC: C, N multiples of 4 and 16-byte aligned x, y).
+ * All calls on one GPU share the one array, which keeps the last call's contents; every call
+ * overwrites what it reads, so nothing carries over, but two calls that may overlap in time on one
+ * GPU (different streams, or the same array through two processes' own copies is fine -- each
+ * process has its own) race on it: order them on one stream or with events. */
+#define TDC_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+int tdc_conv_tucker2_static(void *hip_stream,
+                            const float *x, const float *U_in, const float *core, const float *U_out,
+                            float *y, const tdc_shape *shape);
 
 /* Release the plan and its workspace.  NULL is accepted. */
 int tdc_plan_destroy(tdc_plan *plan);

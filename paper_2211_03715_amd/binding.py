@@ -21,6 +21,8 @@ TDC_ERR_UNSUPPORTED = -4
 TDC_ERR_ALLOC = -5
 TDC_ERR_HIP = -6
 TDC_ERR_BAD_TUNING = -7
+TDC_ERR_TOO_LARGE = -8
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN, VARIANT_DENSE, VARIANT_MERGED = 0, 1, 2, 3, 4, 5, 6
@@ -32,7 +34,8 @@ EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", 
            "tdc_plan_destroy", "tdc_plan_get_tuning", "tdc_plan_describe", "tdc_plan_workspace_bytes",
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
            "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks",
-           "tdc_conv_tucker2_ex", "tdc_conv_dense_ex", "tdc_hosvd_tucker2", "tdc_admm_project"]
+           "tdc_conv_tucker2_ex", "tdc_conv_dense_ex", "tdc_hosvd_tucker2", "tdc_admm_project",
+           "tdc_conv_tucker2_static"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -96,6 +99,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_plan_pack_weights.restype = ip
     lib.tdc_conv_tucker2.argtypes = [vp, vp, vp, vp, vp, vp, vp, sp]
     lib.tdc_conv_tucker2.restype = ip
+    lib.tdc_conv_tucker2_static.argtypes = [vp, vp, vp, vp, vp, vp, sp]
+    lib.tdc_conv_tucker2_static.restype = ip
     lib.tdc_plan_pack_dense.argtypes = [vp, vp, vp]
     lib.tdc_plan_pack_dense.restype = ip
     lib.tdc_conv_dense.argtypes = [vp, vp, vp, vp, vp, sp]
@@ -225,6 +230,14 @@ def tdc_conv_tucker2(plan, x, U_in, core, U_out, y, shape: tdc_shape, stream=Non
                                  _ptr(y), ctypes.byref(shape))
     if rc != TDC_OK:
         raise TdcError(rc, "tdc_conv_tucker2")
+
+
+def tdc_conv_tucker2_static(x, U_in, core, U_out, y, shape: tdc_shape, stream=None) -> None:
+    """The plan-less call that allocates nothing (scratch in a static device array of the library)."""
+    rc = load().tdc_conv_tucker2_static(_stream(stream), _ptr(x), _ptr(U_in), _ptr(core), _ptr(U_out), _ptr(y),
+                                        ctypes.byref(shape))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_conv_tucker2_static")
 
 
 def tdc_plan_pack_dense(plan, W, stream=None) -> None:

@@ -236,6 +236,7 @@ const char *tdc_status_string(int status)
         case TDC_ERR_ALLOC: return "allocation failed";
         case TDC_ERR_HIP: return "HIP runtime or kernel launch error";
         case TDC_ERR_BAD_TUNING: return "forced tuning does not fit the shape or the device";
+        case TDC_ERR_TOO_LARGE: return "layer needs more scratch memory than the static buffer holds";
         default: return "unknown status";
     }
 }
@@ -522,3 +523,77 @@ int tdc_launch_null(void *hip_stream)
 }
 
 }  // extern "C"
+
+// ---- the entry point that allocates nothing.  Its scratch memory (re-laid-out weights, z1, z2: what a SPLIT
+// plan keeps in hipMalloc'ed workspace) is this file-scope device array.  The name is a host-side stand-in,
+// not a device address: host code only ever uses the per-device pointer hipGetSymbolAddress returns for it.
+static __device__ __align__(256) float tdc_static_scratch[TDC_STATIC_SCRATCH_BYTES / sizeof(float)];
+
+namespace {
+
+struct StaticDevice {
+    float *scratch;      // this device's copy of tdc_static_scratch, or null before the first call on it
+    TdcDeviceInfo info;
+};
+constexpr int kMaxStaticDevices = 64;
+StaticDevice static_devices[kMaxStaticDevices];
+std::mutex static_lock;
+
+// Looks the calling thread's current device up, resolving the array's address the first time that device is seen.
+int static_device(StaticDevice *out)
+{
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return TDC_ERR_HIP;
+    if (device < 0 || device >= kMaxStaticDevices) return TDC_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(static_lock);
+    StaticDevice &sd = static_devices[device];
+    if (!sd.scratch) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(tdc_static_scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return TDC_ERR_HIP;
+        }
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return TDC_ERR_HIP;
+        sd.info.cus = v > 0 ? v : 256;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) return TDC_ERR_HIP;
+        sd.info.lds_per_wg = v > 0 ? v : 65536;
+        sd.scratch = static_cast<float *>(ptr);
+    }
+    *out = sd;
+    return TDC_OK;
+}
+
+size_t round64(size_t floats) { return (floats + 63) / 64 * 64; }   // regions start on 256-byte boundaries
+
+}  // namespace
+
+extern "C" int tdc_conv_tucker2_static(void *hip_stream, const float *x, const float *U_in, const float *core,
+                            const float *U_out, float *y, const tdc_shape *shape)
+{
+    if (!x || !U_in || !core || !U_out || !y || !shape) return TDC_ERR_NULL;
+    int rc = validate(*shape);
+    if (rc != TDC_OK) return rc;
+    TdcDims d = make_dims(*shape);
+    if (d.nhwc && misaligned16(x, y, nullptr)) return TDC_ERR_UNSUPPORTED;
+    // scratch regions: packed U_in | packed core | packed U_out | z1 | z2
+    const size_t n_w1 = round64(tdc_packed_floats_uin(d)), n_w2 = round64(tdc_packed_floats_core(d));
+    const size_t n_w3 = round64(tdc_packed_floats_uout(d));
+    const size_t n_z1 = round64((size_t)d.B * 16 * d.NB1 * d.H * d.W), n_z2 = round64((size_t)d.B * 16 * d.NB2 * d.Ho * d.Wo);
+    if (n_w1 + n_w2 + n_w3 + n_z1 + n_z2 > TDC_STATIC_SCRATCH_BYTES / sizeof(float)) return TDC_ERR_TOO_LARGE;
+    StaticDevice sd;
+    rc = static_device(&sd);
+    if (rc != TDC_OK) return rc;
+    tdc_tuning t;
+    memset(&t, 0, sizeof(t));
+    t.variant = TDC_VARIANT_SPLIT;
+    rc = tdc_select(d, sd.info, &t, nullptr);
+    if (rc != TDC_OK) return rc;
+    float *uin_p = sd.scratch, *core_p = uin_p + n_w1, *uout_p = core_p + n_w2, *z1 = uout_p + n_w3, *z2 = z1 + n_z1;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // every element of the five regions is written before it is read (the re-layout kernels write their zero
+    // padding themselves, each GEMM stage writes all of its output), so nothing has to be cleared between calls
+    if (tdc_launch_pack(d, s, U_in, core, U_out, uin_p, core_p, uout_p) != hipSuccess) return TDC_ERR_HIP;
+    const TdcEpi none{nullptr, nullptr, 0};
+    return tdc_launch_split(d, t, s, x, uin_p, core_p, uout_p, z1, z2, y, none) == hipSuccess ? TDC_OK : TDC_ERR_HIP;
+}
