@@ -148,10 +148,11 @@ struct TdcPipe {
     }
 };
 
-// Phase timestamps for kernel bring-up: compiled in only with -DTDC_PHASE_TIMING, in a build that
-// includes every source into one translation unit (never in the shipped library).  Slot s of
-// wavefront w of workgroup b lands in tdc_probe_buf[((b*8+w)*16+s)*2 + {0,1}] as
-// (shader clock, 100 MHz wall clock).
+// Phase timestamps for kernel bring-up: compiled in only with -DTDC_PHASE_TIMING, by the probe build
+// (`python -m paper_2211_03715_amd.build --probes`, which puts every source into one translation unit and
+// writes libtdc_probe.so; never in the shipped library).  Slot s of wavefront w of workgroup b lands in
+// tdc_probe_buf[((b*8+w)*16+s)*2 + {0,1}] as (shader clock, 100 MHz wall clock);
+// `python -m paper_2211_03715_amd.probes` reads them back.
 #ifdef TDC_PHASE_TIMING
 __device__ unsigned long long tdc_probe_buf[2 * 8 * 16 * 4096];
 #define TDC_PROBE(slot)                                                                             \
@@ -165,6 +166,12 @@ __device__ unsigned long long tdc_probe_buf[2 * 8 * 16 * 4096];
 extern "C" int tdc_debug_read_probes(unsigned long long *host, size_t count)
 {
     return hipMemcpyFromSymbol(host, HIP_SYMBOL(tdc_probe_buf), count * sizeof(unsigned long long)) == hipSuccess ? 0 : -1;
+}
+extern "C" int tdc_debug_clear_probes(void)
+{
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(tdc_probe_buf)) != hipSuccess) return -1;
+    return hipMemset(p, 0, sizeof(tdc_probe_buf)) == hipSuccess ? 0 : -1;
 }
 #else
 #define TDC_PROBE(slot) do { } while (0)
