@@ -56,8 +56,10 @@ typedef enum tdc_status {
     TDC_ERR_ALLOC = -5,           /* device or host allocation failed                         */
     TDC_ERR_HIP = -6,             /* a HIP runtime call or a kernel launch failed             */
     TDC_ERR_BAD_TUNING = -7,      /* a forced tuning does not fit the shape or the hardware   */
-    TDC_ERR_TOO_LARGE = -8        /* tdc_conv_tucker2_static: the layer needs more scratch memory than
+    TDC_ERR_TOO_LARGE = -8,       /* tdc_conv_tucker2_static: the layer needs more scratch memory than
                                      TDC_STATIC_SCRATCH_BYTES                                  */
+    TDC_ERR_NO_CONVERGENCE = -9   /* tdc_hosvd_tucker2 / tdc_admm_project: an eigen-decomposition did not reach
+                                     its tolerance within the sweep limit; outputs are not written             */
 } tdc_status;
 
 /* Layer geometry.  Supported domain: square K in 1..7; stride in 1..4; pad in 0..K-1; any
@@ -127,7 +129,10 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
  * section 5.2 does the same conversion offline).  Later tdc_conv_tucker2 calls that pass
  * these same three pointers use the stored copy; the caller thereby promises not to
  * change the weights in place without calling this again.  Without this call every
- * tdc_conv_tucker2 re-lays the weights out on the stream first (correct, slower). */
+ * tdc_conv_tucker2 re-lays the weights out on the stream first (correct, slower).
+ * The re-layout is enqueued on `hip_stream`; a conv call that uses the stored copy from ANOTHER stream
+ * must be ordered after it by the caller (an event, or a synchronise): the library adds no dependency
+ * between streams. */
 int tdc_plan_pack_weights(tdc_plan *plan, void *hip_stream,
                           const float *U_in, const float *core, const float *U_out);
 
@@ -210,6 +215,18 @@ int tdc_version(void);
  * model tdc_plan_create uses; see tdc_select.cpp for its terms. */
 int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, tdc_tuning *inout);
 
+/* The selector's estimate, opened up for calibration (host only, touches no device).  The estimate of a tuning is a
+ * dot product of fitted coefficients with terms computed from the shape and the tuning; this call returns the terms of
+ * the fully specified tuning *tuning (every field set, as tdc_plan_get_tuning or tdc_select_tuning return it):
+ * terms[0 .. *n_terms), their names (static strings) in names[] when names is not NULL, and in *model (when not NULL)
+ * which coefficient table applies: "fused_latency", "fused_throughput", "chain", "fused_merged" or "stage" (the GEMM
+ * launches of SPLIT, MERGED and DENSE, summed over the launches of one call).  A least-squares fit of measured
+ * latencies against these terms reproduces the tables the library is built with (paper section 5.5 compares its
+ * model with exhaustive search the same way).  TDC_ERR_BAD_TUNING for NAIVE / AUTO, TDC_ERR_BAD_SHAPE if max_terms is
+ * too small (32 is enough). */
+int tdc_model_terms(const tdc_shape *shape, const tdc_tuning *tuning, int compute_units, int lds_bytes,
+                    double *terms, const char **names, int max_terms, int *n_terms, const char **model);
+
 /* Measurement aid: enqueue one empty kernel (a single wavefront that does nothing) on the stream,
  * so that a harness can report the launch floor next to per-layer latencies, which at batch 1
  * are of the same order (the paper, section 6, also notes that launch time of the extra 1x1
@@ -264,7 +281,9 @@ int tdc_select_ranks(const tdc_rank_layer *layers, int n_layers, double budget, 
  * tdc_admm_project: the two auxiliary updates of the ADMM training loop that need only that
  * projection:  K_hat <- proj(K + M)  (the tensor of Tucker ranks (R1, R2), in W's layout) and, in
  * place,  M <- M + K - K_hat.  The K update itself needs the training loss's gradient and is the
- * caller's.  Cost is O(C^3 + N^3 + C*N*K*K*(C + N)) per call, meant to run offline. */
+ * caller's; M is updated with the K_hat that is returned (rounded to fp32), so M_new = fp32(M + K - K_hat) holds for
+ * the values the caller sees.  Cost is O(C^3 + N^3 + C*N*K*K*(C + N)) per call, meant to run offline.  Both return
+ * TDC_ERR_NO_CONVERGENCE, and write nothing, if the Jacobi eigensolver does not reach its tolerance in 100 sweeps. */
 int tdc_hosvd_tucker2(const float *W, int C, int N, int K, int R1, int R2,
                       float *U_in, float *core, float *U_out);
 int tdc_admm_project(const float *K_weights, float *M, int C, int N, int K, int R1, int R2, float *K_hat);

@@ -9,6 +9,7 @@ launchable runs) and compares the best with what the selector's closed-form mode
     python -m paper_2211_03715_amd.autotune --config 2            # table: model pick vs best found
     best = autotune(layer)["best"]["tuning"]                      # a tuning to pass to TuckerConv2d
     python -m paper_2211_03715_amd.autotune --analyse sweep.json  # no GPU: the paper's two-step tile rule on a saved sweep
+    python -m paper_2211_03715_amd.autotune --fit a.json b.json   # no GPU: refit the selector's coefficients to saved sweeps
 
 Stage tunings of the SPLIT and MERGED variants are independent of one another (their kernels run
 back to back), so those are searched one stage at a time around the selector's choice; that is
@@ -147,10 +148,15 @@ def autotune(L: Layer, device: int = 0, iters: int = 200, variants=("fused", "ch
         if r["us"] < by_variant[name]["us"]:
             by_variant[name] = r
     rows.sort(key=lambda r: r["us"])
+    # The selector's pick once more, now that clocks and caches are where they were for the candidates: the first
+    # measurement of a process reads 5-10% high on the longer kernels, which would be booked as the model's error.
+    first, auto = auto, run(None)
+    auto["first_us"] = first["us"]
     if progress:
         progress("%s: auto %.2f us [%s]; best %.2f us [%s]; %d tunings timed" % (
             L.name(), auto["us"], auto["plan"], rows[0]["us"], rows[0]["plan"], len(rows)))
-    return {"layer": L.name(), "auto": auto, "best": rows[0], "by_variant": by_variant, "rows": rows}
+    return {"layer": L.name(), "layout": "nhwc" if layout == B.LAYOUT_NHWC else "nchw", "auto": auto, "best": rows[0],
+            "by_variant": by_variant, "rows": rows}
 
 
 def paper_tile_rule(L: Layer, rows: List[Dict], cus: int = 256, top: float = 0.05) -> Dict:
@@ -219,6 +225,164 @@ def analyse(path: str) -> int:
     return 0
 
 
+COEF_HEADER = __import__("os").path.join(__import__("os").path.dirname(__import__("os").path.abspath(__file__)), "csrc", "tdc_select_coef.h")
+COEF_TABLES = {"fused_latency": "kFusedLatencyCoef", "fused_throughput": "kFusedThroughputCoef", "chain": "kChainCoef",
+               "fused_merged": "kFmCoef", "stage": "kStageCoef"}
+_VARIANT_IDS = {v: k for k, v in B.VARIANT_NAMES.items()}
+_LAYER_RE = __import__("re").compile(r"b(\d+)_c(\d+)_n(\d+)_(\d+)x(\d+)_r(\d+)-(\d+)_k(\d+)_s(\d+)_p(\d+)$")
+
+
+def _layer_from_name(name: str) -> Layer:
+    m = _LAYER_RE.match(name)
+    if not m:
+        raise ValueError("not a layer name: %r" % name)
+    return Layer(*[int(v) for v in m.groups()])
+
+
+def read_coefficients(path: str = COEF_HEADER) -> Dict[str, List[float]]:
+    """The coefficient tables the library is built with, by model name."""
+    import re
+    text = open(path).read()
+    out = {}
+    for model, sym in COEF_TABLES.items():
+        m = re.search(r"%s\[\d+\] = \{([^}]*)\}" % sym, text)
+        out[model] = [float(v) for v in m.group(1).split(",")]
+    return out
+
+
+def sweep_rows(paths: Iterable[str], default_layout: str = "nchw") -> Dict[str, List[Dict]]:
+    """Rows of saved sweeps (--out files) grouped by the coefficient table that prices them: each row gets the layer, the
+    measured latency and the model's terms for its tuning (tdc_model_terms: the one copy of the model, in the library)."""
+    by_model: Dict[str, List[Dict]] = {}
+    for path in paths:
+        with open(path) as f:
+            results = json.load(f)
+        for res in results:
+            L = _layer_from_name(res["layer"])
+            layout = B.LAYOUT_NHWC if res.get("layout", default_layout) == "nhwc" else B.LAYOUT_NCHW
+            shape = B.make_shape(**L.asdict(), layout=layout)
+            for r in res["rows"]:
+                t = r["tuning"]
+                tuning = B.make_tuning(variant=_VARIANT_IDS[t["variant"]], tile_h=t["tile_h"], tile_w=t["tile_w"],
+                                       waves=tuple(t["waves"]), mb=tuple(t["mb"]), pb=tuple(t["pb"]))
+                try:
+                    model, names, terms = B.tdc_model_terms(shape, tuning)
+                except B.TdcError:
+                    continue
+                # CHAIN is only ever chosen where every CU gets two pixel blocks or more; its table is fitted there
+                if model == "chain" and L.batch * L.Ho * L.Wo < 32 * 256:
+                    continue
+                by_model.setdefault(model, []).append({"layer": res["layer"], "layout": res.get("layout", default_layout),
+                                                       "us": r["us"], "terms": terms, "names": names, "plan": r["plan"]})
+    return by_model
+
+
+def fit(paths: Iterable[str], default_layout: str = "nchw", models: Iterable[str] = (), near_best: float = 0.0) -> Dict[str, Dict]:
+    """Non-negative least squares of the measured latencies against the model's terms, in relative error (each row
+    weighted by 1 / latency) times (best latency of its layer / its latency) ** near_best: the model has to rank the
+    fast tunings of a layer right, how wrong it is about the slow ones matters less.  Returns {model: {names, coef, rows, median_err, p90_err, regret: {(layer, layout): ...}}};
+    regret = how far the tuning the fitted model ranks first lies behind the best one timed, per layer."""
+    import numpy as np
+    from scipy.optimize import nnls
+    out = {}
+    for model, rows in sweep_rows(paths, default_layout).items():
+        if models and model not in models:
+            continue
+        X = np.array([r["terms"] for r in rows], dtype=float)
+        y = np.array([r["us"] for r in rows], dtype=float)
+        best_of: Dict = {}
+        for r in rows:
+            key = (r["layer"], r["layout"])
+            best_of[key] = min(best_of.get(key, r["us"]), r["us"])
+        w = np.array([(best_of[(r["layer"], r["layout"])] / r["us"]) ** near_best / r["us"] for r in rows])
+        coef, _ = nnls(X * w[:, None], y * w)
+        pred = X @ coef
+        err = np.abs(pred - y) / y
+        groups: Dict = {}
+        for r, p in zip(rows, pred):
+            groups.setdefault((r["layer"], r["layout"]), []).append((p, r["us"], r["plan"]))
+        regret = {}
+        for key, v in groups.items():
+            best = min(x[1] for x in v)
+            pick = min(v, key=lambda x: x[0])
+            regret[key] = {"best_us": best, "pick_us": pick[1], "pick_plan": pick[2], "regret": pick[1] / best - 1.0, "n": len(v)}
+        out[model] = {"names": rows[0]["names"], "coef": [float(c) for c in coef], "rows": len(rows),
+                      "median_err": float(np.median(err)), "p90_err": float(np.percentile(err, 90)), "regret": regret}
+    return out
+
+
+def evaluate(paths: Iterable[str], coefficients: Dict[str, List[float]], default_layout: str = "nchw") -> Dict:
+    """How a set of coefficient tables ranks the tunings of saved sweeps: per (layer, layout), the measured latency of
+    the tuning with the lowest estimate over ALL models (what AUTO compares) against the best one timed."""
+    import numpy as np
+    groups: Dict = {}
+    for model, rows in sweep_rows(paths, default_layout).items():
+        if model not in coefficients:
+            continue
+        c = np.array(coefficients[model])
+        for r in rows:
+            groups.setdefault((r["layer"], r["layout"]), []).append((float(np.dot(c, r["terms"])), r["us"], r["plan"]))
+    out = {}
+    for key, v in groups.items():
+        best = min(x[1] for x in v)
+        pick = min(v, key=lambda x: x[0])
+        out[key] = {"best_us": best, "pick_us": pick[1], "pick_plan": pick[2], "estimate_us": pick[0], "regret": pick[1] / best - 1.0, "n": len(v)}
+    return out
+
+
+def write_coefficients(fitted: Dict[str, Dict], path: str = COEF_HEADER) -> None:
+    """Replace the tables of the fitted models in the coefficient header; the other tables stay as they are."""
+    import re
+    text = open(path).read()
+    for model, res in fitted.items():
+        sym = COEF_TABLES[model]
+        body = ", ".join("%.4f" % c if c else "0" for c in res["coef"])
+        text, n = re.subn(r"(%s\[\d+\] = \{)[^}]*(\})" % sym, lambda m: m.group(1) + body + m.group(2), text)
+        if n != 1:
+            raise RuntimeError("table %s not found in %s" % (sym, path))
+    with open(path, "w") as f:
+        f.write(text)
+
+
+def fit_main(paths: List[str], default_layout: str, models: List[str], write: bool, held_out: List[str] = (),
+             near_best: float = 0.0) -> int:
+    B.load()
+    fitted = fit(paths, default_layout, models, near_best)
+    current = read_coefficients()
+    for model, res in fitted.items():
+        print("model %s: %d tunings, median relative error %.1f%%, 90th percentile %.1f%%" % (
+            model, res["rows"], 100 * res["median_err"], 100 * res["p90_err"]))
+        print("  %-12s %10s %10s" % ("term", "fitted", "built with"))
+        for n, c, old in zip(res["names"], res["coef"], current[model]):
+            print("  %-12s %10.4f %10.4f" % (n, c, old))
+        regs = [v["regret"] for v in res["regret"].values()]
+        for (layer, layout), v in sorted(res["regret"].items()):
+            print("  %-46s %-4s best %8.2f us  model's first %8.2f us (%4.1f%% behind) of %d" % (
+                layer, layout, v["best_us"], v["pick_us"], 100 * v["regret"], v["n"]))
+        print("  the model's first choice behind the best tuning timed: mean %.1f%%, max %.1f%% over %d layers" % (
+            100 * sum(regs) / len(regs), 100 * max(regs), len(regs)))
+        print("  static const double %s[%d] = {%s};" % (COEF_TABLES[model], len(res["coef"]),
+                                                       ", ".join("%.4f" % c if c else "0" for c in res["coef"])))
+    merged = dict(current)
+    merged.update({m: r["coef"] for m, r in fitted.items()})
+    cases = [("fitted sweeps", paths, "built-in tables", current), ("fitted sweeps", paths, "fitted tables", merged)]
+    if held_out:
+        cases += [("held-out sweeps", held_out, "built-in tables", current), ("held-out sweeps", held_out, "fitted tables", merged)]
+    for which, files, label, table in cases:
+        ev = evaluate(files, table, default_layout)
+        regs = [v["regret"] for v in ev.values()]
+        print("%s, across models, %s: lowest estimate behind the best tuning timed: mean %.1f%%, max %.1f%% over %d layers" % (
+            which, label, 100 * sum(regs) / len(regs), 100 * max(regs), len(regs)))
+        if label == "fitted tables":
+            for (layer, layout), v in sorted(ev.items()):
+                print("  %-46s %-4s best %8.2f  picked %8.2f (%4.1f%%)  %s" % (layer, layout, v["best_us"], v["pick_us"], 100 * v["regret"],
+                                                                            v["pick_plan"].split(" model=")[0]))
+    if write:
+        write_coefficients(fitted)
+        print("wrote %s -- rebuild the library (python -m paper_2211_03715_amd.build)" % COEF_HEADER)
+    return 0
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--config", type=int, nargs="*", default=[2])
@@ -229,7 +393,19 @@ def main(argv=None) -> int:
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"])
     ap.add_argument("--out", default=None, help="JSON with every timed tuning")
     ap.add_argument("--analyse", default=None, metavar="JSON", help="no GPU: the paper's two-step tile rule on a sweep saved with --out")
+    ap.add_argument("--fit", nargs="+", default=None, metavar="JSON",
+                    help="no GPU: refit the selector's coefficients to sweeps saved with --out (the library supplies the "
+                         "model's terms per tuning, tdc_model_terms) and print the tables of csrc/tdc_select_coef.h")
+    ap.add_argument("--models", nargs="*", default=[], help="with --fit: only these coefficient tables "
+                    "(fused_latency fused_throughput chain fused_merged stage)")
+    ap.add_argument("--held-out", nargs="*", default=[], metavar="JSON", help="with --fit: sweeps the fit does not see, "
+                    "ranked with the fitted tables as a check")
+    ap.add_argument("--near-best", type=float, default=0.0, help="with --fit: exponent of (layer's best / row's latency) "
+                    "in a row's weight; 0 weighs every tuning of a layer alike")
+    ap.add_argument("--write-coef", action="store_true", help="with --fit: write the fitted tables into csrc/tdc_select_coef.h")
     args = ap.parse_args(argv)
+    if args.fit:
+        return fit_main(args.fit, args.layout, args.models, args.write_coef, args.held_out, args.near_best)
     if args.analyse:
         B.load()
         return analyse(args.analyse)

@@ -22,6 +22,7 @@ TDC_ERR_ALLOC = -5
 TDC_ERR_HIP = -6
 TDC_ERR_BAD_TUNING = -7
 TDC_ERR_TOO_LARGE = -8
+TDC_ERR_NO_CONVERGENCE = -9
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
@@ -35,7 +36,7 @@ EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", 
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
            "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks",
            "tdc_conv_tucker2_ex", "tdc_conv_dense_ex", "tdc_hosvd_tucker2", "tdc_admm_project",
-           "tdc_conv_tucker2_static"]
+           "tdc_conv_tucker2_static", "tdc_model_terms"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -128,6 +129,9 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_out_size.restype = ip
     lib.tdc_select_tuning.argtypes = [sp, ip, ip, tp]
     lib.tdc_select_tuning.restype = ip
+    lib.tdc_model_terms.argtypes = [sp, tp, ip, ip, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_char_p), ip,
+                                    ctypes.POINTER(ip), ctypes.POINTER(ctypes.c_char_p)]
+    lib.tdc_model_terms.restype = ip
     lib.tdc_launch_null.argtypes = [vp]
     lib.tdc_launch_null.restype = ip
     lib.tdc_select_ranks.argtypes = [ctypes.POINTER(tdc_rank_layer), ip, ctypes.c_double, ctypes.c_double,
@@ -177,6 +181,18 @@ def tdc_select_tuning(shape: tdc_shape, compute_units: int = 256, lds_bytes: int
     if rc != TDC_OK:
         raise TdcError(rc, "tdc_select_tuning")
     return t
+
+
+def tdc_model_terms(shape: tdc_shape, tuning: tdc_tuning, compute_units: int = 256, lds_bytes: int = 160 * 1024):
+    """(model name, term names, terms) of the selector's estimate for a fully specified tuning."""
+    terms = (ctypes.c_double * 32)()
+    names = (ctypes.c_char_p * 32)()
+    n, model = ctypes.c_int(0), ctypes.c_char_p()
+    rc = load().tdc_model_terms(ctypes.byref(shape), ctypes.byref(tuning), compute_units, lds_bytes, terms, names, 32,
+                                ctypes.byref(n), ctypes.byref(model))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_model_terms")
+    return model.value.decode(), [names[i].decode() for i in range(n.value)], [terms[i] for i in range(n.value)]
 
 
 def tdc_plan_create(shape: tdc_shape, device: int = 0, tuning: Optional[tdc_tuning] = None) -> ctypes.c_void_p:

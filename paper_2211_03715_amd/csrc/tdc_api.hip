@@ -237,6 +237,7 @@ const char *tdc_status_string(int status)
         case TDC_ERR_HIP: return "HIP runtime or kernel launch error";
         case TDC_ERR_BAD_TUNING: return "forced tuning does not fit the shape or the device";
         case TDC_ERR_TOO_LARGE: return "layer needs more scratch memory than the static buffer holds";
+        case TDC_ERR_NO_CONVERGENCE: return "eigen-decomposition did not converge within the sweep limit";
         default: return "unknown status";
     }
 }
@@ -373,6 +374,35 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     if (rc == TDC_OK) rc = check_tuning(tmp, dev);
     if (rc == TDC_OK) *inout = tmp.tuning;
     return rc;
+}
+
+int tdc_model_terms(const tdc_shape *shape, const tdc_tuning *tuning, int compute_units, int lds_bytes, double *terms,
+                    const char **names, int max_terms, int *n_terms, const char **model)
+{
+    if (!shape || !tuning || !terms || !n_terms) return TDC_ERR_NULL;
+    int rc = validate(*shape);
+    if (rc != TDC_OK) return rc;
+    if (compute_units < 1 || lds_bytes < 1024) return TDC_ERR_BAD_TUNING;
+    if (tuning->variant <= TDC_VARIANT_NAIVE || tuning->variant > TDC_VARIANT_FUSED_MERGED) return TDC_ERR_BAD_TUNING;
+    const tdc_shape kshape = kernel_shape(*shape, tuning->variant);
+    rc = validate(kshape);
+    if (rc != TDC_OK) return rc;
+    TdcDeviceInfo dev;
+    dev.cus = compute_units;
+    dev.lds_per_wg = lds_bytes;
+    tdc_plan tmp;
+    memset(&tmp, 0, sizeof(tmp));
+    tmp.dims = make_dims(kshape);
+    tmp.tuning = *tuning;
+    if (tuning->variant == TDC_VARIANT_FUSED)
+        tmp.geom = tdc_fused_geometry(tmp.dims, tuning->tile_h, tuning->tile_w, lds_bytes);
+    if (tuning->variant == TDC_VARIANT_CHAIN)
+        tmp.geom = tdc_chain_geometry(tmp.dims, tuning->tile_h, tuning->tile_w, tuning->waves[0], tuning->pb[0], lds_bytes);
+    if (tuning->variant == TDC_VARIANT_FUSED_MERGED)
+        tmp.geom = tdc_fm_geometry(tmp.dims, tuning->tile_h, tuning->tile_w, tuning->waves[0], tuning->mb[1]);
+    rc = check_tuning(tmp, dev);
+    if (rc != TDC_OK) return rc;
+    return tdc_select_terms(tmp.dims, dev, tmp.tuning, terms, names, max_terms, n_terms, model);
 }
 
 int tdc_plan_create(tdc_plan **out, const tdc_shape *shape, int device)

@@ -347,7 +347,9 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.n_sb = (g.QH * a.RPR + 15) / 16;
     a.div_RPR = tdc_make_div((unsigned)a.RPR); a.div_nsb = tdc_make_div((unsigned)a.n_sb);
     const int lay = d.nhwc ? TDC_LAY_NHWC : d.s1_runs ? TDC_LAY_NCHW_RUNS : TDC_LAY_NCHW;
-    a.vec = (g.TW % 4 == 0 && d.Wo % 4 == 0) ? 1 : 0;
+    // 16-byte stores of four consecutive pixels need rows of whole quads and a 16-byte aligned y (a slice of a larger
+    // tensor may not be); otherwise the same values go out as four 4-byte stores
+    a.vec = (g.TW % 4 == 0 && d.Wo % 4 == 0 && ((uintptr_t)y & 15u) == 0) ? 1 : 0;
     a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
     a.div_TW = tdc_make_div((unsigned)g.TW); a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);

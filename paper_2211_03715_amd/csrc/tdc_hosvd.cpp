@@ -22,18 +22,24 @@
 
 namespace {
 
-// A (n x n, symmetric, row-major) -> eigenvalues in w, eigenvectors in the columns of V.
-void jacobi_eigen(std::vector<double> &A, int n, std::vector<double> &w, std::vector<double> &V)
+// A (n x n, symmetric, row-major) -> eigenvalues in w, eigenvectors in the columns of V.  Returns false if the
+// off-diagonal mass is still above the threshold after the last sweep (the basis is then not to be trusted).
+bool jacobi_eigen(std::vector<double> &A, int n, std::vector<double> &w, std::vector<double> &V)
 {
     V.assign((size_t)n * n, 0.0);
     for (int i = 0; i < n; ++i) V[(size_t)i * n + i] = 1.0;
     double diag2 = 0.0;
     for (int i = 0; i < n; ++i) diag2 += A[(size_t)i * n + i] * A[(size_t)i * n + i];
-    for (int sweep = 0; sweep < 100; ++sweep) {
+    bool converged = false;
+    for (int sweep = 0; sweep <= 100; ++sweep) {
         double off2 = 0.0;
         for (int p = 0; p < n; ++p)
             for (int q = p + 1; q < n; ++q) off2 += A[(size_t)p * n + q] * A[(size_t)p * n + q];
-        if (off2 <= 1e-30 * (diag2 + 2.0 * off2) || off2 == 0.0) break;
+        if (off2 <= 1e-30 * (diag2 + 2.0 * off2) || off2 == 0.0) {
+            converged = true;
+            break;
+        }
+        if (sweep == 100) break;           // the check above was the one after the last sweep
         for (int p = 0; p < n - 1; ++p)
             for (int q = p + 1; q < n; ++q) {
                 const double apq = A[(size_t)p * n + q];
@@ -63,11 +69,12 @@ void jacobi_eigen(std::vector<double> &A, int n, std::vector<double> &w, std::ve
     }
     w.resize(n);
     for (int i = 0; i < n; ++i) w[i] = A[(size_t)i * n + i];
+    return converged;
 }
 
 // The `rank` leading left singular vectors of the n x m matrix T (rows = the mode being decomposed),
 // as columns of U (n x rank, row-major).
-void leading_left_singular_vectors(const std::vector<double> &T, int n, size_t m, int rank, std::vector<double> &U)
+bool leading_left_singular_vectors(const std::vector<double> &T, int n, size_t m, int rank, std::vector<double> &U)
 {
     std::vector<double> G((size_t)n * n, 0.0), w, V;
     for (int i = 0; i < n; ++i)
@@ -77,7 +84,7 @@ void leading_left_singular_vectors(const std::vector<double> &T, int n, size_t m
             for (size_t k = 0; k < m; ++k) s += a[k] * b[k];
             G[(size_t)i * n + j] = G[(size_t)j * n + i] = s;
         }
-    jacobi_eigen(G, n, w, V);
+    if (!jacobi_eigen(G, n, w, V)) return false;
     std::vector<int> order(n);
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return w[a] > w[b]; });
@@ -90,18 +97,19 @@ void leading_left_singular_vectors(const std::vector<double> &T, int n, size_t m
         const double sign = V[(size_t)big * n + col] < 0.0 ? -1.0 : 1.0;
         for (int i = 0; i < n; ++i) U[(size_t)i * rank + r] = sign * V[(size_t)i * n + col];
     }
+    return true;
 }
 
-// T (fp64, [C][N][KK]) -> U1 [C][R1], U2 [N][R2], core [R1][R2][KK]
-void hosvd(const std::vector<double> &T, int C, int N, int KK, int R1, int R2, std::vector<double> &U1,
+// T (fp64, [C][N][KK]) -> U1 [C][R1], U2 [N][R2], core [R1][R2][KK]; false if an eigen-decomposition did not converge
+bool hosvd(const std::vector<double> &T, int C, int N, int KK, int R1, int R2, std::vector<double> &U1,
            std::vector<double> &U2, std::vector<double> &core)
 {
-    leading_left_singular_vectors(T, C, (size_t)N * KK, R1, U1);
+    if (!leading_left_singular_vectors(T, C, (size_t)N * KK, R1, U1)) return false;
     std::vector<double> T2((size_t)N * C * KK);                      // mode-2 matricization: [N][C][KK]
     for (int c = 0; c < C; ++c)
         for (int n = 0; n < N; ++n)
             for (int k = 0; k < KK; ++k) T2[((size_t)n * C + c) * KK + k] = T[((size_t)c * N + n) * KK + k];
-    leading_left_singular_vectors(T2, N, (size_t)C * KK, R2, U2);
+    if (!leading_left_singular_vectors(T2, N, (size_t)C * KK, R2, U2)) return false;
     std::vector<double> A((size_t)R1 * N * KK, 0.0);                 // T x_1 U1^T : [R1][N][KK]
     for (int c = 0; c < C; ++c)
         for (int d1 = 0; d1 < R1; ++d1) {
@@ -117,6 +125,7 @@ void hosvd(const std::vector<double> &T, int C, int N, int KK, int R1, int R2, s
                 const double u = U2[(size_t)n * R2 + d2];
                 for (int k = 0; k < KK; ++k) core[((size_t)d1 * R2 + d2) * KK + k] += u * A[((size_t)d1 * N + n) * KK + k];
             }
+    return true;
 }
 
 bool bad_dims(int C, int N, int K, int R1, int R2)
@@ -134,7 +143,7 @@ extern "C" int tdc_hosvd_tucker2(const float *W, int C, int N, int K, int R1, in
     try {
         std::vector<double> T((size_t)C * N * KK), U1, U2, G;
         for (size_t i = 0; i < T.size(); ++i) T[i] = W[i];
-        hosvd(T, C, N, KK, R1, R2, U1, U2, G);
+        if (!hosvd(T, C, N, KK, R1, R2, U1, U2, G)) return TDC_ERR_NO_CONVERGENCE;
         for (size_t i = 0; i < U1.size(); ++i) U_in[i] = (float)U1[i];
         for (size_t i = 0; i < G.size(); ++i) core[i] = (float)G[i];
         for (int n = 0; n < N; ++n)
@@ -153,8 +162,8 @@ extern "C" int tdc_admm_project(const float *Kw, float *M, int C, int N, int K, 
     try {
         std::vector<double> T((size_t)C * N * KK), U1, U2, G;
         for (size_t i = 0; i < T.size(); ++i) T[i] = (double)Kw[i] + (double)M[i];
-        hosvd(T, C, N, KK, R1, R2, U1, U2, G);
-        // K-hat = core x_1 U1 x_2 U2, then M <- M + K - K-hat
+        if (!hosvd(T, C, N, KK, R1, R2, U1, U2, G)) return TDC_ERR_NO_CONVERGENCE;   // K_hat and M untouched
+        // K-hat = core x_1 U1 x_2 U2, then M <- M + K - K-hat with the K-hat the caller receives (rounded to fp32)
         std::vector<double> A((size_t)R1 * N * KK, 0.0);             // core x_2 U2 : [R1][N][KK]
         for (int d1 = 0; d1 < R1; ++d1)
             for (int d2 = 0; d2 < R2; ++d2)
@@ -173,7 +182,7 @@ extern "C" int tdc_admm_project(const float *Kw, float *M, int C, int N, int K, 
             for (size_t k = 0; k < row.size(); ++k) {
                 const size_t i = (size_t)c * N * KK + k;
                 K_hat[i] = (float)row[k];
-                M[i] = (float)((double)M[i] + (double)Kw[i] - row[k]);
+                M[i] = (float)((double)M[i] + (double)Kw[i] - (double)K_hat[i]);
             }
         }
     } catch (const std::bad_alloc &) {

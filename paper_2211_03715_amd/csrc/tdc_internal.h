@@ -141,5 +141,8 @@ struct TdcDeviceInfo {
 };
 // `model_us`, when not null, receives the latency estimate of the chosen tuning (0 for NAIVE)
 int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double *model_us);
+// the terms of the estimate of a fully specified tuning `t` (what tdc_model_terms hands out)
+int tdc_select_terms(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &t, double *terms, const char **names,
+                     int max_terms, int *n_terms, const char **model);
 
 #endif

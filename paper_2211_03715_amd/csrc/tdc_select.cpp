@@ -15,15 +15,17 @@
 // non-negative least squares to exhaustive sweeps on MI355X, separately for the latency regime
 // (batch 1: one-launch and GEMM kernels, ~2500-6600 tunings per model) and the throughput regime
 // (eight batch-1 to batch-64 layers: fused and chain kernels in both activation layouts and both
-// forms of stage 1, ~30000 tunings); median relative errors 5-12%.  Each coefficient struct below
-// says what its terms stand for.
+// forms of stage 1, ~30000 tunings); median relative errors 5-12%.  Each term enumeration below
+// says what its terms stand for; the coefficients live in tdc_select_coef.h.
 #include <algorithm>
 #include <climits>
 #include <cmath>
 
 #include "tdc_internal.h"
+#include "tdc_select_coef.h"
 
 namespace {
+
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
@@ -39,38 +41,25 @@ inline int resident_wgs(const TdcDeviceInfo &dev, size_t lds_bytes, int nw, int 
     return std::max(1, std::min({(int)(dev.lds_per_wg / std::max<size_t>(lds_bytes, 1)), 4 * wps / nw, 8}));
 }
 
-struct FusedCoef {
-    double launch = 3.5583;
-    double s1_unit = 1.2599, s1_kg = 0.0435, s1_mfma = 0.0751;
-    double s2_kg_lds = 0.0186, s2_kg_glb = 0.0356;
-    double s3_unit = 0.3151, s3_kg_lds = 0.0806, s3_kg_glb = 0.0875, s3_mfma = 0.2474;
-    double w_kb = 0.0340;         // per KiB of weights copied into LDS, per co-resident workgroup
-    // throughput regime only: stage-2 MFMAs, MB moved per CU by layout, NCHW row segments per CU (thousands),
-    // and the run-major form of stage 1 (64-pixel units, one 16-byte load per channel and run)
-    double s2_mfma = 0.0;
-    double s1r_unit = 0.0, s1r_kg = 0.0, s1r_mfma = 0.0;
-    double x_mb[3] = {0.0, 0.0, 0.0}, y_mb[2] = {0.0, 0.0};   // x: [NCHW, NHWC, NCHW in runs], y: [NCHW, NHWC]
-    double x_rows = 0.0, y_rows = 0.0;
-    bool by_registers = false;    // residency from the register footprint of the unit (throughput fit) or from wavefront slots
-};
+// Every estimate below is a dot product  sum_i coef[i] * term[i]  of fitted coefficients (microseconds; the tables in
+// tdc_select_coef.h, written by `python -m paper_2211_03715_amd.autotune --fit`) with terms that are computed from the
+// shape and the tuning alone.  tdc_model_terms() hands the terms out, so the fit needs no second copy of the model.
 
-// The same form refitted on ~17500 tunings of eight batch-8 to batch-64 layers (median relative error
-// 9%), the NCHW ones timed with both forms of stage 1: there the bytes a CU moves and, in NCHW, the
-// number of row segments they come in decide between tilings.
-FusedCoef fused_throughput_coef()
-{
-    FusedCoef c;
-    c.launch = 4.1622;
-    c.s1_unit = 0.4289; c.s1_kg = 0.0492; c.s1_mfma = 0.0288;
-    c.s1r_unit = 0.2708; c.s1r_kg = 0.3399; c.s1r_mfma = 0.0028;
-    c.s2_kg_lds = 0.0402; c.s2_kg_glb = 0.0992; c.s2_mfma = 0.0229;
-    c.s3_unit = 0.2002; c.s3_kg_lds = 0.0733; c.s3_kg_glb = 0.0; c.s3_mfma = 0.1458;
-    c.w_kb = 0.0222;
-    c.x_mb[0] = 12.4128; c.x_mb[1] = 6.1156; c.x_mb[2] = 6.5838; c.y_mb[0] = 60.5491; c.y_mb[1] = 29.7202;
-    c.x_rows = 0.4209; c.y_rows = 2.5605;
-    c.by_registers = true;
-    return c;
-}
+// FUSED.  Terms, all per workgroup round over the chip except the first:
+enum {
+    F_LAUNCH, F_S1_UNIT, F_S1_KG, F_S1_MFMA,       // constant; stage 1 per register tile, per k-group, per MFMA quad x pipe share
+    F_S1R_UNIT, F_S1R_KG, F_S1R_MFMA,              // the same for the run-major form of stage 1 (64-pixel units)
+    F_S2_KG_LDS, F_S2_KG_GLB, F_S2_MFMA,           // stage 2 per k-group with weights in LDS / streamed, per MFMA quad
+    F_S3_UNIT, F_S3_KG_LDS, F_S3_KG_GLB, F_S3_MFMA,
+    F_W_KB,                                        // KiB of weights copied into LDS, per co-resident workgroup
+    F_X_MB_NCHW, F_X_MB_NHWC, F_X_MB_RUNS,         // MB of x a CU pulls, by the way it is read
+    F_Y_MB_NCHW, F_Y_MB_NHWC,                      // MB of y a CU pushes
+    F_X_ROWS, F_Y_ROWS,                            // NCHW: thousands of row segments a CU reads (4-byte loads only) / writes
+    F_TERMS
+};
+const char *const kFusedTermNames[F_TERMS] = {"launch", "s1_unit", "s1_kg", "s1_mfma", "s1r_unit", "s1r_kg", "s1r_mfma",
+                                              "s2_kg_lds", "s2_kg_glb", "s2_mfma", "s3_unit", "s3_kg_lds", "s3_kg_glb", "s3_mfma",
+                                              "w_kb", "x_mb_nchw", "x_mb_nhwc", "x_mb_runs", "y_mb_nchw", "y_mb_nhwc", "x_rows", "y_rows"};
 
 // One GEMM launch of SPLIT, MERGED or DENSE.  Fitted to ~2500 stage tunings of the batch-1 layers
 // (median relative error 5%, the picked tuning within 10% of the best one timed): a launch
@@ -79,15 +68,8 @@ FusedCoef fused_throughput_coef()
 // re-read by every output-channel group, which is what makes taller register tiles (mb > 1) pay
 // once there are many channel blocks -- charged as k-group loads per CU over the whole launch,
 // more per load for a strided gather.
-struct StageCoef {
-    double launch = 2.15;
-    double wave = 0.05;           // per wavefront of the workgroup (dispatch, partial-sum traffic)
-    double kg = 0.0649, mfma = 0.0785;
-    double conv_b = 0.0255;       // K x K stage: per k-group and pixel block of the register tile
-    double reduce = 0.3158;       // cross-wavefront sum through LDS, per 16x16 block of the tile
-    double act_1x1 = 0.0653;      // per activation k-group load per CU, 1x1 stages
-    double act_conv = 0.0246;     // same for the K x K stage, times its stride
-};
+enum { G_LAUNCH, G_WAVE, G_KG, G_MFMA, G_CONV_B, G_REDUCE, G_ACT_1X1, G_ACT_CONV, G_TERMS };
+const char *const kStageTermNames[G_TERMS] = {"launch", "wave", "kg", "mfma", "conv_b", "reduce", "act_1x1", "act_conv"};
 
 const int kMb[3] = {1, 2, 4};
 
@@ -104,8 +86,16 @@ Stage1Work stage1_work(const TdcDims &d, const TdcFusedGeom &g, bool runs, int n
     return {cdiv(cdiv(g.QH * rpr, 16) * (d.NB1 / mb1), nw), 4 * mb1, g.QH * rpr * 16.0 * d.C * 1e-6};
 }
 
-double fused_us(const FusedCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, bool runs, int nw,
-                int mb1, int mb2, int mb3, int pb)
+inline double dot(const double *coef, const double *terms, int n)
+{
+    double t = 0.0;
+    for (int i = 0; i < n; ++i) t += coef[i] * terms[i];
+    return t;
+}
+
+// `by_registers`: residency from the register footprint of the unit (throughput fit) or from the wavefront slots
+void fused_terms(double (&f)[F_TERMS], bool by_registers, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g,
+                 bool runs, int nw, int mb1, int mb2, int mb3, int pb)
 {
     const int KG2 = d.K * d.K * d.NB1, KG3 = d.NB2;
     const Stage1Work s1 = stage1_work(d, g, runs, nw, mb1, pb);
@@ -113,21 +103,38 @@ double fused_us(const FusedCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, 
     const int r3 = cdiv(cdiv(g.PBk, pb) * (d.NB3 / mb3), nw);
     const long wgs = (long)g.tiles_x * g.tiles_y * d.B;
     // register tiles of 1, 2, 4+ blocks leave room for 4, 3, 2 wavefronts per SIMD (kernel resource usage of the instances)
-    const int unit = mb1 * pb, wps = !c.by_registers ? kWavesPerCu / 4 : unit == 1 ? 4 : unit == 2 ? 3 : 2;
+    const int unit = mb1 * pb, wps = !by_registers ? kWavesPerCu / 4 : unit == 1 ? 4 : unit == 2 ? 3 : 2;
     const int resident = resident_wgs(dev, g.lds_bytes, nw, wps);
     const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
     const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
     const double share = std::max(1.0, per_cu * nw / 4.0);
     const bool wl = g.weights_in_lds;
     const double w_kb = wl ? (double)(d.NB2 * KG2 + d.NB3 * KG3) : 0.0;
-    double t = runs ? s1.rounds * (c.s1r_unit + d.KG1 * (c.s1r_kg + c.s1r_mfma * s1.quads * share))
-                    : s1.rounds * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * s1.quads * share));
-    t += r2 * KG2 * ((wl ? c.s2_kg_lds : c.s2_kg_glb) + c.s2_mfma * mb2 * pb * share);
-    t += r3 * (c.s3_unit + KG3 * ((wl ? c.s3_kg_lds : c.s3_kg_glb) + c.s3_mfma * mb3 * pb * share));
-    t += c.w_kb * w_kb * per_cu;
-    t += per_cu * (c.x_mb[d.nhwc ? 1 : runs ? 2 : 0] * s1.x_mb + c.y_mb[d.nhwc ? 1 : 0] * g.PBk * 16.0 * d.N * 4e-6);
-    if (!d.nhwc) t += per_cu * ((runs ? 0.0 : c.x_rows) * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
-    return c.launch + rounds * t;
+    for (double &v : f) v = 0.0;
+    f[F_LAUNCH] = 1.0;
+    f[runs ? F_S1R_UNIT : F_S1_UNIT] = rounds * s1.rounds;
+    f[runs ? F_S1R_KG : F_S1_KG] = rounds * s1.rounds * d.KG1;
+    f[runs ? F_S1R_MFMA : F_S1_MFMA] = rounds * s1.rounds * d.KG1 * s1.quads * share;
+    f[wl ? F_S2_KG_LDS : F_S2_KG_GLB] = rounds * r2 * KG2;
+    f[F_S2_MFMA] = rounds * r2 * KG2 * mb2 * pb * share;
+    f[F_S3_UNIT] = rounds * r3;
+    f[wl ? F_S3_KG_LDS : F_S3_KG_GLB] = rounds * r3 * KG3;
+    f[F_S3_MFMA] = rounds * r3 * KG3 * mb3 * pb * share;
+    f[F_W_KB] = rounds * w_kb * per_cu;
+    f[d.nhwc ? F_X_MB_NHWC : runs ? F_X_MB_RUNS : F_X_MB_NCHW] = rounds * per_cu * s1.x_mb;
+    f[d.nhwc ? F_Y_MB_NHWC : F_Y_MB_NCHW] = rounds * per_cu * g.PBk * 16.0 * d.N * 4e-6;
+    if (!d.nhwc) {
+        if (!runs) f[F_X_ROWS] = rounds * per_cu * g.QH * d.C * 1e-3;
+        f[F_Y_ROWS] = rounds * per_cu * g.TH * d.N * 1e-3;
+    }
+}
+
+double fused_us(bool throughput, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, bool runs, int nw,
+                int mb1, int mb2, int mb3, int pb)
+{
+    double f[F_TERMS];
+    fused_terms(f, throughput, d, dev, g, runs, nw, mb1, mb2, mb3, pb);
+    return dot(throughput ? kFusedThroughputCoef : kFusedLatencyCoef, f, F_TERMS);
 }
 
 struct FusedChoice {
@@ -138,7 +145,6 @@ struct FusedChoice {
 FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &forced)
 {
     const bool throughput = (long)d.B * d.Ho * d.Wo >= 16L * dev.cus;
-    const FusedCoef c = throughput ? fused_throughput_coef() : FusedCoef();
     const bool runs = tdc_runs_apply(d, dev.cus);
     FusedChoice best;
     const int th_lo = forced.tile_h ? forced.tile_h : 1, th_hi = forced.tile_h ? forced.tile_h : std::min(d.Ho, 16);
@@ -161,7 +167,7 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
                                 if (forced.pb[0] && pb != forced.pb[0]) continue;
                                 if (d.NB1 % mb1 || d.NB2 % mb2 || d.NB3 % mb3) continue;   // whole register tiles only
                                 if (!tdc_fused_unit_supported(mb1, mb2, mb3, pb)) continue;
-                                const double us = fused_us(c, d, dev, g, runs, nw, mb1, mb2, mb3, pb);
+                                const double us = fused_us(throughput, d, dev, g, runs, nw, mb1, mb2, mb3, pb);
                                 if (us < best.us) {
                                     best.us = us;
                                     best.th = th; best.tw = tw; best.nw = nw;
@@ -180,21 +186,20 @@ FusedChoice best_fused(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 // width is not a multiple of 4, and, in NCHW, the number of row segments a CU reads and writes
 // (tiles that span whole image rows move longer runs).  Fitted to ~12600 tunings of eight batch-8 to
 // batch-64 layers, the NCHW ones timed with both forms of stage 1 (median relative error 9%).
-struct ChainCoef {
-    double launch = 3.6918;
-    double s1_unit = 0.5859, s1_kg = 0.0211, s1_mfma = 0.0906;
-    double s1r_unit = 0.2783, s1r_kg = 0.3798, s1r_mfma = 0.0096;   // run-major stage 1
-    double kg2_lds = 0.0298, kg2_glb = 0.2335, blk2 = 0.0141;
-    double nb3_lds = 0.2690, blk3 = 0.0402;
-    double w_kb = 0.0235;
-    double x_mb[3] = {6.4658, 0.0, 15.9944}; // per MB per CU, [NCHW, NHWC, NCHW in runs]
-    double y_mb = 32.4026;
-    double x_rows = 0.2683, y_rows = 2.9056; // NCHW: per 1000 row segments (tile rows x channels) per CU, in (4-byte loads only) and out
-    double novec = 0.1707;                   // per output-channel block and pixel block stored with 4-byte stores
+enum {
+    C_LAUNCH, C_S1_UNIT, C_S1_KG, C_S1_MFMA, C_S1R_UNIT, C_S1R_KG, C_S1R_MFMA,
+    C_KG2_LDS, C_KG2_GLB, C_BLK2,                  // stage 2 per k-group (weights in LDS / streamed), per MFMA quad x pipe share
+    C_NB3_LDS, C_BLK3,                             // stage 3 per output block with weights in LDS, per MFMA quad
+    C_W_KB, C_X_MB_NCHW, C_X_MB_NHWC, C_X_MB_RUNS, C_Y_MB, C_X_ROWS, C_Y_ROWS,
+    C_NOVEC,                                       // per output-channel block and pixel block stored with 4-byte stores
+    C_TERMS
 };
+const char *const kChainTermNames[C_TERMS] = {"launch", "s1_unit", "s1_kg", "s1_mfma", "s1r_unit", "s1r_kg", "s1r_mfma",
+                                              "kg2_lds", "kg2_glb", "blk2", "nb3_lds", "blk3", "w_kb", "x_mb_nchw", "x_mb_nhwc",
+                                              "x_mb_runs", "y_mb", "x_rows", "y_rows", "novec"};
 
-double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, bool runs, int nw,
-                int mb1, int pb, int *cu_waves)
+void chain_terms(double (&f)[C_TERMS], const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, bool runs, int nw,
+                 int mb1, int pb, int *cu_waves)
 {
     const int KG2 = d.K * d.K * d.NB1;
     const Stage1Work s1 = stage1_work(d, g, runs, nw, mb1, pb);
@@ -213,19 +218,34 @@ double chain_us(const ChainCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, 
     const double share = std::max(1.0, per_cu * nw / 4.0);
     const double w_kb = wl ? (double)(d.NB2 * KG2 + d.NB3 * d.NB2) : 0.0;
     const bool vec = d.nhwc || (g.TW % 4 == 0 && d.Wo % 4 == 0);
-    double t = runs ? s1.rounds * (c.s1r_unit + d.KG1 * (c.s1r_kg + c.s1r_mfma * s1.quads * share))
-                    : s1.rounds * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * s1.quads * share));
-    t += r23 * (KG2 * ((wl ? c.kg2_lds : c.kg2_glb) + c.blk2 * d.NB2 * pb * share) +
-                d.NB3 * ((wl ? c.nb3_lds : 0.0) + c.blk3 * d.NB2 * pb * share + (vec ? 0.0 : c.novec * pb)));
-    t += c.w_kb * w_kb * per_cu;
-    t += per_cu * (c.x_mb[d.nhwc ? 1 : runs ? 2 : 0] * s1.x_mb + c.y_mb * g.PBk * 16.0 * d.N * 4e-6);
-    if (!d.nhwc) t += per_cu * ((runs ? 0.0 : c.x_rows) * g.QH * d.C * 1e-3 + c.y_rows * g.TH * d.N * 1e-3);
-    return c.launch + rounds * t;
+    for (double &v : f) v = 0.0;
+    f[C_LAUNCH] = 1.0;
+    f[runs ? C_S1R_UNIT : C_S1_UNIT] = rounds * s1.rounds;
+    f[runs ? C_S1R_KG : C_S1_KG] = rounds * s1.rounds * d.KG1;
+    f[runs ? C_S1R_MFMA : C_S1_MFMA] = rounds * s1.rounds * d.KG1 * s1.quads * share;
+    f[wl ? C_KG2_LDS : C_KG2_GLB] = rounds * r23 * KG2;
+    f[C_BLK2] = rounds * r23 * KG2 * d.NB2 * pb * share;
+    if (wl) f[C_NB3_LDS] = rounds * r23 * d.NB3;
+    f[C_BLK3] = rounds * r23 * d.NB3 * d.NB2 * pb * share;
+    if (!vec) f[C_NOVEC] = rounds * r23 * d.NB3 * pb;
+    f[C_W_KB] = rounds * w_kb * per_cu;
+    f[d.nhwc ? C_X_MB_NHWC : runs ? C_X_MB_RUNS : C_X_MB_NCHW] = rounds * per_cu * s1.x_mb;
+    f[C_Y_MB] = rounds * per_cu * g.PBk * 16.0 * d.N * 4e-6;
+    if (!d.nhwc) {
+        if (!runs) f[C_X_ROWS] = rounds * per_cu * g.QH * d.C * 1e-3;
+        f[C_Y_ROWS] = rounds * per_cu * g.TH * d.N * 1e-3;
+    }
+}
+
+double chain_us(const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, bool runs, int nw, int mb1, int pb, int *cu_waves)
+{
+    double f[C_TERMS];
+    chain_terms(f, d, dev, g, runs, nw, mb1, pb, cu_waves);
+    return dot(kChainCoef, f, C_TERMS);
 }
 
 FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &forced)
 {
-    const ChainCoef c;
     const bool runs = tdc_runs_apply(d, dev.cus);
     FusedChoice best;
     int best_cu_waves = 0;
@@ -252,7 +272,7 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
                         if (forced.mb[0] && mb1 != forced.mb[0]) continue;
                         if (d.NB1 % mb1 || !tdc_chain_supported(d.NB2, mb1, pb)) continue;
                         int cu_waves = 0;
-                        const double us = chain_us(c, d, dev, g, runs, nw, mb1, pb, &cu_waves);
+                        const double us = chain_us(d, dev, g, runs, nw, mb1, pb, &cu_waves);
                         const bool tie = std::fabs(us - best.us) <= 1e-9 * us;
                         const long x_pixels = (long)g.tiles_x * g.tiles_y * g.Q;      // input pixels read per image, halos included
                         if ((!tie && us < best.us) || (tie && cu_waves > best_cu_waves) ||
@@ -278,14 +298,8 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
 // pulls (input tile with halo, once per workgroup; dearer in NCHW, where they arrive as 4-byte
 // loads), and a dispatch term per 256 workgroups -- the recomputation of stage 1 by every
 // output-channel group shows up there and in the x bytes.
-struct FmCoef {
-    double launch = 2.5879;
-    double s1_unit = 0.2174, s1_kg = 0.0197, s1_mfma = 0.0407;
-    double frag = 0.0803;         // per weight fragment and pixel block, times the MFMA pipe share
-    double reduce = 0.4477;       // per pixel block when the contraction is sliced
-    double x_mb[2] = {38.3935, 16.4747};   // per MB of x per CU, [NCHW, NHWC]
-    double wgs = 0.5418;          // per 256 workgroups
-};
+enum { M_LAUNCH, M_S1_UNIT, M_S1_KG, M_S1_MFMA, M_FRAG, M_REDUCE, M_X_MB_NCHW, M_X_MB_NHWC, M_WGS, M_TERMS };
+const char *const kFmTermNames[M_TERMS] = {"launch", "s1_unit", "s1_kg", "s1_mfma", "frag", "reduce", "x_mb_nchw", "x_mb_nhwc", "wgs"};
 
 struct FmChoice {
     double us = 1e300;
@@ -293,7 +307,7 @@ struct FmChoice {
     int th = 0, tw = 0, nw = 0, mb1 = 0, nbg = 0;
 };
 
-double fm_us(const FmCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw, int mb1, int nbg)
+void fm_terms(double (&f)[M_TERMS], const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw, int mb1, int nbg)
 {
     const int KG2 = d.K * d.K * d.NB1, ks = nw / nbg;
     const long wgs = (long)g.tiles_x * g.tiles_y * (d.NB3 / nbg) * d.B;
@@ -303,15 +317,26 @@ double fm_us(const FmCoef &c, const TdcDims &d, const TdcDeviceInfo &dev, const 
     const double share = std::max(1.0, per_cu * nw / 4.0);
     const int r1 = cdiv(g.QB * (d.NB1 / mb1), nw);
     const int frags = cdiv(KG2, ks);
-    double t = r1 * (c.s1_unit + d.KG1 * (c.s1_kg + c.s1_mfma * mb1 * share));
-    t += g.PBk * frags * c.frag * share + (ks > 1 ? c.reduce * g.PBk : 0.0);
-    t += per_cu * c.x_mb[d.nhwc ? 1 : 0] * g.QB * 16.0 * d.C * 4e-6;
-    return c.launch + rounds * t + c.wgs * wgs / 256.0;
+    for (double &v : f) v = 0.0;
+    f[M_LAUNCH] = 1.0;
+    f[M_S1_UNIT] = rounds * r1;
+    f[M_S1_KG] = rounds * r1 * d.KG1;
+    f[M_S1_MFMA] = rounds * r1 * d.KG1 * mb1 * share;
+    f[M_FRAG] = rounds * g.PBk * frags * share;
+    if (ks > 1) f[M_REDUCE] = rounds * g.PBk;
+    f[d.nhwc ? M_X_MB_NHWC : M_X_MB_NCHW] = rounds * per_cu * g.QB * 16.0 * d.C * 4e-6;
+    f[M_WGS] = wgs / 256.0;
+}
+
+double fm_us(const TdcDims &d, const TdcDeviceInfo &dev, const TdcFusedGeom &g, int nw, int mb1, int nbg)
+{
+    double f[M_TERMS];
+    fm_terms(f, d, dev, g, nw, mb1, nbg);
+    return dot(kFmCoef, f, M_TERMS);
 }
 
 FmChoice best_fm(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &forced)
 {
-    const FmCoef c;
     FmChoice best;
     const int ks_min = cdiv(d.K * d.K * d.NB1, 9);   // a wavefront holds nine weight fragments
     const int th_lo = forced.tile_h ? forced.tile_h : 1, th_hi = forced.tile_h ? forced.tile_h : std::min(d.Ho, 8);
@@ -336,7 +361,7 @@ FmChoice best_fm(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &f
                         if (pass == 0 && !forced.waves[0] && !forced.mb[1] && ks != ks_min && ks != 2 * ks_min) continue;
                         const TdcFusedGeom g = tdc_fm_geometry(d, th, tw, nw, nbg);
                         if ((long)g.lds_bytes > dev.lds_per_wg) continue;
-                        const double us = fm_us(c, d, dev, g, nw, mb1, nbg);
+                        const double us = fm_us(d, dev, g, nw, mb1, nbg);
                         if (us < best.us) {
                             best.us = us;
                             best.th = th; best.tw = tw; best.nw = nw; best.mb1 = mb1; best.nbg = nbg;
@@ -354,10 +379,31 @@ struct StageChoice {
 
 // one GEMM launch: n_mblocks x n_pblocks output blocks per image, `kgroups` k-groups;
 // conv_stride = 0 for a 1x1 stage, the stride for the K x K stage
+void stage_terms(double (&f)[G_TERMS], const TdcDeviceInfo &dev, int batch, int n_mblocks, int n_pblocks, int kgroups, int mb, int pb,
+                 int nw, int conv_stride)
+{
+    const long wgs = (long)(n_mblocks / mb) * cdiv(n_pblocks, pb) * batch;
+    const int resident = std::max(1, std::min(kWavesPerCu / nw, 8));
+    const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
+    const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
+    const double share = std::max(1.0, per_cu * nw / 4.0);
+    const int kgw = cdiv(kgroups, nw);
+    const double act_loads = (double)batch * (n_mblocks / mb) * n_pblocks * kgroups / dev.cus;
+    for (double &v : f) v = 0.0;
+    f[G_LAUNCH] = 1.0;
+    f[G_WAVE] = rounds * nw;
+    f[G_KG] = rounds * kgw;
+    f[G_MFMA] = rounds * kgw * mb * pb * share;
+    if (conv_stride) f[G_CONV_B] = rounds * kgw * pb;
+    if (nw > 1) f[G_REDUCE] = rounds * mb * pb;
+    f[conv_stride ? G_ACT_CONV : G_ACT_1X1] = act_loads * (conv_stride ? conv_stride : 1);
+}
+
+// one GEMM launch: n_mblocks x n_pblocks output blocks per image, `kgroups` k-groups;
+// conv_stride = 0 for a 1x1 stage, the stride for the K x K stage
 StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n_pblocks, int kgroups, int fmb,
                        int fpb, int fnw, int conv_stride)
 {
-    const StageCoef c;
     StageChoice best;
     for (int mb : kMb)
         for (int pb : kMb)
@@ -368,17 +414,9 @@ StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n
                 if (n_mblocks % mb) continue;         // whole register tiles only
                 if (!fnw && nw > kgroups) continue;   // idle wavefronts are legal, just never chosen
                 if ((size_t)nw * mb * pb * 1024 > 64 * 1024 && nw > 1) continue;
-                const long wgs = (long)(n_mblocks / mb) * cdiv(n_pblocks, pb) * batch;
-                const int resident = std::max(1, std::min(kWavesPerCu / nw, 8));
-                const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
-                const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
-                const double share = std::max(1.0, per_cu * nw / 4.0);
-                const int kgw = cdiv(kgroups, nw);
-                const double act_loads = (double)batch * (n_mblocks / mb) * n_pblocks * kgroups / dev.cus;
-                const double us = c.launch +
-                                  rounds * (kgw * (c.kg + c.mfma * mb * pb * share + (conv_stride ? c.conv_b * pb : 0.0)) +
-                                            (nw > 1 ? c.reduce * mb * pb : 0.0) + c.wave * nw) +
-                                  act_loads * (conv_stride ? c.act_conv * conv_stride : c.act_1x1);
+                double f[G_TERMS];
+                stage_terms(f, dev, batch, n_mblocks, n_pblocks, kgroups, mb, pb, nw, conv_stride);
+                const double us = dot(kStageCoef, f, G_TERMS);
                 if (us < best.us) {
                     best.us = us;
                     best.mb = mb; best.pb = pb; best.nw = nw;
@@ -388,6 +426,65 @@ StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n
 }
 
 }  // namespace
+
+// The terms of the estimate for a fully specified tuning (see tdc_model_terms in tdc.h).
+int tdc_select_terms(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tuning &t, double *terms, const char **names,
+                     int max_terms, int *n_terms, const char **model)
+{
+    const bool runs = tdc_runs_apply(d, dev.cus);
+    const auto emit = [&](const double *f, const char *const *nm, int n, const char *which) {
+        if (n > max_terms) return (int)TDC_ERR_BAD_SHAPE;
+        for (int i = 0; i < n; ++i) {
+            terms[i] = f[i];
+            if (names) names[i] = nm[i];
+        }
+        *n_terms = n;
+        if (model) *model = which;
+        return (int)TDC_OK;
+    };
+    if (t.variant == TDC_VARIANT_FUSED) {
+        const bool throughput = (long)d.B * d.Ho * d.Wo >= 16L * dev.cus;
+        const TdcFusedGeom g = tdc_fused_geometry(d, t.tile_h, t.tile_w, dev.lds_per_wg);
+        double f[F_TERMS];
+        fused_terms(f, throughput, d, dev, g, runs, t.waves[0], t.mb[0], t.mb[1], t.mb[2], t.pb[0]);
+        return emit(f, kFusedTermNames, F_TERMS, throughput ? "fused_throughput" : "fused_latency");
+    }
+    if (t.variant == TDC_VARIANT_CHAIN) {
+        const TdcFusedGeom g = tdc_chain_geometry(d, t.tile_h, t.tile_w, t.waves[0], t.pb[0], dev.lds_per_wg);
+        double f[C_TERMS];
+        int cu_waves = 0;
+        chain_terms(f, d, dev, g, runs, t.waves[0], t.mb[0], t.pb[0], &cu_waves);
+        return emit(f, kChainTermNames, C_TERMS, "chain");
+    }
+    if (t.variant == TDC_VARIANT_FUSED_MERGED) {
+        const TdcFusedGeom g = tdc_fm_geometry(d, t.tile_h, t.tile_w, t.waves[0], t.mb[1]);
+        double f[M_TERMS];
+        fm_terms(f, d, dev, g, t.waves[0], t.mb[0], t.mb[1]);
+        return emit(f, kFmTermNames, M_TERMS, "fused_merged");
+    }
+    if (t.variant == TDC_VARIANT_SPLIT || t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_DENSE) {
+        // the launches of a call share one set of coefficients, so their terms add up
+        const int pb_in = cdiv(d.H * d.W, 16), pb_out = cdiv(d.Ho * d.Wo, 16), KG2 = d.K * d.K * d.NB1;
+        double f[G_TERMS], sum[G_TERMS] = {0};
+        const auto add = [&](int n_mblocks, int n_pblocks, int kgroups, int st, int conv_stride) {
+            stage_terms(f, dev, d.B, n_mblocks, n_pblocks, kgroups, t.mb[st], t.pb[st], t.waves[st], conv_stride);
+            for (int i = 0; i < G_TERMS; ++i) sum[i] += f[i];
+        };
+        if (t.variant == TDC_VARIANT_DENSE) {
+            add(d.NB2, pb_out, KG2, 1, d.stride);
+        } else {
+            add(d.NB1, pb_in, d.KG1, 0, 0);
+            if (t.variant == TDC_VARIANT_MERGED) {
+                add(d.NB3, pb_out, KG2, 1, d.stride);
+            } else {
+                add(d.NB2, pb_out, KG2, 1, d.stride);
+                add(d.NB3, pb_out, d.NB2, 2, 0);
+            }
+        }
+        return emit(sum, kStageTermNames, G_TERMS, "stage");
+    }
+    return TDC_ERR_BAD_TUNING;
+}
 
 int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double *model_us)
 {
@@ -442,7 +539,11 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     if (forced.variant == TDC_VARIANT_AUTO || forced.variant == TDC_VARIANT_FUSED) f = best_fused(d, dev, forced);
     // output pixels alone give every CU a 16-pixel block: the throughput regime
     const bool pixels_fill_chip = (long)d.B * d.Ho * d.Wo >= 16L * dev.cus;
-    if (forced.variant == TDC_VARIANT_AUTO && pixels_fill_chip) {
+    // CHAIN keeps whole pixel blocks per wavefront and needs two 16-pixel blocks per CU to pay: below that FUSED,
+    // which cuts the same tile along channels as well, won every sweep (batch 8 at 28x28, batch 32 at 14x14),
+    // by 5-80%, while the two estimates are too close there to tell.
+    const bool chain_pays = (long)d.B * d.Ho * d.Wo >= 32L * dev.cus;
+    if (forced.variant == TDC_VARIANT_AUTO && chain_pays) {
         tdc_tuning free_choice = forced;
         const FusedChoice c = best_chain(d, dev, free_choice);
         if (c.us < f.us) {

@@ -1,0 +1,19 @@
+// Fitted coefficients of the selector's latency estimates (microseconds per term), in the order of the term
+// enumerations of tdc_select.cpp.  Written by
+//     python -m paper_2211_03715_amd.autotune --fit <sweeps.json ...> --write-coef
+// from exhaustive sweeps timed on MI355X (`--out` of the same module); do not edit by hand.
+#ifndef TDC_SELECT_COEF_H
+#define TDC_SELECT_COEF_H
+
+// fused, latency regime: launch s1_unit s1_kg s1_mfma s1r_unit s1r_kg s1r_mfma s2_kg_lds s2_kg_glb s2_mfma s3_unit s3_kg_lds s3_kg_glb s3_mfma w_kb x_mb_nchw x_mb_nhwc x_mb_runs y_mb_nchw y_mb_nhwc x_rows y_rows
+static const double kFusedLatencyCoef[22] = {3.5583, 1.2599, 0.0435, 0.0751, 0, 0, 0, 0.0186, 0.0356, 0, 0.3151, 0.0806, 0.0875, 0.2474, 0.0340, 0, 0, 0, 0, 0, 0, 0};
+// fused, throughput regime: same terms
+static const double kFusedThroughputCoef[22] = {4.1622, 0.4289, 0.0492, 0.0288, 0.2708, 0.3399, 0.0028, 0.0402, 0.0992, 0.0229, 0.2002, 0.0733, 0, 0.1458, 0.0222, 12.4128, 6.1156, 6.5838, 60.5491, 29.7202, 0.4209, 2.5605};
+// chain: launch s1_unit s1_kg s1_mfma s1r_unit s1r_kg s1r_mfma kg2_lds kg2_glb blk2 nb3_lds blk3 w_kb x_mb_nchw x_mb_nhwc x_mb_runs y_mb x_rows y_rows novec
+static const double kChainCoef[20] = {3.6918, 0.5859, 0.0211, 0.0906, 0.2783, 0.3798, 0.0096, 0.0298, 0.2335, 0.0141, 0.2690, 0.0402, 0.0235, 6.4658, 0, 15.9944, 32.4026, 0.2683, 2.9056, 0.1707};
+// fused-merged: launch s1_unit s1_kg s1_mfma frag reduce x_mb_nchw x_mb_nhwc wgs
+static const double kFmCoef[9] = {2.5879, 0.2174, 0.0197, 0.0407, 0.0803, 0.4477, 38.3935, 16.4747, 0.5418};
+// one GEMM launch (split, merged, dense): launch wave kg mfma conv_b reduce act_1x1 act_conv
+static const double kStageCoef[8] = {2.15, 0.05, 0.0649, 0.0785, 0.0255, 0.3158, 0.0653, 0.0246};
+
+#endif

@@ -10,6 +10,32 @@ from typing import Optional
 from . import binding as B
 
 
+def _torch_stream(stream):
+    """torch's stream object for None (the current stream), a raw stream handle, or a torch stream."""
+    import torch
+    if stream is None:
+        return torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return torch.cuda.ExternalStream(stream) if stream else torch.cuda.default_stream()
+    return stream
+
+
+def _order_after(conv, stream) -> None:
+    """Make `stream` wait for conv's weight re-layout if that ran on another stream and may still be in flight.
+    Nothing is enqueued on a stream that is being captured: finish the re-layout before capturing."""
+    import torch
+    ev = getattr(conv, "_pack_event", None)
+    if ev is None or torch.cuda.is_current_stream_capturing():
+        return
+    if ev.query():                       # the re-layout is complete: no stream needs to wait any more
+        conv._pack_event = None
+        return
+    ts = _torch_stream(stream)
+    if ts.cuda_stream not in conv._ordered:
+        ts.wait_event(ev)
+        conv._ordered.add(ts.cuda_stream)
+
+
 class TuckerConv2d:
     """One Tucker-2 convolution layer (paper section 3, Eqs. 2-4) bound to a device plan."""
 
@@ -39,14 +65,24 @@ class TuckerConv2d:
         return B.tdc_plan_kernel_count(self.plan)
 
     def pack(self, U_in, core, U_out, stream=None) -> None:
-        """Re-lay the weights out once; the tensors must stay alive and unchanged."""
+        """Re-lay the weights out once; the tensors must stay alive and unchanged.
+
+        The re-layout runs on ``stream`` (default: the current stream).  The library orders nothing between streams,
+        so a later call or bind() on another stream is made to wait for it here (an event recorded now)."""
         self._weights = (U_in, core, U_out)
         B.tdc_plan_pack_weights(self.plan, U_in, core, U_out, stream)
+        ts = _torch_stream(stream)
+        self._pack_event = ts.record_event()
+        self._ordered = {ts.cuda_stream}
+
+    def _order_after_pack(self, stream) -> None:
+        _order_after(self, stream)
 
     def __call__(self, x, y=None, weights=None, stream=None, bias=None, residual=None, relu=False):
         """y = layer(x), optionally followed by the fused epilogue y = relu?(y + bias[n] + residual)."""
         import torch
         U_in, core, U_out = weights if weights is not None else self._weights
+        self._order_after_pack(stream)
         if y is None:
             y = torch.empty(self.out_shape(), device=x.device, dtype=torch.float32)
         if bias is None and residual is None and not relu:
@@ -62,6 +98,7 @@ class TuckerConv2d:
         For callers that enqueue the same buffers repeatedly: the per-call cost is one foreign
         call.  The tensors and the stream must outlive the launcher."""
         U_in, core, U_out = weights if weights is not None else self._weights
+        self._order_after_pack(stream)
         vp = ctypes.c_void_p
         args = (self.plan, vp(B._stream(stream)), vp(x.data_ptr()), vp(U_in.data_ptr()), vp(core.data_ptr()),
                 vp(U_out.data_ptr()), vp(y.data_ptr()), ctypes.byref(self.shape))
@@ -120,10 +157,14 @@ class DenseConv2d:
     def pack(self, W, stream=None) -> None:
         self._W = W
         B.tdc_plan_pack_dense(self.plan, W, stream)
+        ts = _torch_stream(stream)
+        self._pack_event = ts.record_event()
+        self._ordered = {ts.cuda_stream}
 
     def __call__(self, x, y=None, W=None, stream=None, bias=None, residual=None, relu=False):
         import torch
         W = W if W is not None else self._W
+        _order_after(self, stream)
         if y is None:
             y = torch.empty(self.out_shape(), device=x.device, dtype=torch.float32)
         if bias is None and residual is None and not relu:
@@ -135,6 +176,7 @@ class DenseConv2d:
     def bind(self, x, y, W=None, stream=None, bias=None, residual=None, relu=False):
         """Zero-argument launcher with the arguments of tdc_conv_dense(_ex) marshalled once."""
         W = W if W is not None else self._W
+        _order_after(self, stream)
         vp = ctypes.c_void_p
         args = (self.plan, vp(B._stream(stream)), vp(x.data_ptr()), vp(W.data_ptr()), vp(y.data_ptr()),
                 ctypes.byref(self.shape))

@@ -115,9 +115,9 @@ def test_nhwc_epilogue(orc, variant, layer):
     assert_parity(got, nhwc(want), "nhwc epilogue %s %s [%s]" % (variant, layer.name(), desc))
 
 
-@pytest.mark.parametrize("cfg", [2, 4])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_nhwc_full_size_workloads(orc, cfg):
-    """The benchmark's sweep and the stride / batch ladder at full size with the selector's choice."""
+    """All five workloads at full size with the selector's choice."""
     for i, layer in enumerate(config_layers(cfg)):
         _announce("nhwc config", cfg, "layer", i, layer.name())
         inputs = make_inputs(layer, layer_seed(cfg, i))

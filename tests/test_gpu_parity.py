@@ -290,6 +290,59 @@ def test_run_major_refuses_misaligned_x(orc):
         B.tdc_plan_destroy(plan)
 
 
+def test_chain_takes_a_y_that_is_only_4_byte_aligned(orc):
+    """The NCHW CHAIN kernel writes y sixteen bytes at a time where rows allow it; a y that is only 4-byte aligned (a
+    slice of a larger tensor) is not refused but written with 4-byte stores, and nothing outside it is touched."""
+    import torch
+    layer = Layer(2, 32, 40, 8, 12, 16, 16)                  # tile and image widths multiples of 4: the 16-byte store path
+    _announce("chain, y 4-byte aligned", layer.name())
+    lib = B.load()
+    inputs = make_inputs(layer, 912)
+    want = _oracle(orc, layer, inputs)
+    t = {k: torch.from_numpy(v).cuda() for k, v in inputs.items()}
+    n_y = layer.batch * layer.N * layer.Ho * layer.Wo
+    ybuf = torch.full((n_y + 8,), float("nan"), device="cuda")
+    s = B.make_shape(**layer.asdict())
+    st = torch.cuda.current_stream().cuda_stream
+    plan = B.tdc_plan_create(s, 0, B.make_tuning(variant=B.VARIANT_CHAIN, tile_h=4, tile_w=12, waves=(4, 4, 4), mb=(1, 1, 1), pb=(1, 1, 1)))
+    p = lambda a: a.data_ptr()
+    try:
+        for shift in (1, 0):                                  # floats: 4-byte aligned only, then 16-byte aligned
+            ybuf.fill_(float("nan"))
+            rc = lib.tdc_conv_tucker2(plan, st, p(t["x"]), p(t["U_in"]), p(t["core"]), p(t["U_out"]), p(ybuf) + 4 * shift, s)
+            assert rc == B.TDC_OK, B.status_string(rc)
+            torch.cuda.synchronize()
+            got = ybuf[shift:shift + n_y].cpu().numpy().reshape(want.shape)
+            assert_parity(got, want, "chain with y shifted by %d floats" % shift)
+            rest = torch.cat([ybuf[:shift], ybuf[shift + n_y:]])
+            assert bool(torch.isnan(rest).all())              # the floats around y were left alone
+    finally:
+        B.tdc_plan_destroy(plan)
+
+
+def test_pack_on_one_stream_conv_on_another(orc):
+    """layer.py orders a conv call behind a weight re-layout that was enqueued on another stream."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    layer = Layer(2, 64, 64, 28, 28, 16, 32)
+    _announce("pack stream != conv stream", layer.name())
+    inputs = make_inputs(layer, 913)
+    want = _oracle(orc, layer, inputs)
+    t = {k: torch.from_numpy(v).cuda() for k, v in inputs.items()}
+    side = torch.cuda.Stream()
+    for variant in (B.VARIANT_FUSED, B.VARIANT_MERGED):
+        conv = TuckerConv2d(layer, 0, B.make_tuning(variant=variant))
+        try:
+            side.wait_stream(torch.cuda.current_stream())     # the weights were uploaded on the current stream
+            for _ in range(3):
+                conv.pack(t["U_in"], t["core"], t["U_out"], stream=side)
+                y = conv(t["x"])                              # current stream
+                torch.cuda.synchronize()
+                assert_parity(y.cpu().numpy(), want, conv.describe())
+        finally:
+            conv.close()
+
+
 def test_two_plans_on_two_streams(orc):
     """Calls only enqueue on the stream they are given: two layers with plans of their own run on two
     non-default streams at once, repeatedly, and each matches the oracle (no hidden use of the default stream,
