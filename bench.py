@@ -10,7 +10,7 @@ weights already resident in HBM.  Prints ONE JSON line.
 
   value        effective GFLOP/s of the sweep: algorithmic FLOPs of the four layers / step time
   layers       per layer: latency_us (event-timed over back-to-back launches on one stream, the
-               primary figure), sync_latency_us (one launch + host synchronise, median),
+               primary figure: median of 7 repeats, with min and max), sync_latency_us (one launch + host synchronise, median),
                cold_latency_us (back-to-back launches that cycle through more than 512 MB of distinct
                x / y buffers, so no activation is found in a cache), GFLOP/s, the fraction of the
                layer's roofline max(bytes/8 TB/s, flops/157.3 TFLOP/s), dense_conv_us (this
@@ -19,7 +19,8 @@ weights already resident in HBM.  Prints ONE JSON line.
   roofline     the same for the dominant (slowest) layer's kernel
   null_launch_us  an empty kernel timed the same way: the floor any batch-1 layer sits on
   throughput_regime  the batch-32 128->256 stride-2 layer (config 4) timed the same way, against the
-               fp32 MFMA peak: a side figure, not part of value
+               fp32 MFMA peak: a side figure, not part of value; throughput_layers lists it with the
+               other batched layers (28x28 and 14x14 at batch 32 and 128, the stride-2 layer at batch 64)
   cpu_baseline the CPU oracle (three-stage, fp64) timed on the host cores on the same sweep
 """
 from __future__ import annotations
@@ -34,16 +35,33 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per layer call (all its kernels) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/cfg2.txt, each scaled by what the same counter reads for a plain 256 MiB
-# device copy (FETCH_SIZE under-reads 2.0x on this machine, WRITE_SIZE is exact): (fetched, written) KiB,
-# keyed by layer name and the variant that was profiled.
-MEASURED_TRAFFIC = {
-    ("b1_c64_n64_56x56_r16-16_k3_s1_p1", "fused-merged"): (5819.3, 784.0),
-    ("b1_c128_n128_28x28_r32-32_k3_s1_p1", "fused-merged"): (4570.4, 784.0),
-    ("b1_c256_n256_14x14_r64-64_k3_s1_p1", "merged"): (1082.9 + 1054.9, 49.0 + 196.0),
-    ("b1_c512_n512_7x7_r128-128_k3_s1_p1", "merged"): (1110.9 + 2586.7, 24.5 + 98.0),
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "traffic.txt")
+
+
+def measured_traffic(layer_name, layout, plan):
+    """HBM bytes one call of `layer_name` moved when it was profiled with exactly this plan, from profiles/traffic.txt
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the counter reads for a plain device copy of known
+    size; the file names its runs).  None when no profile of this plan exists: a changed tuning never carries the
+    bytes of another one."""
+    key = plan.split(" model=")[0].strip()
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                if line.startswith("#") or not line.strip():
+                    continue
+                cols = [c.strip() for c in line.rstrip("\n").split("|")]
+                if len(cols) >= 5 and cols[0] == layer_name and cols[1] == layout and cols[2] == key:
+                    return float(cols[3]), float(cols[4])
+    except OSError:
+        pass
+    return None
+
+
+def _time_repeats(fn, iters, repeats, torch):
+    """`repeats` event-timed runs of `iters` back-to-back launches: (median, min, max) seconds per call.  The spread
+    shows the two clock / power states a run of launches can land in."""
+    ts = sorted(_time_events(fn, iters, torch) for _ in range(repeats))
+    return ts[len(ts) // 2], ts[0], ts[-1]
 
 
 def _time_events(fn, iters, torch):
@@ -209,14 +227,15 @@ def main():
     for launch in launchers:
         for _ in range(200):                      # clocks and caches settled before the timed launches
             launch()
-        queued.append(_time_events(launch, iters, torch))
+        queued.append(_time_repeats(launch, max(100, iters // 4), 7, torch))
     per_layer = []
     for i, (L, conv, launch) in enumerate(zip(layers, convs, launchers)):
-        sec = queued[i]
+        sec, sec_min, sec_max = queued[i]
         bound, t_roof, t_hbm, t_mfma = R.roofline(L)
         row = {
             "layer": L.name(), "plan": conv.describe(), "kernels": conv.kernel_count(),
-            "latency_us": sec * 1e6, "gflops": R.flops(L) / sec / 1e9,
+            "latency_us": sec * 1e6, "latency_us_min": sec_min * 1e6, "latency_us_max": sec_max * 1e6,
+            "latency_repeats": 7, "gflops": R.flops(L) / sec / 1e9,
             "dense_equiv_gflops": R.dense_flops(L) / sec / 1e9,
             "bound": bound, "roofline_us": t_roof * 1e6, "roofline_frac": t_roof / sec,
         }
@@ -224,6 +243,8 @@ def main():
             row["sync_latency_us"] = _time_sync(launch, 200, torch) * 1e6
             cold, n_sets = _time_cold(conv, L, xs[i], torch)
             row["cold_latency_us"], row["cold_buffer_sets"] = cold * 1e6, n_sets
+            # compulsory bytes over the cold-cache latency: what the layer pulls from HBM when nothing is cached
+            row["achieved_hbm_gbs"] = R.bytes_compulsory(L) / cold / 1e9
             # the undecomposed layer on this library's own dense kernel (the t2 of the paper's threshold test)
             dense = DenseConv2d(L, 0, layout=layout)
             W = torch.from_numpy(make_dense_inputs(L, layer_seed(args.config, i) + 500)["W"]).to(dev)
@@ -253,9 +274,13 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": R.flops(Ld) / sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    traffic = MEASURED_TRAFFIC.get((Ld.name(), pd["plan"].split(" ")[0])) if layout == B.LAYOUT_NCHW else None
+    traffic = measured_traffic(Ld.name(), args.layout, pd["plan"])
     roof["traffic"] = None if traffic is None else (traffic[0] + traffic[1]) * 1024.0      # bytes per layer call
     roof["traffic_fetch_write_kib"] = traffic
+    roof["traffic_source"] = "profiles/traffic.txt (rocprofv3 FETCH_SIZE / WRITE_SIZE of this plan, an earlier run)" if traffic else None
+    for row in per_layer:
+        tr = measured_traffic(row["layer"], args.layout, row["plan"])
+        row["traffic_bytes"] = None if tr is None else (tr[0] + tr[1]) * 1024.0
     roof["algorithmic_bytes"] = R.bytes_compulsory(Ld)
     roof["kernel"] = pd["plan"]
     roof["layer"] = Ld.name()
@@ -323,26 +348,37 @@ def main():
         for c in n_convs:
             c.close()
     if args.config == 2 and variant == 0 and not args.brief:
-        # beside the latency-bound headline: the one layer of config 4 whose batch fills the chip, against the
-        # same fp32 MFMA peak (a reported side figure; `value` and `roofline` above are the batch-1 sweep's)
-        Lt = config_layers(4)[2]
-        inp = make_inputs(Lt, layer_seed(4, 2))
-        t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
-        ct = TuckerConv2d(Lt, 0, None, layout=layout)
-        ct.pack(t["U_in"], t["core"], t["U_out"])
-        xt = t["x"].permute(0, 2, 3, 1).contiguous() if layout == B.LAYOUT_NHWC else t["x"]
-        yt = torch.empty(ct.out_shape(), device=dev, dtype=torch.float32)
-        lt = ct.bind(xt, yt)
-        for _ in range(200):
-            lt()
-        t_sec = _time_events(lt, 500, torch)
-        out["throughput_regime"] = {
-            "layer": Lt.name(), "plan": ct.describe(), "latency_us": t_sec * 1e6,
-            "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / t_sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12,
-                         "unit": "TFLOP/s", "frac": R.flops(Lt) / t_sec / R.FP32_MFMA_PEAK}}
-        torch.cuda.synchronize()
-        ct.close()
-        del xt, yt, t
+        # beside the latency-bound headline: layers whose batch fills the chip, against the same fp32 MFMA peak
+        # (reported side figures; `value` and `roofline` above are the batch-1 sweep's).  The first is the
+        # batch-32 stride-2 layer of config 4, then its 28x28 layer, then a batched 14x14 layer, then larger batches.
+        from paper_2211_03715_amd.workloads import Layer
+
+        def throughput(Lt, seed):
+            inp = make_inputs(Lt, seed)
+            t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
+            ct = TuckerConv2d(Lt, 0, None, layout=layout)
+            ct.pack(t["U_in"], t["core"], t["U_out"])
+            xt = t["x"].permute(0, 2, 3, 1).contiguous() if layout == B.LAYOUT_NHWC else t["x"]
+            yt = torch.empty(ct.out_shape(), device=dev, dtype=torch.float32)
+            lt = ct.bind(xt, yt)
+            for _ in range(100):
+                lt()
+            t_sec, t_min, t_max = _time_repeats(lt, 100, 5, torch)
+            torch.cuda.synchronize()
+            entry = {"layer": Lt.name(), "plan": ct.describe(), "latency_us": t_sec * 1e6, "latency_us_min": t_min * 1e6,
+                     "latency_us_max": t_max * 1e6,
+                     "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / t_sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12,
+                                  "unit": "TFLOP/s", "frac": R.flops(Lt) / t_sec / R.FP32_MFMA_PEAK}}
+            ct.close()
+            return entry
+
+        L4 = config_layers(4)
+        regime = [throughput(L4[2], layer_seed(4, 2)), throughput(L4[5], layer_seed(4, 5))]
+        for j, Lt in enumerate((Layer(32, 256, 256, 14, 14, 64, 64), Layer(128, 256, 256, 14, 14, 64, 64),
+                                Layer(128, 128, 128, 28, 28, 32, 32), Layer(64, 128, 256, 56, 56, 32, 64, 3, 2, 1))):
+            regime.append(throughput(Lt, layer_seed(4, 10 + j)))
+        out["throughput_regime"] = regime[0]
+        out["throughput_layers"] = regime
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
         if not args.brief:
