@@ -239,6 +239,13 @@ def _layer_from_name(name: str) -> Layer:
     return Layer(*[int(v) for v in m.groups()])
 
 
+def _load_sweep(path: str) -> List[Dict]:
+    """The per-layer results of a sweep file: the list --out writes, or that list under "results" beside a note."""
+    with open(path) as f:
+        d = json.load(f)
+    return d["results"] if isinstance(d, dict) else d
+
+
 def read_coefficients(path: str = COEF_HEADER) -> Dict[str, List[float]]:
     """The coefficient tables the library is built with, by model name."""
     import re
@@ -255,9 +262,7 @@ def sweep_rows(paths: Iterable[str], default_layout: str = "nchw") -> Dict[str, 
     measured latency and the model's terms for its tuning (tdc_model_terms: the one copy of the model, in the library)."""
     by_model: Dict[str, List[Dict]] = {}
     for path in paths:
-        with open(path) as f:
-            results = json.load(f)
-        for res in results:
+        for res in _load_sweep(path):
             L = _layer_from_name(res["layer"])
             layout = B.LAYOUT_NHWC if res.get("layout", default_layout) == "nhwc" else B.LAYOUT_NCHW
             shape = B.make_shape(**L.asdict(), layout=layout)
@@ -330,6 +335,44 @@ def evaluate(paths: Iterable[str], coefficients: Dict[str, List[float]], default
     return out
 
 
+def selector_gap(paths: Iterable[str], default_layout: str = "nchw") -> List[Dict]:
+    """The library's own choice (tdc_select_tuning with everything left open, all its rules applied) looked up in saved
+    sweeps: per (layer, layout) the latency timed for exactly that tuning against the best tuning timed.  A choice the
+    sweep did not time (a tile outside its menu) is listed with gap None."""
+    def key(t):
+        return (t["variant"], t["tile_h"], t["tile_w"], tuple(t["waves"]), tuple(t["mb"]), tuple(t["pb"]))
+    out = []
+    for path in paths:
+        for res in _load_sweep(path):
+            L = _layer_from_name(res["layer"])
+            lay = res.get("layout", default_layout)
+            shape = B.make_shape(**L.asdict(), layout=B.LAYOUT_NHWC if lay == "nhwc" else B.LAYOUT_NCHW)
+            pick = B.tdc_select_tuning(shape).as_dict()
+            same = [r for r in res["rows"] if key(r["tuning"]) == key(pick)]
+            best = min(r["us"] for r in res["rows"])
+            out.append({"layer": res["layer"], "layout": lay, "best_us": best, "pick": pick,
+                        "pick_us": same[0]["us"] if same else None, "gap": same[0]["us"] / best - 1.0 if same else None})
+    return out
+
+
+def selector_gap_main(paths: List[str], default_layout: str) -> int:
+    B.load()
+    rows = selector_gap(paths, default_layout)
+    print("%-46s %-5s %9s %9s %7s  %s" % ("layer", "", "best us", "chosen us", "gap", "chosen tuning"))
+    for r in rows:
+        t = r["pick"]
+        what = "%s tile=%dx%d waves=%s mb=%s pb=%s" % (t["variant"], t["tile_h"], t["tile_w"], t["waves"], t["mb"], t["pb"])
+        if r["gap"] is None:
+            print("%-46s %-5s %9.2f %9s %7s  %s" % (r["layer"], r["layout"], r["best_us"], "-", "-", what + "  (not timed in the sweep)"))
+        else:
+            print("%-46s %-5s %9.2f %9.2f %6.1f%%  %s" % (r["layer"], r["layout"], r["best_us"], r["pick_us"], 100 * r["gap"], what))
+    gaps = [r["gap"] for r in rows if r["gap"] is not None]
+    if gaps:
+        print("the selector's choice behind the best tuning timed: mean %.1f%%, max %.1f%% over %d layers (%d more not timed)" % (
+            100 * sum(gaps) / len(gaps), 100 * max(gaps), len(gaps), len(rows) - len(gaps)))
+    return 0
+
+
 def write_coefficients(fitted: Dict[str, Dict], path: str = COEF_HEADER) -> None:
     """Replace the tables of the fitted models in the coefficient header; the other tables stay as they are."""
     import re
@@ -396,6 +439,9 @@ def main(argv=None) -> int:
     ap.add_argument("--fit", nargs="+", default=None, metavar="JSON",
                     help="no GPU: refit the selector's coefficients to sweeps saved with --out (the library supplies the "
                          "model's terms per tuning, tdc_model_terms) and print the tables of csrc/tdc_select_coef.h")
+    ap.add_argument("--selector-gap", nargs="+", default=None, metavar="JSON",
+                    help="no GPU: look the built library's own choice up in sweeps saved with --out and print how far it "
+                         "lies behind the best tuning timed")
     ap.add_argument("--models", nargs="*", default=[], help="with --fit: only these coefficient tables "
                     "(fused_latency fused_throughput chain fused_merged stage)")
     ap.add_argument("--held-out", nargs="*", default=[], metavar="JSON", help="with --fit: sweeps the fit does not see, "
@@ -404,6 +450,8 @@ def main(argv=None) -> int:
                     "in a row's weight; 0 weighs every tuning of a layer alike")
     ap.add_argument("--write-coef", action="store_true", help="with --fit: write the fitted tables into csrc/tdc_select_coef.h")
     args = ap.parse_args(argv)
+    if args.selector_gap:
+        return selector_gap_main(args.selector_gap, args.layout)
     if args.fit:
         return fit_main(args.fit, args.layout, args.models, args.write_coef, args.held_out, args.near_best)
     if args.analyse:

@@ -1,0 +1,111 @@
+"""The selector's calibration tool on the CPU: the library exports the terms of its latency estimate per tuning
+(tdc_model_terms), autotune.fit refits the coefficient tables to saved sweeps.  Runs on a small sample of a sweep timed
+on MI355X (tests/golden/sweep_sample.json); no GPU, no kernels."""
+import json
+import os
+import shutil
+
+import numpy as np
+import pytest
+
+from paper_2211_03715_amd import autotune as A
+from paper_2211_03715_amd import binding as B
+
+SAMPLE = os.path.join(os.path.dirname(__file__), "golden", "sweep_sample.json")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    B.load()
+    return B
+
+
+def test_tables_match_the_terms_the_library_exports(lib):
+    tables = A.read_coefficients()
+    assert set(tables) == set(A.COEF_TABLES)
+    rows = A.sweep_rows([SAMPLE])
+    assert {"chain", "fused_throughput"} <= set(rows)
+    for model, rs in rows.items():
+        for r in rs:
+            assert len(r["terms"]) == len(r["names"]) == len(tables[model])
+            assert all(t >= 0.0 for t in r["terms"])
+            assert r["terms"][0] >= 1.0          # every model starts with its launches
+
+
+def test_estimate_is_the_dot_product_the_selector_ranks_by(lib):
+    """A tuning the selector prefers has the lower dot product: force two CHAIN tunings of one layer and compare the
+    selector's choice between them with the estimates rebuilt from the exported terms and the tracked tables."""
+    tables = A.read_coefficients()
+    shape = B.make_shape(batch=32, C=128, N=128, H=28, W=28, R1=32, R2=32, K=3, stride=1, pad=1)
+    pick = B.tdc_select_tuning(shape, tuning=B.make_tuning(variant=B.VARIANT_CHAIN))
+    model, names, terms = B.tdc_model_terms(shape, pick)
+    assert model == "chain"
+    est_pick = float(np.dot(tables[model], terms))
+    d = pick.as_dict()
+    for mb1 in (1, 2):
+        for pb in (1, 2):
+            other = B.make_tuning(variant=B.VARIANT_CHAIN, tile_h=d["tile_h"], tile_w=d["tile_w"], waves=tuple(d["waves"]),
+                                  mb=(mb1, 1, 1), pb=(pb, pb, pb))
+            try:
+                _, _, t2 = B.tdc_model_terms(shape, other)
+            except B.TdcError:
+                continue
+            assert est_pick <= float(np.dot(tables[model], t2)) + 1e-9
+
+
+def test_fit_recovers_latencies_made_from_known_coefficients(lib, tmp_path):
+    """Latencies synthesised as (tracked table) . terms are fitted back to zero error and zero regret."""
+    tables = A.read_coefficients()
+    with open(SAMPLE) as f:
+        sample = json.load(f)
+    for res in sample["results"]:
+        L = A._layer_from_name(res["layer"])
+        shape = B.make_shape(**L.asdict(), layout=B.LAYOUT_NHWC if res["layout"] == "nhwc" else B.LAYOUT_NCHW)
+        keep = []
+        for r in res["rows"]:
+            t = r["tuning"]
+            tuning = B.make_tuning(variant=A._VARIANT_IDS[t["variant"]], tile_h=t["tile_h"], tile_w=t["tile_w"],
+                                   waves=tuple(t["waves"]), mb=tuple(t["mb"]), pb=tuple(t["pb"]))
+            try:
+                model, _, terms = B.tdc_model_terms(shape, tuning)
+            except B.TdcError:
+                continue
+            r["us"] = float(np.dot(tables[model], terms))
+            keep.append(r)
+        res["rows"] = keep
+    path = tmp_path / "synthetic.json"
+    path.write_text(json.dumps(sample))
+    fitted = A.fit([str(path)])
+    assert fitted
+    for model, res in fitted.items():
+        assert res["median_err"] < 1e-6 and res["p90_err"] < 1e-5, model
+        assert max(v["regret"] for v in res["regret"].values()) < 1e-9
+
+
+def test_fit_on_the_measured_sample(lib):
+    fitted = A.fit([SAMPLE], models=("chain", "fused_throughput"))
+    for model in ("chain", "fused_throughput"):
+        res = fitted[model]
+        assert all(c >= 0.0 for c in res["coef"])
+        assert res["median_err"] < 0.15, (model, res["median_err"])
+        assert max(v["regret"] for v in res["regret"].values()) < 0.15
+    ev = A.evaluate([SAMPLE], A.read_coefficients())
+    assert len(ev) == 4 and all(v["regret"] < 0.25 for v in ev.values())
+
+
+def test_selector_choice_looked_up_in_the_sample(lib):
+    rows = A.selector_gap([SAMPLE])
+    assert len(rows) == 4
+    for r in rows:
+        assert r["gap"] is None or 0.0 <= r["gap"] < 0.25
+
+
+def test_coefficient_header_round_trip(lib, tmp_path):
+    copy = tmp_path / "coef.h"
+    shutil.copy(A.COEF_HEADER, copy)
+    before = A.read_coefficients(str(copy))
+    fake = {"chain": {"coef": [0.5 * i for i in range(len(before["chain"]))]}}
+    A.write_coefficients(fake, str(copy))
+    after = A.read_coefficients(str(copy))
+    assert after["chain"] == pytest.approx(fake["chain"]["coef"])
+    assert after["stage"] == before["stage"] and after["fused_latency"] == before["fused_latency"]
