@@ -379,6 +379,20 @@ def main():
             regime.append(throughput(Lt, layer_seed(4, 10 + j)))
         out["throughput_regime"] = regime[0]
         out["throughput_layers"] = regime
+    if args.config == 2 and variant == 0 and not args.brief:
+        # the paper's end-to-end setting in this library's terms: the 3 + 4 + 6 + 3 bottleneck blocks of a ResNet-50-shaped
+        # network (dense 1x1s, Tucker-2 3x3s, projection shortcuts, epilogues fused), eagerly and as ONE HIP graph
+        from paper_2211_03715_amd.bottleneck import TuckerResNetBody, time_network
+        chains = []
+        for lay_name, lay in (("nchw", B.LAYOUT_NCHW), ("nhwc", B.LAYOUT_NHWC)):
+            net = TuckerResNetBody(1, layout=lay)
+            entry = {"network": "ResNet-50 residual stages (16 bottleneck blocks), 64x56x56 in, 2048x7x7 out, batch 1",
+                     "layout": lay_name, "kernels": net.kernels(), "gflop": net.flops() / 1e9}
+            entry.update(time_network(net))
+            entry["graph_gflops"] = net.flops() / entry["graph_us"] / 1e3
+            chains.append(entry)
+            net.close()
+        out["resnet50_body"] = chains
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
         if not args.brief:

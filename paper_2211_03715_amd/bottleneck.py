@@ -12,7 +12,12 @@ All buffers are allocated when the block is built, so a call only enqueues three
 (four when the selector gives the Tucker layer two kernels) and can be captured into a HIP
 graph: `graph = block.capture(x_static)`, then `graph.replay()`.
 
-    python -m paper_2211_03715_amd.bottleneck [--nhwc]   # eager vs graph latency of a few block shapes
+A block that changes width or resolution (the first of a ResNet stage) has stride 2 on its 3x3 convolution and
+a projection shortcut, one more dense 1x1 launch:   s = Wp (*) x + bp,   y = relu(W3 (*) t2 + b3 + s).
+TuckerResNetBody strings 3 + 4 + 6 + 3 such blocks into the residual stages of a ResNet-50-shaped network.
+
+    python -m paper_2211_03715_amd.bottleneck [--nhwc]             # eager vs graph latency of a few block shapes
+    python -m paper_2211_03715_amd.bottleneck --resnet50 [--nhwc] [--batch B]   # the 16-block network
 """
 from __future__ import annotations
 
@@ -26,44 +31,64 @@ from .layer import DenseConv2d, TuckerConv2d
 from .workloads import Layer
 
 
-def make_block_weights(C: int, M: int, R1: int, R2: int, seed: int) -> Dict[str, np.ndarray]:
-    """Seeded float32 weights of one block, N(0, 1/fan_in); biases N(0, 0.01)."""
+def make_block_weights(C: int, M: int, R1: int, R2: int, seed: int, C_out: int = 0, projection: bool = False) -> Dict[str, np.ndarray]:
+    """Seeded float32 weights of one block, N(0, 1/fan_in); biases N(0, 0.01).  C_out (default C) is the width the
+    block leaves with; with ``projection`` the shortcut is a 1x1 convolution C -> C_out ("Wp", "bp")."""
     rng = np.random.default_rng(seed)
+    C_out = C_out or C
     n = lambda shape, fan: (rng.standard_normal(shape, dtype=np.float32) * np.float32(fan ** -0.5))
-    return {"W1": n((C, M, 1, 1), C), "b1": n((M,), 100.0),
-            "U_in": n((M, R1), M), "core": n((R1, R2, 3, 3), R1 * 9), "U_out": n((R2, M), R2), "b2": n((M,), 100.0),
-            "W3": n((M, C, 1, 1), M), "b3": n((C,), 100.0)}
+    w = {"W1": n((C, M, 1, 1), C), "b1": n((M,), 100.0),
+         "U_in": n((M, R1), M), "core": n((R1, R2, 3, 3), R1 * 9), "U_out": n((R2, M), R2), "b2": n((M,), 100.0),
+         "W3": n((M, C_out, 1, 1), M), "b3": n((C_out,), 100.0)}
+    if projection:
+        w["Wp"], w["bp"] = n((C, C_out, 1, 1), C), n((C_out,), 100.0)
+    return w
 
 
 class TuckerBottleneck:
     def __init__(self, batch: int, C: int, M: int, H: int, W: int, R1: int, R2: int, weights: Dict, device: int = 0,
-                 layout: int = B.LAYOUT_NCHW):
-        """``layout``: LAYOUT_NCHW (x, y [batch][C][H][W]) or LAYOUT_NHWC ([batch][H][W][C]); C, M multiples of 4 for NHWC."""
+                 layout: int = B.LAYOUT_NCHW, stride: int = 1, C_out: int = 0):
+        """``layout``: LAYOUT_NCHW (x, y [batch][C][H][W]) or LAYOUT_NHWC ([batch][H][W][C]); C, M multiples of 4 for NHWC.
+        ``stride`` sits on the 3x3 convolution; with stride != 1 or C_out != C the shortcut is the projection
+        s = Wp (*) x + bp (1x1, same stride, no activation: weights "Wp", "bp") and y = relu(W3 (*) t2 + b3 + s)."""
         import torch
         self.dev = torch.device("cuda", device)
         self.layout = layout
+        C_out = C_out or C
+        self.projection = stride != 1 or C_out != C
         self.l1 = Layer(batch, C, M, H, W, 1, 1, 1, 1, 0)
-        self.l2 = Layer(batch, M, M, H, W, R1, R2, 3, 1, 1)
-        self.l3 = Layer(batch, M, C, H, W, 1, 1, 1, 1, 0)
+        self.l2 = Layer(batch, M, M, H, W, R1, R2, 3, stride, 1)
+        self.l3 = Layer(batch, M, C_out, self.l2.Ho, self.l2.Wo, 1, 1, 1, 1, 0)
+        self.lp = Layer(batch, C, C_out, H, W, 1, 1, 1, stride, 0) if self.projection else None
         self.w = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.dev) for k, v in weights.items()}
         self.conv1, self.conv2, self.conv3 = (DenseConv2d(self.l1, device, layout=layout), TuckerConv2d(self.l2, device, layout=layout),
                                               DenseConv2d(self.l3, device, layout=layout))
+        self.convp = DenseConv2d(self.lp, device, layout=layout) if self.projection else None
         self.conv1.pack(self.w["W1"])
         self.conv2.pack(self.w["U_in"], self.w["core"], self.w["U_out"])
         self.conv3.pack(self.w["W3"])
         self.t1 = torch.empty(self.conv1.out_shape(), device=self.dev, dtype=torch.float32)
         self.t2 = torch.empty(self.conv2.out_shape(), device=self.dev, dtype=torch.float32)
         self.y = torch.empty(self.conv3.out_shape(), device=self.dev, dtype=torch.float32)
+        self.s = None
+        if self.projection:
+            self.convp.pack(self.w["Wp"])
+            self.s = torch.empty(self.convp.out_shape(), device=self.dev, dtype=torch.float32)
+            assert tuple(self.s.shape) == tuple(self.y.shape)
         self._launchers = None
         self._x = None
 
+    def _convs(self):
+        return [c for c in (self.convp, self.conv1, self.conv2, self.conv3) if c is not None]
+
     def bind(self, x):
-        """Marshal the three calls for a fixed input tensor; returns self for chaining."""
+        """Marshal the block's calls for a fixed input tensor; returns self for chaining."""
         self._x = x
-        self._launchers = (
+        first = (self.convp.bind(x, self.s, bias=self.w["bp"]),) if self.projection else ()    # while x is the freshest data
+        self._launchers = first + (
             self.conv1.bind(x, self.t1, bias=self.w["b1"], relu=True),
             self.conv2.bind(self.t1, self.t2, bias=self.w["b2"], relu=True),
-            self.conv3.bind(self.t2, self.y, bias=self.w["b3"], residual=x, relu=True),
+            self.conv3.bind(self.t2, self.y, bias=self.w["b3"], residual=self.s if self.projection else x, relu=True),
         )
         return self
 
@@ -91,14 +116,120 @@ class TuckerBottleneck:
         return graph
 
     def kernels(self) -> int:
-        return 2 + self.conv2.kernel_count()
+        return 2 + self.conv2.kernel_count() + (1 if self.projection else 0)
+
+    def flops(self) -> int:
+        """Algorithmic FLOPs of the block as built (2 per multiply-add; the Tucker layer in its factored form)."""
+        from . import roofline as R
+        dense = lambda L: 2 * L.batch * L.C * L.N * L.K * L.K * L.Ho * L.Wo
+        return dense(self.l1) + R.flops(self.l2) + dense(self.l3) + (dense(self.lp) if self.projection else 0)
 
     def describe(self) -> str:
-        return "1x1: %s | 3x3: %s | 1x1: %s" % (self.conv1.describe(), self.conv2.describe(), self.conv3.describe())
+        head = "shortcut 1x1: %s | " % self.convp.describe() if self.projection else ""
+        return head + "1x1: %s | 3x3: %s | 1x1: %s" % (self.conv1.describe(), self.conv2.describe(), self.conv3.describe())
 
     def close(self) -> None:
-        for c in (self.conv1, self.conv2, self.conv3):
+        for c in self._convs():
             c.close()
+
+
+def default_rank(M: int) -> int:
+    """The rank the synthetic networks give a 3x3 layer of M channels: 0.3 M rounded to a multiple of 8, at least 8."""
+    return max(8, int(round(0.3 * M / 8.0)) * 8)
+
+
+class TuckerResNetBody:
+    """The four residual stages of a ResNet-50-shaped network (section 7.3's end-to-end setting) with every 3x3 convolution
+    in Tucker-2 form: ``blocks`` = (3, 4, 6, 3) bottleneck blocks of widths M = width, 2 width, 4 width, 8 width, each
+    leaving with 4 M channels; the first block of a stage has a projection shortcut and, from the second stage on,
+    stride 2 on its 3x3 convolution.  The input is the stem's output ([batch][width][H][W], 64 x 56 x 56 for the
+    real network); the stem, pooling and classifier are dense layers outside this library.  Weights are seeded and
+    synthetic (make_block_weights), ranks come from ``rank(M)``."""
+
+    def __init__(self, batch: int, H: int = 56, W: int = 56, width: int = 64, blocks=(3, 4, 6, 3), rank=default_rank,
+                 seed: int = 0, device: int = 0, layout: int = B.LAYOUT_NCHW):
+        import torch
+        self.dev = torch.device("cuda", device)
+        self.layout = layout
+        self.batch, self.width = batch, width
+        self.blocks = []
+        self.weights = []
+        C, h, w = width, H, W
+        for stage, count in enumerate(blocks):
+            M = width << stage
+            for i in range(count):
+                first = i == 0
+                stride = 2 if (first and stage > 0) else 1
+                R = rank(M)
+                wts = make_block_weights(C, M, R, R, seed + 100 * stage + i, C_out=4 * M, projection=first)
+                blk = TuckerBottleneck(batch, C, M, h, w, R, R, wts, device, layout, stride=stride, C_out=4 * M)
+                assert blk.projection == first
+                self.blocks.append(blk)
+                self.weights.append(wts)
+                C, h, w = 4 * M, blk.l2.Ho, blk.l2.Wo
+        self.in_shape = (batch, H, W, width) if layout == B.LAYOUT_NHWC else (batch, width, H, W)
+        self.y = self.blocks[-1].y
+
+    def __call__(self, x):
+        """Enqueue every block on the current stream; returns the last block's (network-owned) output."""
+        for blk in self.blocks:
+            x = blk(x)
+        return x
+
+    def capture(self, x_static):
+        """One HIP graph holding every launch of the network on x_static."""
+        import torch
+        self(x_static)                       # once eagerly: kernel attributes, lazy module load
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            x = x_static
+            for blk in self.blocks:
+                blk.bind(x)                  # launchers carry their stream: bind to the capturing one
+                x = blk()
+        for blk in self.blocks:
+            blk._launchers = None
+        return graph
+
+    def kernels(self) -> int:
+        return sum(b.kernels() for b in self.blocks)
+
+    def flops(self) -> int:
+        return sum(b.flops() for b in self.blocks)
+
+    def describe(self) -> str:
+        return "\n".join("block %2d  %s" % (i, b.describe()) for i, b in enumerate(self.blocks))
+
+    def close(self) -> None:
+        for b in self.blocks:
+            b.close()
+
+
+def time_network(net, iters: int = 100, repeats: int = 5) -> Dict[str, float]:
+    """Median over ``repeats`` of the time per pass (HIP events around ``iters`` passes), eagerly and from one graph."""
+    import torch
+    x = torch.randn(net.in_shape, device=net.dev)
+    graph = net.capture(x)
+
+    def timed(fn):
+        for _ in range(10):
+            fn()
+        out = []
+        for _ in range(repeats):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(iters):
+                fn()
+            b.record()
+            b.synchronize()
+            out.append(a.elapsed_time(b) * 1e3 / iters)
+        return sorted(out)
+
+    eager, replay = timed(lambda: net(x)), timed(graph.replay)
+    torch.cuda.synchronize()
+    del graph
+    return {"eager_us": eager[len(eager) // 2], "eager_us_min": eager[0], "eager_us_max": eager[-1],
+            "graph_us": replay[len(replay) // 2], "graph_us_min": replay[0], "graph_us_max": replay[-1]}
 
 
 def main(argv=None) -> int:
@@ -107,6 +238,15 @@ def main(argv=None) -> int:
         sys.exit("bottleneck needs a GPU")
     B.load()
     layout = B.LAYOUT_NHWC if argv and "--nhwc" in argv else B.LAYOUT_NCHW
+    if argv and "--resnet50" in argv:
+        batch = int(argv[argv.index("--batch") + 1]) if "--batch" in argv else 1
+        net = TuckerResNetBody(batch, layout=layout)
+        r = time_network(net)
+        print(net.describe())
+        print("ResNet-50 body, batch %d, %s: %d blocks, %d kernels, %.3f GFLOP; eager %.1f us, one graph %.1f us" % (
+            batch, "NHWC" if layout else "NCHW", len(net.blocks), net.kernels(), net.flops() / 1e9, r["eager_us"], r["graph_us"]))
+        net.close()
+        return 0
     print("%-34s %8s %10s %10s  %s" % ("block (batch 1, %s)" % ("NHWC" if layout else "NCHW"), "kernels", "eager us", "graph us", "plans"),
           flush=True)
     for (C, M, HW, R) in ((256, 64, 56, 16), (512, 128, 28, 32), (1024, 256, 14, 64), (2048, 512, 7, 128)):

@@ -1,12 +1,13 @@
 """A bottleneck block (dense 1x1 + Tucker 3x3 + dense 1x1, epilogues fused) against the oracle, eagerly
-and replayed from a HIP graph."""
+and replayed from a HIP graph; blocks with stride 2 and a projection shortcut; and the 3 + 4 + 6 + 3 blocks of a
+ResNet-50-shaped network chained, eagerly and as one graph."""
 import sys
 
 import numpy as np
 import pytest
 
 from paper_2211_03715_amd import binding as B
-from paper_2211_03715_amd.bottleneck import TuckerBottleneck, make_block_weights
+from paper_2211_03715_amd.bottleneck import TuckerBottleneck, TuckerResNetBody, make_block_weights
 from parity_util import assert_parity
 
 pytestmark = pytest.mark.gpu
@@ -18,7 +19,19 @@ def _oracle_block(orc, blk, w, x):
     y2, _ = orc.conv_factored(orc.Shape(**blk.l2.asdict()), t1, w["U_in"], w["core"], w["U_out"])
     t2 = orc.apply_epilogue(y2, w["b2"], None, True).astype(np.float32)
     y3, _ = orc.conv_dense_with(orc.Shape(**blk.l3.asdict()), t2, w["W3"].astype(np.float64))
-    return orc.apply_epilogue(y3, w["b3"], x, True)
+    s = x
+    if blk.projection:                                                          # s = Wp (*) x + bp, stored in fp32
+        yp, _ = orc.conv_dense_with(orc.Shape(**blk.lp.asdict()), x, w["Wp"].astype(np.float64))
+        s = orc.apply_epilogue(yp, w["bp"], None, False).astype(np.float32)
+    return orc.apply_epilogue(y3, w["b3"], s, True)
+
+
+def _perm(layout):
+    return (lambda a: np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1)))) if layout == B.LAYOUT_NHWC else (lambda a: a)
+
+
+def _unperm(layout):
+    return (lambda a: np.ascontiguousarray(np.transpose(a, (0, 3, 1, 2)))) if layout == B.LAYOUT_NHWC else (lambda a: a)
 
 
 @pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
@@ -31,7 +44,7 @@ def test_bottleneck_eager_and_graph(orc, shape, layout):
     sys.stdout.flush()
     w = make_block_weights(C, M, R1, R2, 11)
     blk = TuckerBottleneck(batch, C, M, H, W, R1, R2, w, layout=layout)
-    perm = (lambda a: np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1)))) if layout == B.LAYOUT_NHWC else (lambda a: a)
+    perm = _perm(layout)
     try:
         rng = np.random.default_rng(5)
         xs = [rng.standard_normal((batch, C, H, W), dtype=np.float32) for _ in range(3)]
@@ -98,3 +111,99 @@ def test_large_lds_kernels_under_graph_capture(orc, variant):
                 assert torch.equal(eager, y)
     finally:
         conv.close()
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
+@pytest.mark.parametrize("shape", [(1, 32, 16, 14, 14, 8, 8, 2, 64), (2, 24, 12, 9, 11, 8, 12, 2, 48), (1, 16, 16, 10, 7, 8, 8, 1, 64),
+                                   (1, 256, 128, 56, 56, 32, 32, 2, 512)],
+                         ids=lambda s: "b%d_c%d_m%d_%dx%d_r%d-%d_s%d_out%d" % s)
+def test_projection_block(orc, shape, layout):
+    """The first block of a stage: stride on the 3x3 convolution, shortcut through a strided 1x1 projection."""
+    import torch
+    batch, C, M, H, W, R1, R2, stride, C_out = shape
+    print("[case] projection block", shape, "layout", layout, flush=True)
+    sys.stdout.flush()
+    w = make_block_weights(C, M, R1, R2, 13, C_out=C_out, projection=True)
+    blk = TuckerBottleneck(batch, C, M, H, W, R1, R2, w, layout=layout, stride=stride, C_out=C_out)
+    perm = _perm(layout)
+    try:
+        assert blk.projection and blk.kernels() >= 4
+        rng = np.random.default_rng(6)
+        xs = [rng.standard_normal((batch, C, H, W), dtype=np.float32) for _ in range(2)]
+        wants = [perm(_oracle_block(orc, blk, w, x)) for x in xs]
+        x_static = torch.from_numpy(perm(xs[0])).to(blk.dev)
+        got = blk(x_static)
+        torch.cuda.synchronize()
+        assert tuple(got.shape) == wants[0].shape
+        assert_parity(got.cpu().numpy(), wants[0], "eager " + blk.describe())
+        graph = blk.capture(x_static)
+        for x, want in zip(xs[::-1], wants[::-1]):
+            x_static.copy_(torch.from_numpy(perm(x)).to(blk.dev))
+            blk.y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert_parity(blk.y.cpu().numpy(), want, "graph replay")
+    finally:
+        blk.close()
+
+
+def _oracle_network(orc, net, x):
+    """The oracle chained block by block; every tensor the GPU stores (block outputs included) is rounded to fp32."""
+    outs = []
+    for blk, w in zip(net.blocks, net.weights):
+        x = _oracle_block(orc, blk, w, x).astype(np.float32)
+        outs.append(x)
+    return outs
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
+@pytest.mark.parametrize("case", [(2, 16, 32, 32), (1, 64, 56, 56)], ids=["b2_width16_32x32", "resnet50_b1_width64_56x56"])
+def test_resnet_body_eager_and_one_graph(orc, case, layout):
+    """3 + 4 + 6 + 3 bottleneck blocks (projection + stride 2 where a stage starts) run back to back.  Compared with
+    the oracle chained through all 16 blocks (whole-network parity, the tolerance of a single layer), and block by
+    block on the input the GPU itself produced; then the whole network replayed from ONE HIP graph on new inputs."""
+    import torch
+    batch, width, H, W = case
+    print("[case] resnet body", case, "layout", layout, flush=True)
+    sys.stdout.flush()
+    net = TuckerResNetBody(batch, H, W, width, layout=layout, seed=40)
+    perm, unperm = _perm(layout), _unperm(layout)
+    try:
+        assert len(net.blocks) == 16 and [b.projection for b in net.blocks] == [i in (0, 3, 7, 13) for i in range(16)]
+        assert [b.l2.stride for b in net.blocks] == [2 if i in (3, 7, 13) else 1 for i in range(16)]
+        rng = np.random.default_rng(8)
+        xs = [rng.standard_normal((batch, width, H, W), dtype=np.float32) for _ in range(2)]
+        x_static = torch.from_numpy(perm(xs[0])).to(net.dev)
+        got = net(x_static)
+        torch.cuda.synchronize()
+        assert tuple(got.shape) == ((batch, H // 8, W // 8, 32 * width) if layout == B.LAYOUT_NHWC else (batch, 32 * width, H // 8, W // 8))
+        wants = _oracle_network(orc, net, xs[0])
+        for i, (blk, want) in enumerate(zip(net.blocks, wants)):
+            assert_parity(blk.y.cpu().numpy(), perm(want), "network up to block %d" % i)
+        # block by block on the GPU's own block inputs: an error in one block cannot hide behind the others
+        x_in = xs[0]
+        for i, (blk, w) in enumerate(zip(net.blocks, net.weights)):
+            assert_parity(blk.y.cpu().numpy(), perm(_oracle_block(orc, blk, w, x_in)), "block %d alone" % i)
+            x_in = unperm(blk.y.cpu().numpy())
+        eager_first = got.clone()
+        graph = net.capture(x_static)
+        n_kernels = net.kernels()
+        assert n_kernels >= 16 * 3 + 4
+        for rep, k in enumerate((1, 0, 1)):
+            x_static.copy_(torch.from_numpy(perm(xs[k])).to(net.dev))
+            for blk in net.blocks:
+                blk.y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            replayed = net.y.clone()
+            if k == 0:
+                assert torch.equal(replayed, eager_first)
+            else:
+                assert_parity(replayed.cpu().numpy(), perm(_oracle_network(orc, net, xs[1])[-1]), "graph replay %d" % rep)
+            eager = net(x_static).clone()                     # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(eager, replayed)
+    finally:
+        net.close()
