@@ -170,6 +170,9 @@ def main():
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by)")
+    ap.add_argument("--graph-study", action="store_true",
+                    help="only the step, --steps times eagerly, then (after a 50 ms pause that separates the two in a kernel "
+                         "trace) --steps replays of its HIP graph; prints both per-step times and exits")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -212,6 +215,34 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.graph_study:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cap = [conv.bind(x, y) for conv, x, y in zip(convs, xs, ys)]     # launchers carry their stream
+            for launch in cap:
+                launch()
+        graph8 = torch.cuda.CUDAGraph()                                       # eight steps in one graph
+        with torch.cuda.graph(graph8):
+            for _ in range(8):
+                for launch in cap:
+                    launch()
+        for _ in range(args.warmup):
+            graph.replay()
+            graph8.replay()
+        torch.cuda.synchronize()
+        res = {"steps": args.steps, "kernels_per_step": sum(c.kernel_count() for c in convs)}
+        for name, fn, per in (("eager", step, 1), ("graph", graph.replay, 1), ("graph_of_8_steps", graph8.replay, 8)):
+            time.sleep(0.05)
+            t0 = time.perf_counter()
+            for _ in range(args.steps // per):
+                fn()
+            t_enq = time.perf_counter() - t0
+            torch.cuda.synchronize()
+            n = args.steps // per * per
+            res[name + "_us_per_step"] = (time.perf_counter() - t0) / n * 1e6
+            res[name + "_host_enqueue_us_per_step"] = t_enq / n * 1e6
+        print(json.dumps(res))
+        return
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
