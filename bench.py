@@ -160,7 +160,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default: the ResNet-18-shaped sweep)")
+    ap.add_argument("--config", type=int, default=2, help="workload id 1..6 (default 2: the ResNet-18-shaped sweep)")
     ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged", "fused_merged"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"],
                     help="activation layout (default NCHW, the layout the metric's workload is stated in)")
@@ -327,7 +327,9 @@ def main():
             2: "ResNet-18-shaped sweep, batch 1, 3x3 s1 p1, (C=N,HxW) in (64,56) (128,28) (256,14) (512,7), R1=R2=C/4",
             3: "rank sweep at C=N=256, 14x14, (R1,R2) in {8,16,32,64,128}^2, batch 1",
             4: "stride/batch variants: 128->256 s2 56->28 r32/64 and 128->128 28x28 r32, batch 1/8/32",
-            5: "ResNet-50-style chain of 16 Tucker-2 3x3 layers, ranks round(0.3C) to 8, batch 1"}[args.config]),
+            5: "ResNet-50-style chain of 16 Tucker-2 3x3 layers, ranks round(0.3C) to 8, batch 1",
+            6: "throughput set: 128->256 s2 56->28 r32/64 at batch 32 and 64, 128->128 28x28 r32 at batch 32 and 128, "
+               "256->256 14x14 r64 at batch 32 and 128"}[args.config]),
             "layers_per_step": len(layers), "variant": args.variant, "layout": args.layout},
         "roofline": roof,
         "layers": per_layer,
@@ -380,9 +382,8 @@ def main():
             c.close()
     if args.config == 2 and variant == 0 and not args.brief:
         # beside the latency-bound headline: layers whose batch fills the chip, against the same fp32 MFMA peak
-        # (reported side figures; `value` and `roofline` above are the batch-1 sweep's).  The first is the
-        # batch-32 stride-2 layer of config 4, then its 28x28 layer, then a batched 14x14 layer, then larger batches.
-        from paper_2211_03715_amd.workloads import Layer
+        # (reported side figures; `value` and `roofline` above are the batch-1 sweep's): workload 6, whose first
+        # two layers are the batch-32 layers of config 4, then a 14x14 layer at batch 32 and 128, then larger batches.
 
         def throughput(Lt, seed):
             inp = make_inputs(Lt, seed)
@@ -403,11 +404,7 @@ def main():
             ct.close()
             return entry
 
-        L4 = config_layers(4)
-        regime = [throughput(L4[2], layer_seed(4, 2)), throughput(L4[5], layer_seed(4, 5))]
-        for j, Lt in enumerate((Layer(32, 256, 256, 14, 14, 64, 64), Layer(128, 256, 256, 14, 14, 64, 64),
-                                Layer(128, 128, 128, 28, 28, 32, 32), Layer(64, 128, 256, 56, 56, 32, 64, 3, 2, 1))):
-            regime.append(throughput(Lt, layer_seed(4, 10 + j)))
+        regime = [throughput(Lt, layer_seed(6, j)) for j, Lt in enumerate(config_layers(6))]
         out["throughput_regime"] = regime[0]
         out["throughput_layers"] = regime
     if args.config == 2 and variant == 0 and not args.brief:

@@ -62,7 +62,8 @@ def _round8(v: float) -> int:
 
 
 def config_layers(config_id: int) -> List[Layer]:
-    """The five synthetic workloads, numbered 1..5."""
+    """The five synthetic workloads, numbered 1..5, and 6: this library's own throughput set (layers of 4 and a
+    14x14 layer at batch sizes that fill the chip)."""
     if config_id == 1:   # single layer, the primary parity case
         return [Layer(1, 64, 64, 56, 56, 16, 16)]
     if config_id == 2:   # ResNet-18-shaped sweep, R = C/4
@@ -85,7 +86,11 @@ def config_layers(config_id: int) -> List[Layer]:
                 else:
                     out.append(Layer(1, c, c, hw, hw, r, r))
         return out
-    raise ValueError("config_id must be 1..5")
+    if config_id == 6:   # throughput regime: every compute unit gets work
+        return [Layer(32, 128, 256, 56, 56, 32, 64, 3, 2, 1), Layer(32, 128, 128, 28, 28, 32, 32),
+                Layer(32, 256, 256, 14, 14, 64, 64), Layer(128, 256, 256, 14, 14, 64, 64),
+                Layer(128, 128, 128, 28, 28, 32, 32), Layer(64, 128, 256, 56, 56, 32, 64, 3, 2, 1)]
+    raise ValueError("config_id must be 1..6")
 
 
 def layer_seed(config_id: int, layer_index: int) -> int:

@@ -92,7 +92,7 @@ def test_validation_happens_before_any_device_call():
 
 
 def test_selector_fills_a_launchable_tuning_for_every_workload():
-    for cfg in range(1, 6):
+    for cfg in range(1, 7):
         for L in config_layers(cfg):
             t = B.tdc_select_tuning(B.make_shape(**L.asdict()))
             n = B.tdc_select_tuning(B.make_shape(**L.asdict(), layout=B.LAYOUT_NHWC)).as_dict()
