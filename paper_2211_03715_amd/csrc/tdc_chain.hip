@@ -36,10 +36,11 @@ struct ChainArgs {
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
     int mb1;                // stage-1 register tile height (1, 2 or 4 channel blocks)
     int QH, RPR, n_sb;      // run-major stage 1: tile rows, runs per row, 64-pixel blocks of runs
-    TdcDiv div_RPR, div_nsb;
+    TdcDiv div_RPR;
     int vec;                // 1: tile width, image width and tile origin are multiples of 4 -> 16-byte stores
     TdcEpi epi;
-    TdcDiv div_tiles_x, div_QW, div_TW, div_npg1;   // launch-time constant divisors (npg1: stage-1 pixel groups)
+    TdcDiv div_tiles_x, div_QW, div_TW;   // launch-time constant divisors
+    unsigned inv_mg1;       // ceil(2^20 / (NB1 / mb1)): divides a stage-1 unit index by the channel groups
 };
 
 __device__ __forceinline__ void tdc_buf_store(tdc_rsrc r, unsigned byte_off, float v)
@@ -63,8 +64,8 @@ __device__ __forceinline__ void chain_stage1(const ChainArgs &a, tdc_f4 *__restr
     sg.x_img = a.x + (size_t)b * a.C * a.H * a.W; sg.uin_p = a.uin_p;
     sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
     sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
-    sg.div_QW = a.div_QW; sg.div_npg = a.div_npg1;
-    sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR; sg.div_nsb = a.div_nsb;
+    sg.div_QW = a.div_QW; sg.inv_mg = a.inv_mg1;
+    sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR;
     const tdc_f4 *__restrict__ core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
     const tdc_f4 *__restrict__ uout4 = reinterpret_cast<const tdc_f4 *>(a.uout_p);
     const auto stage1 = [&](auto &s1) {
@@ -106,8 +107,8 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
     TDC_FETCH_NOW(TDC_OUTS("+s"(bd), "+s"(div_tiles_x.m)), "s"(a.x), "s"(a.uin_p), "s"(a.core_p), "s"(a.uout_p), "s"(a.y), "s"(a.C), "s"(a.H), "s"(a.W),
                   "s"(a.stride), "s"(a.pad), "s"(a.NB1), "s"(a.KG1), "s"(a.TH), "s"(a.TW), "s"(a.QW), "s"(a.Q), "s"(a.QB), "s"(a.tiles_x),
                   "s"(a.pitch1), "s"(a.w_core4), "s"(a.w_uout4), "s"(a.QH), "s"(a.RPR), "s"(a.n_sb), "s"(a.div_RPR.m), "s"(a.div_RPR.sh1),
-                  "s"(a.div_RPR.sh2), "s"(a.div_nsb.m), "s"(a.div_nsb.sh1), "s"(a.div_nsb.sh2), "s"(div_tiles_x.sh1), "s"(div_tiles_x.sh2),
-                  "s"(a.div_QW.m), "s"(a.div_QW.sh1), "s"(a.div_QW.sh2), "s"(a.div_npg1.m), "s"(a.div_npg1.sh1), "s"(a.div_npg1.sh2), "s"(a.mb1));
+                  "s"(a.div_RPR.sh2), "s"(div_tiles_x.sh1), "s"(div_tiles_x.sh2),
+                  "s"(a.div_QW.m), "s"(a.div_QW.sh1), "s"(a.div_QW.sh2), "s"(a.inv_mg1), "s"(a.mb1));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = (int)(bd >> 6);
     const int g = lane >> 4, l16 = lane & 15;
@@ -345,13 +346,14 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.QH = g.QH;
     a.RPR = tdc_runs_per_row(d.W, d.Wo, g.TW, d.K, d.stride, d.pad);
     a.n_sb = (g.QH * a.RPR + 15) / 16;
-    a.div_RPR = tdc_make_div((unsigned)a.RPR); a.div_nsb = tdc_make_div((unsigned)a.n_sb);
+    a.div_RPR = tdc_make_div((unsigned)a.RPR);
     const int lay = d.nhwc ? TDC_LAY_NHWC : d.s1_runs ? TDC_LAY_NCHW_RUNS : TDC_LAY_NCHW;
     // 16-byte stores of four consecutive pixels need rows of whole quads and a 16-byte aligned y (a slice of a larger
     // tensor may not be); otherwise the same values go out as four 4-byte stores
     a.vec = (g.TW % 4 == 0 && d.Wo % 4 == 0 && ((uintptr_t)y & 15u) == 0) ? 1 : 0;
     a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
-    a.div_TW = tdc_make_div((unsigned)g.TW); a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
+    a.div_TW = tdc_make_div((unsigned)g.TW);
+    a.inv_mg1 = ((1u << 20) + (unsigned)(d.NB1 / t.mb[0]) - 1u) / (unsigned)(d.NB1 / t.mb[0]);
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_LAUNCH(N_, P_, W_, L_)                                                                     \
     {                                                                                                  \

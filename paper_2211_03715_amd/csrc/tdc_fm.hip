@@ -36,9 +36,10 @@ struct FmArgs {
     int NBG, KS;            // output-channel blocks per workgroup, contraction slices
     int kg_q, kg_r;         // KG2 = KS * kg_q + kg_r: the first kg_r slices take kg_q + 1 k-groups
     TdcEpi epi;
-    TdcDiv div_tiles, div_tiles_x, div_NBG, div_QB, div_QW, div_TW, div_NB1, div_K;   // constant divisors
+    TdcDiv div_tiles, div_tiles_x, div_NBG, div_QW, div_TW, div_NB1, div_K;   // constant divisors
     int QH, RPR, n_sb;      // run-major stage 1: tile rows, runs per row, 64-pixel blocks of runs
-    TdcDiv div_RPR, div_nsb;
+    TdcDiv div_RPR;
+    unsigned inv_mg1;       // ceil(2^20 / (NB1 / mb1)): divides a stage-1 unit index by the channel groups
 };
 
 template <int MB1, int PBK, int LAY>
@@ -76,8 +77,8 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
         sg.x_img = a.x + (size_t)b * a.C * HW; sg.uin_p = a.uin_p;
         sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
         sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
-        sg.div_QW = a.div_QW; sg.div_npg = a.div_QB;
-        sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR; sg.div_nsb = a.div_nsb;
+        sg.div_QW = a.div_QW; sg.inv_mg = a.inv_mg1;
+        sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR;
         const auto stage1 = [&](auto &s1) {
             s1.prefetch();
             // The weight fragments of stage 2+3 go out right behind the first stage-1 operands: loads
@@ -251,13 +252,14 @@ hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGe
     const int kg2 = d.K * d.K * d.NB1;
     a.kg_q = kg2 / a.KS; a.kg_r = kg2 % a.KS;
     a.div_tiles = tdc_make_div((unsigned)a.tiles); a.div_tiles_x = tdc_make_div((unsigned)a.tiles_x);
-    a.div_NBG = tdc_make_div((unsigned)a.NBG); a.div_QB = tdc_make_div((unsigned)a.QB);
+    a.div_NBG = tdc_make_div((unsigned)a.NBG);
+    a.inv_mg1 = ((1u << 20) + (unsigned)(d.NB1 / t.mb[0]) - 1u) / (unsigned)(d.NB1 / t.mb[0]);
     a.div_QW = tdc_make_div((unsigned)a.QW); a.div_TW = tdc_make_div((unsigned)a.TW);
     a.div_NB1 = tdc_make_div((unsigned)a.NB1); a.div_K = tdc_make_div((unsigned)a.K);
     a.QH = g.QH;
     a.RPR = tdc_runs_per_row(d.W, d.Wo, g.TW, d.K, d.stride, d.pad);
     a.n_sb = (g.QH * a.RPR + 15) / 16;
-    a.div_RPR = tdc_make_div((unsigned)a.RPR); a.div_nsb = tdc_make_div((unsigned)a.n_sb);
+    a.div_RPR = tdc_make_div((unsigned)a.RPR);
     const int lay = d.nhwc ? TDC_LAY_NHWC : d.s1_runs ? TDC_LAY_NCHW_RUNS : TDC_LAY_NCHW;
     dim3 grid((unsigned)(a.tiles * (d.NB3 / a.NBG)), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_FM_LAUNCH(M_, P_, L_)                                                                  \

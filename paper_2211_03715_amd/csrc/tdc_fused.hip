@@ -45,9 +45,10 @@ struct FusedArgs {
     int pitch1, pitch2;     // LDS row pitches of the z1 / z2 tiles, in 16-byte units
     int w_core4, w_uout4;   // 16-byte units of the packed core / U_out arrays
     int QH, RPR, n_sb;      // run-major stage 1: tile rows, runs per row, 64-pixel blocks of runs
-    TdcDiv div_RPR, div_nsb;
+    TdcDiv div_RPR;
     TdcEpi epi;
-    TdcDiv div_tiles_x, div_QW, div_TW, div_npg1, div_npg2;   // launch-time constant divisors (pixel groups of stage 1 / stages 2, 3)
+    TdcDiv div_tiles_x, div_QW, div_TW, div_npg2;   // launch-time constant divisors (npg2: pixel groups of stages 2, 3)
+    unsigned inv_mg1;       // ceil(2^20 / (NB1 / mb1)): divides a stage-1 unit index by the channel groups
 };
 
 // LDS tiles hold 16-byte cells: cell (cb, g, col) = channels 16*cb + 4*g + {0,1,2,3} of pixel col,
@@ -71,8 +72,8 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
     TDC_FETCH_NOW(TDC_OUTS("+s"(bd), "+s"(div_tiles_x.m)), "s"(a.x), "s"(a.uin_p), "s"(a.core_p), "s"(a.uout_p), "s"(a.y), "s"(a.C), "s"(a.H), "s"(a.W),
                   "s"(a.stride), "s"(a.pad), "s"(a.NB1), "s"(a.KG1), "s"(a.TH), "s"(a.TW), "s"(a.QW), "s"(a.Q), "s"(a.QB), "s"(a.tiles_x),
                   "s"(a.pitch1), "s"(a.w_core4), "s"(a.w_uout4), "s"(a.QH), "s"(a.RPR), "s"(a.n_sb), "s"(a.div_RPR.m), "s"(a.div_RPR.sh1),
-                  "s"(a.div_RPR.sh2), "s"(a.div_nsb.m), "s"(a.div_nsb.sh1), "s"(a.div_nsb.sh2), "s"(div_tiles_x.sh1), "s"(div_tiles_x.sh2),
-                  "s"(a.div_QW.m), "s"(a.div_QW.sh1), "s"(a.div_QW.sh2), "s"(a.div_npg1.m), "s"(a.div_npg1.sh1), "s"(a.div_npg1.sh2));
+                  "s"(a.div_RPR.sh2), "s"(div_tiles_x.sh1), "s"(div_tiles_x.sh2),
+                  "s"(a.div_QW.m), "s"(a.div_QW.sh1), "s"(a.div_QW.sh2), "s"(a.inv_mg1));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = (int)(bd >> 6);
     const int g = lane >> 4, l16 = lane & 15;
@@ -88,8 +89,8 @@ __global__ __launch_bounds__(512) void tdc_fused_kernel(FusedArgs a)
         sg.x_img = a.x + (size_t)b * a.C * HW; sg.uin_p = a.uin_p;
         sg.C = a.C; sg.H = a.H; sg.W = a.W; sg.KG1 = a.KG1; sg.NB1 = a.NB1;
         sg.QB = a.QB; sg.Q = a.Q; sg.QW = a.QW; sg.h0 = h0; sg.w0 = w0; sg.pitch1 = a.pitch1;
-        sg.div_QW = a.div_QW; sg.div_npg = a.div_npg1;
-        sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR; sg.div_nsb = a.div_nsb;
+        sg.div_QW = a.div_QW; sg.inv_mg = a.inv_mg1;
+        sg.QH = a.QH; sg.RPR = a.RPR; sg.n_sb = a.n_sb; sg.div_RPR = a.div_RPR;
         const tdc_f4 *__restrict__ core4 = reinterpret_cast<const tdc_f4 *>(a.core_p);
         const tdc_f4 *__restrict__ uout4 = reinterpret_cast<const tdc_f4 *>(a.uout_p);
         const auto stage1 = [&](auto &s1) {
@@ -312,12 +313,12 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     a.w_uout4 = (int)(tdc_packed_floats_uout(d) / 4);
     a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
     a.div_TW = tdc_make_div((unsigned)g.TW);
-    a.div_npg1 = tdc_make_div((unsigned)((g.QB + t.pb[0] - 1) / t.pb[0]));
+    a.inv_mg1 = ((1u << 20) + (unsigned)(d.NB1 / t.mb[0]) - 1u) / (unsigned)(d.NB1 / t.mb[0]);
     a.div_npg2 = tdc_make_div((unsigned)((g.PBk + t.pb[0] - 1) / t.pb[0]));
     a.QH = g.QH;
     a.RPR = tdc_runs_per_row(d.W, d.Wo, g.TW, d.K, d.stride, d.pad);
     a.n_sb = (g.QH * a.RPR + 15) / 16;
-    a.div_RPR = tdc_make_div((unsigned)a.RPR); a.div_nsb = tdc_make_div((unsigned)a.n_sb);
+    a.div_RPR = tdc_make_div((unsigned)a.RPR);
     const int lay = d.nhwc ? TDC_LAY_NHWC : d.s1_runs ? TDC_LAY_NCHW_RUNS : TDC_LAY_NCHW;
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
 #define TDC_LAUNCH(A_, B_, C_, D_, W_, L_)                                                             \

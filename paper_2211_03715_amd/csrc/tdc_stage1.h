@@ -3,7 +3,9 @@
 // LDS cells.
 //
 // The tile's 16-pixel blocks and the 16-channel blocks of R1 are grouped into MB1 x PB register
-// tiles ("units") dealt round-robin to the wavefronts.  A wavefront treats ALL its units as one
+// tiles ("units") dealt round-robin to the wavefronts, the channel groups of one pixel group next to
+// each other: wavefronts that need the same pixels of x load them at the same time, so x comes from
+// HBM once however many channel groups there are.  A wavefront treats ALL its units as one
 // stream of k-groups: operands travel in two register buffers of U k-groups, the loads of one
 // buffer are issued before the MFMAs of the other, and the stream runs on across unit
 // boundaries -- the first operands of the next unit are already in flight while the last
@@ -23,10 +25,11 @@ struct TdcS1Geom {
     int QB, Q, QW;          // input tile: 16-pixel blocks, pixels, row length
     int h0, w0;             // image coordinates of the tile's first pixel (may be negative)
     int pitch1;             // z1 tile row pitch in LDS, in cells
-    TdcDiv div_QW, div_npg; // npg = ceil(QB / PB)
+    TdcDiv div_QW;
+    unsigned inv_mg;        // ceil(2^20 / (NB1 / MB1)), from the host: unit u = pixel group (u * inv_mg) >> 20, channel group the rest
     // run-major form (TdcStage1R): tile rows, aligned 4-pixel runs per row, 64-pixel blocks of runs
     int QH, RPR, n_sb;
-    TdcDiv div_RPR, div_nsb;
+    TdcDiv div_RPR;
 };
 
 template <int MB1, int PB, int U, bool NHWC>
@@ -35,6 +38,7 @@ struct TdcStage1 {
     tdc_rsrc xrs, urs;
     int lane, g, l16, wave, nw;
     int n_pg, n_units;
+    unsigned n_mg, inv_mg;  // channel groups and the multiplier that divides by them
     // fetch-side cursor: unit, k-group slot within the unit (dead at and beyond KG1), its channel group
     int fu, fkg, fmg, slots;
     unsigned xoff[PB];      // byte offset of this lane's pixel (NCHW: within a channel row), or TDC_OOB
@@ -47,7 +51,9 @@ struct TdcStage1 {
         xrs = tdc_make_rsrc(s.x_img, (unsigned)s.C * HW * 4u);
         urs = tdc_make_rsrc(s.uin_p, (unsigned)s.NB1 * s.KG1 * 1024u);
         n_pg = (s.QB + PB - 1) / PB;
-        n_units = n_pg * (s.NB1 / MB1);
+        n_mg = (unsigned)(s.NB1 / MB1);
+        n_units = n_pg * (int)n_mg;
+        inv_mg = s.inv_mg;
         slots = (s.KG1 + U - 1) / U * U;
         fu = wave;
         place();
@@ -58,8 +64,8 @@ struct TdcStage1 {
     {
         fkg = 0;
         const bool live = fu < n_units;
-        fmg = live ? tdc_div(fu, s.div_npg) : 0;
-        const int pg = fu - fmg * n_pg;
+        const int pg = live ? (int)(((unsigned)fu * inv_mg) >> 20) : 0;
+        fmg = live ? fu - pg * (int)n_mg : 0;
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
             const int q = 16 * (pg * PB + pb) + l16;
@@ -130,7 +136,7 @@ struct TdcStage1 {
         };
         const auto finish_buffer = [&]() {
             if (++cb < spu) return;
-            const int mg = tdc_div(cu, s.div_npg), pg = cu - mg * n_pg;
+            const int pg = (int)(((unsigned)cu * inv_mg) >> 20), mg = cu - pg * (int)n_mg;
 #pragma unroll
             for (int mb = 0; mb < MB1; ++mb)
 #pragma unroll
@@ -175,6 +181,7 @@ struct TdcStage1R {
     tdc_rsrc xrs, urs;
     int lane, g, l16, wave, nw;
     int n_units, wa;        // wa: image column of the first run of a row (a multiple of 4, >= 0)
+    unsigned n_mg, inv_mg;  // channel groups and the multiplier that divides by them
     int fu, fkg, fmg, slots;
     unsigned xoff;          // byte offset of this lane's run within a channel plane, or TDC_OOB
     tdc_f4 a0[U][MB1], a1[U][MB1], b0[U][4], b1[U][4];
@@ -185,7 +192,9 @@ struct TdcStage1R {
         const int HW = s.H * s.W;
         xrs = tdc_make_rsrc(s.x_img, (unsigned)s.C * HW * 4u);
         urs = tdc_make_rsrc(s.uin_p, (unsigned)s.NB1 * s.KG1 * 1024u);
-        n_units = s.n_sb * (s.NB1 / MB1);
+        n_mg = (unsigned)(s.NB1 / MB1);
+        n_units = s.n_sb * (int)n_mg;
+        inv_mg = s.inv_mg;
         slots = (s.KG1 + U - 1) / U * U;
         wa = s.w0 > 0 ? (s.w0 & ~3) : 0;
         fu = wave;
@@ -211,8 +220,8 @@ struct TdcStage1R {
     {
         fkg = 0;
         const bool live = fu < n_units;
-        fmg = live ? tdc_div(fu, s.div_nsb) : 0;
-        const int sb = fu - fmg * s.n_sb;
+        const int sb = live ? (int)(((unsigned)fu * inv_mg) >> 20) : 0;
+        fmg = live ? fu - sb * (int)n_mg : 0;
         const int rho = 16 * sb + l16;
         const int qh = tdc_div(rho, s.div_RPR), rc = rho - qh * s.RPR;
         const int h = s.h0 + qh, col = wa + 4 * rc;
@@ -272,7 +281,7 @@ struct TdcStage1R {
         };
         const auto finish_buffer = [&]() {
             if (++cb < spu) return;
-            const int mg = tdc_div(cu, s.div_nsb), sb = cu - mg * s.n_sb;
+            const int sb = (int)(((unsigned)cu * inv_mg) >> 20), mg = cu - sb * (int)n_mg;
             const int rho = 16 * sb + l16;
             const int qh = tdc_div(rho, s.div_RPR), rc = rho - qh * s.RPR;
             const int qw0 = wa + 4 * rc - s.w0;            // tile column of the run's first pixel (may be < 0)
