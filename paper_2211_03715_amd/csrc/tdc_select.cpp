@@ -287,10 +287,12 @@ FusedChoice best_chain(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tun
                 }
             }
         }
-    // NHWC: one channel block per stage-1 unit reads the input tile once per block (twice the HBM fetch measured at
-    // R1 = 32), and in every sweep timed two blocks per unit were 2-17 % faster than one at the same tile, which the
-    // fitted stage-1 terms do not reproduce: the choice of tile stands, the unit is widened afterwards.
-    if (!forced.mb[0] && d.nhwc && best.mb1 == 1 && d.NB1 % 2 == 0 && tdc_chain_supported(d.NB2, 2, best.pb)) best.mb1 = 2;
+    // One channel block per stage-1 unit issues the loads of the input tile once per block.  Two blocks per unit were
+    // 2-17 % faster at the same tile in every NHWC sweep timed, and in the NCHW ones from 64 output pixels per compute
+    // unit (below that, 12-16 % slower), which the fitted stage-1 terms do not reproduce: the choice of tile stands,
+    // the unit is widened afterwards.
+    const bool widen = d.nhwc || (long)d.B * d.Ho * d.Wo >= 64L * dev.cus;
+    if (!forced.mb[0] && widen && best.mb1 == 1 && d.NB1 % 2 == 0 && tdc_chain_supported(d.NB2, 2, best.pb)) best.mb1 = 2;
     return best;
 }
 
