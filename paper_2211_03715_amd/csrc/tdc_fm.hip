@@ -36,7 +36,8 @@ struct FmArgs {
     int NBG, KS;            // output-channel blocks per workgroup, contraction slices
     int kg_q, kg_r;         // KG2 = KS * kg_q + kg_r: the first kg_r slices take kg_q + 1 k-groups
     TdcEpi epi;
-    TdcDiv div_tiles, div_tiles_x, div_NBG, div_QW, div_TW, div_NB1, div_K;   // constant divisors
+    TdcDiv div_groups, div_tiles_x, div_NBG, div_QW, div_TW, div_NB1, div_K;   // constant divisors (groups: output-channel groups per tile)
+    int n_groups, xcd_per, xcd_rem;   // workgroups per XCD (and the remainder) of the id remap below
     int QH, RPR, n_sb;      // run-major stage 1: tile rows, runs per row, 64-pixel blocks of runs
     TdcDiv div_RPR;
     unsigned inv_mg1;       // ceil(2^20 / (NB1 / mb1)): divides a stage-1 unit index by the channel groups
@@ -52,12 +53,18 @@ __global__ __launch_bounds__(512) void tdc_fm_kernel(FmArgs a)
 
     TDC_PROBE(0);
     unsigned bd = blockDim.x;
-    TdcDiv div_tiles = a.div_tiles;
-    TDC_FETCH_NOW(TDC_OUTS("+s"(bd), "+s"(div_tiles.m)), "s"(a.x), "s"(a.uin_p), "s"(a.wm_p), "s"(div_tiles.sh1), "s"(div_tiles.sh2));
+    TdcDiv div_groups = a.div_groups;
+    TDC_FETCH_NOW(TDC_OUTS("+s"(bd), "+s"(div_groups.m)), "s"(a.x), "s"(a.uin_p), "s"(a.wm_p), "s"(div_groups.sh1), "s"(div_groups.sh2),
+                  "s"(a.n_groups), "s"(a.xcd_per), "s"(a.xcd_rem));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = (int)(bd >> 6);
     const int g = lane >> 4, l16 = lane & 15;
-    const int ng = tdc_div(blockIdx.x, div_tiles), tile = blockIdx.x - ng * a.tiles, b = blockIdx.y;
+    // Workgroup ids are dealt to the 8 XCDs round-robin, each with its own L2.  Give every XCD one contiguous range of
+    // logical ids and make the output-channel group the fast index: the groups of one pixel tile run on one XCD at the
+    // same time and pull that tile of x from HBM once instead of once per group.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int lb = xcd * a.xcd_per + min(xcd, a.xcd_rem) + slot;
+    const int tile = tdc_div(lb, div_groups), ng = lb - tile * a.n_groups, b = blockIdx.y;
     const int ty = tdc_div(tile, a.div_tiles_x), tx = tile - ty * a.tiles_x;
     const int i0 = ty * a.TH, j0 = tx * a.TW;
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;
@@ -251,7 +258,9 @@ hipError_t tdc_launch_fm(const TdcDims &d, const tdc_tuning &t, const TdcFusedGe
     a.NBG = t.mb[1]; a.KS = t.waves[0] / t.mb[1];
     const int kg2 = d.K * d.K * d.NB1;
     a.kg_q = kg2 / a.KS; a.kg_r = kg2 % a.KS;
-    a.div_tiles = tdc_make_div((unsigned)a.tiles); a.div_tiles_x = tdc_make_div((unsigned)a.tiles_x);
+    a.n_groups = d.NB3 / a.NBG;
+    a.div_groups = tdc_make_div((unsigned)a.n_groups); a.div_tiles_x = tdc_make_div((unsigned)a.tiles_x);
+    a.xcd_per = a.tiles * a.n_groups / 8; a.xcd_rem = a.tiles * a.n_groups % 8;
     a.div_NBG = tdc_make_div((unsigned)a.NBG);
     a.inv_mg1 = ((1u << 20) + (unsigned)(d.NB1 / t.mb[0]) - 1u) / (unsigned)(d.NB1 / t.mb[0]);
     a.div_QW = tdc_make_div((unsigned)a.QW); a.div_TW = tdc_make_div((unsigned)a.TW);
