@@ -39,7 +39,8 @@ struct ChainArgs {
     TdcDiv div_RPR;
     int vec;                // 1: tile width, image width and tile origin are multiples of 4 -> 16-byte stores
     TdcEpi epi;
-    TdcDiv div_tiles_x, div_QW, div_TW;   // launch-time constant divisors
+    TdcDiv div_tiles_x, div_QW, div_TW, div_tiles;   // launch-time constant divisors
+    int tiles, xcd_per, xcd_rem;   // tiles per image; workgroups per XCD (and the remainder) of the id remap
     unsigned inv_mg1;       // ceil(2^20 / (NB1 / mb1)): divides a stage-1 unit index by the channel groups
 };
 
@@ -108,11 +109,19 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(ChainArgs a)
                   "s"(a.stride), "s"(a.pad), "s"(a.NB1), "s"(a.KG1), "s"(a.TH), "s"(a.TW), "s"(a.QW), "s"(a.Q), "s"(a.QB), "s"(a.tiles_x),
                   "s"(a.pitch1), "s"(a.w_core4), "s"(a.w_uout4), "s"(a.QH), "s"(a.RPR), "s"(a.n_sb), "s"(a.div_RPR.m), "s"(a.div_RPR.sh1),
                   "s"(a.div_RPR.sh2), "s"(div_tiles_x.sh1), "s"(div_tiles_x.sh2),
-                  "s"(a.div_QW.m), "s"(a.div_QW.sh1), "s"(a.div_QW.sh2), "s"(a.inv_mg1), "s"(a.mb1));
+                  "s"(a.div_QW.m), "s"(a.div_QW.sh1), "s"(a.div_QW.sh2), "s"(a.inv_mg1), "s"(a.mb1), "s"(a.tiles), "s"(a.xcd_per),
+                  "s"(a.xcd_rem), "s"(a.div_tiles.m), "s"(a.div_tiles.sh1), "s"(a.div_tiles.sh2));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = (int)(bd >> 6);
     const int g = lane >> 4, l16 = lane & 15;
-    const int ty = tdc_div(blockIdx.x, div_tiles_x), tx = blockIdx.x - ty * a.tiles_x, b = blockIdx.y;
+    // Workgroups are dealt to the 8 XCDs round-robin in launch order (x fastest), each XCD with its own L2.  Every
+    // XCD gets one contiguous range of (image, tile) pairs instead, so the tiles that share halo rows and columns of x
+    // run on one XCD at the same time and those pixels come from HBM once.
+    const int lin = blockIdx.y * a.tiles + blockIdx.x;
+    const int xcd = lin & 7, slot = lin >> 3;
+    const int lb = xcd * a.xcd_per + min(xcd, a.xcd_rem) + slot;
+    const int b = tdc_div(lb, a.div_tiles), tile = lb - b * a.tiles;
+    const int ty = tdc_div(tile, div_tiles_x), tx = tile - ty * a.tiles_x;
     const int i0 = ty * a.TH, j0 = tx * a.TW;                   // first output pixel of the tile
     const int h0 = i0 * a.stride - a.pad, w0 = j0 * a.stride - a.pad;  // first input pixel (may be < 0)
 
@@ -352,6 +361,8 @@ hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFuse
     // tensor may not be); otherwise the same values go out as four 4-byte stores
     a.vec = (g.TW % 4 == 0 && d.Wo % 4 == 0 && ((uintptr_t)y & 15u) == 0) ? 1 : 0;
     a.div_tiles_x = tdc_make_div((unsigned)g.tiles_x); a.div_QW = tdc_make_div((unsigned)g.QW);
+    a.tiles = g.tiles_x * g.tiles_y; a.div_tiles = tdc_make_div((unsigned)a.tiles);
+    a.xcd_per = a.tiles * d.B / 8; a.xcd_rem = a.tiles * d.B % 8;
     a.div_TW = tdc_make_div((unsigned)g.TW);
     a.inv_mg1 = ((1u << 20) + (unsigned)(d.NB1 / t.mb[0]) - 1u) / (unsigned)(d.NB1 / t.mb[0]);
     dim3 grid((unsigned)(g.tiles_x * g.tiles_y), (unsigned)d.B), block(64 * t.waves[0]);
