@@ -405,6 +405,45 @@ def main():
                      "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / t_sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12,
                                   "unit": "TFLOP/s", "frac": R.flops(Lt) / t_sec / R.FP32_MFMA_PEAK}}
             ct.close()
+            # the same layer with four independent calls in flight: four plans, four sets of buffers, four streams
+            # (default priority; four, so that they land on four different hardware queues whatever streams this
+            # process made before), launched round-robin.  The next call's workgroups then start as those of the
+            # previous one finish and share compute units with them in different phases, which back-to-back launches
+            # on one stream (each waits for the last workgroup of the one before) cannot offer.
+            n_str = 4
+            streams = [torch.cuda.Stream() for _ in range(n_str)]
+            cs, ls, keep = [], [], []
+            for st in streams:
+                c = TuckerConv2d(Lt, 0, None, layout=layout)
+                c.pack(t["U_in"], t["core"], t["U_out"])
+                xs_, ys_ = xt.clone(), torch.empty_like(yt)
+                keep.append((xs_, ys_))
+                torch.cuda.synchronize()
+                ls.append(c.bind(xs_, ys_, stream=st.cuda_stream))
+                cs.append(c)
+
+            def rounds(n):
+                for _ in range(n):
+                    for l in ls:
+                        l()
+
+            rounds(30)
+            torch.cuda.synchronize()
+            per_call = []
+            for _ in range(5):
+                t0 = time.perf_counter()
+                rounds(100)
+                torch.cuda.synchronize()
+                per_call.append((time.perf_counter() - t0) / (100 * n_str))
+            per_call.sort()
+            c_sec = per_call[len(per_call) // 2]
+            entry["concurrent"] = {"streams": n_str, "us_per_call": c_sec * 1e6, "us_per_call_min": per_call[0] * 1e6,
+                                   "us_per_call_max": per_call[-1] * 1e6,
+                                   "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / c_sec / 1e12,
+                                                "peak": R.FP32_MFMA_PEAK / 1e12, "unit": "TFLOP/s",
+                                                "frac": R.flops(Lt) / c_sec / R.FP32_MFMA_PEAK}}
+            for c in cs:
+                c.close()
             return entry
 
         regime = [throughput(Lt, layer_seed(6, j)) for j, Lt in enumerate(config_layers(6))]

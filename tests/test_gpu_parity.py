@@ -373,6 +373,43 @@ def test_two_plans_on_two_streams(orc):
             conv.close()
 
 
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
+def test_three_calls_in_flight_at_full_size(orc, layout):
+    """The configuration bench.py's `concurrent` figures time: three plans of one batch-32 layer (selector's choice, the
+    one-launch kernels) on three streams, launched round-robin so that their workgroups share compute units; every
+    call's output against the oracle on its own input."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    dev = torch.device("cuda:0")
+    layer = Layer(32, 128, 128, 28, 28, 32, 32)
+    _announce("three streams", layer.name(), "layout", layout)
+    base = make_inputs(layer, 77)
+    w = {k: torch.from_numpy(base[k]).to(dev) for k in ("U_in", "core", "U_out")}
+    cases = []
+    for seed in (78, 79, 80):
+        inputs = dict(base, x=make_inputs(layer, seed)["x"])
+        want = _oracle(orc, layer, inputs)
+        x = torch.from_numpy(inputs["x"]).to(dev)
+        if layout == B.LAYOUT_NHWC:
+            x, want = x.permute(0, 2, 3, 1).contiguous(), np.ascontiguousarray(np.transpose(want, (0, 2, 3, 1)))
+        conv = TuckerConv2d(layer, 0, None, layout=layout)
+        conv.pack(w["U_in"], w["core"], w["U_out"])
+        y = torch.full(conv.out_shape(), float("nan"), device=dev)
+        stream = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        cases.append((conv, conv.bind(x, y, stream=stream.cuda_stream), x, y, want, stream))
+    try:
+        for _ in range(30):
+            for _, launch, *_ in cases:
+                launch()
+        for conv, _, _, y, want, stream in cases:
+            stream.synchronize()
+            assert_parity(y.cpu().numpy(), want, conv.describe())
+    finally:
+        for conv, *_ in cases:
+            conv.close()
+
+
 def test_error_paths_on_device():
     import ctypes
     import torch
