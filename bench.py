@@ -405,45 +405,52 @@ def main():
                      "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / t_sec / 1e12, "peak": R.FP32_MFMA_PEAK / 1e12,
                                   "unit": "TFLOP/s", "frac": R.flops(Lt) / t_sec / R.FP32_MFMA_PEAK}}
             ct.close()
-            # the same layer with four independent calls in flight: four plans, four sets of buffers, four streams
-            # (default priority; four, so that they land on four different hardware queues whatever streams this
-            # process made before), launched round-robin.  The next call's workgroups then start as those of the
-            # previous one finish and share compute units with them in different phases, which back-to-back launches
-            # on one stream (each waits for the last workgroup of the one before) cannot offer.
-            n_str = 4
-            streams = [torch.cuda.Stream() for _ in range(n_str)]
-            cs, ls, keep = [], [], []
-            for st in streams:
-                c = TuckerConv2d(Lt, 0, None, layout=layout)
-                c.pack(t["U_in"], t["core"], t["U_out"])
-                xs_, ys_ = xt.clone(), torch.empty_like(yt)
-                keep.append((xs_, ys_))
-                torch.cuda.synchronize()
-                ls.append(c.bind(xs_, ys_, stream=st.cuda_stream))
-                cs.append(c)
+            # the same layer with several independent calls in flight: one plan, one set of buffers and one stream
+            # (default priority) per call, launched round-robin.  The next call's workgroups then start as those of
+            # the previous one finish and share compute units with them in different phases, which back-to-back
+            # launches on one stream (each waits for the last workgroup of the one before) cannot offer.  Timed with
+            # 2, 3 and 4 calls in flight, each on fresh streams: which hardware queue (4 per process) a stream lands on
+            # depends on the streams the process made before, and two streams on one queue serialise; the best of the
+            # three is reported with its count, all three are listed.
+            def in_flight(n_str):
+                streams = [torch.cuda.Stream() for _ in range(n_str)]
+                cs, ls, keep = [], [], []
+                for st in streams:
+                    c = TuckerConv2d(Lt, 0, None, layout=layout)
+                    c.pack(t["U_in"], t["core"], t["U_out"])
+                    xs_, ys_ = xt.clone(), torch.empty_like(yt)
+                    keep.append((xs_, ys_))
+                    torch.cuda.synchronize()
+                    ls.append(c.bind(xs_, ys_, stream=st.cuda_stream))
+                    cs.append(c)
 
-            def rounds(n):
-                for _ in range(n):
-                    for l in ls:
-                        l()
+                def rounds(n):
+                    for _ in range(n):
+                        for l in ls:
+                            l()
 
-            rounds(30)
-            torch.cuda.synchronize()
-            per_call = []
-            for _ in range(5):
-                t0 = time.perf_counter()
-                rounds(100)
+                rounds(30)
                 torch.cuda.synchronize()
-                per_call.append((time.perf_counter() - t0) / (100 * n_str))
-            per_call.sort()
-            c_sec = per_call[len(per_call) // 2]
-            entry["concurrent"] = {"streams": n_str, "us_per_call": c_sec * 1e6, "us_per_call_min": per_call[0] * 1e6,
-                                   "us_per_call_max": per_call[-1] * 1e6,
+                per_call = []
+                for _ in range(5):
+                    t0 = time.perf_counter()
+                    rounds(100)
+                    torch.cuda.synchronize()
+                    per_call.append((time.perf_counter() - t0) / (100 * n_str))
+                for c in cs:
+                    c.close()
+                per_call.sort()
+                return per_call
+
+            tried = {n: in_flight(n) for n in (2, 3, 4)}
+            n_best = min(tried, key=lambda n: tried[n][2])
+            c_sec = tried[n_best][2]
+            entry["concurrent"] = {"streams": n_best, "us_per_call": c_sec * 1e6, "us_per_call_min": tried[n_best][0] * 1e6,
+                                   "us_per_call_max": tried[n_best][-1] * 1e6,
+                                   "us_per_call_by_streams": {str(n): v[2] * 1e6 for n, v in tried.items()},
                                    "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / c_sec / 1e12,
                                                 "peak": R.FP32_MFMA_PEAK / 1e12, "unit": "TFLOP/s",
                                                 "frac": R.flops(Lt) / c_sec / R.FP32_MFMA_PEAK}}
-            for c in cs:
-                c.close()
             return entry
 
         regime = [throughput(Lt, layer_seed(6, j)) for j, Lt in enumerate(config_layers(6))]
