@@ -15,12 +15,18 @@ weights already resident in HBM.  Prints ONE JSON line.
                x / y buffers, so no activation is found in a cache), GFLOP/s, the fraction of the
                layer's roofline max(bytes/8 TB/s, flops/157.3 TFLOP/s), dense_conv_us (this
                library's kernel for the undecomposed K x K layer, timed the same way) and oracle_us
-               (the CPU oracle's three-stage and dense paths, all host threads and one thread)
-  roofline     the same for the dominant (slowest) layer's kernel
+               (the CPU oracle's three-stage and dense paths, all host threads and one thread),
+               achieved_hbm_gbs (compulsory bytes over the cold-cache latency), traffic_bytes (see roofline)
+  roofline     the same for the dominant (slowest) layer's kernel; traffic = HBM bytes per call measured with
+               rocprofv3 for exactly this plan, looked up in profiles/traffic.txt (null for a plan not profiled)
   null_launch_us  an empty kernel timed the same way: the floor any batch-1 layer sits on
   throughput_regime  the batch-32 128->256 stride-2 layer (config 4) timed the same way, against the
                fp32 MFMA peak: a side figure, not part of value; throughput_layers lists it with the
-               other batched layers (28x28 and 14x14 at batch 32 and 128, the stride-2 layer at batch 64)
+               other batched layers (28x28 and 14x14 at batch 32 and 128, the stride-2 layer at batch 64); each
+               carries `concurrent`: time per call with 2 / 3 / 4 independent calls in flight on as many streams
+  resnet50_body  the 16 bottleneck blocks (65 kernels) of a ResNet-50-shaped network at batch 1, eagerly and as
+               one HIP graph, NCHW and NHWC
+  graph_replay_us_per_step  the step replayed from a HIP graph (--graph-study explains the difference to eager)
   cpu_baseline the CPU oracle (three-stage, fp64) timed on the host cores on the same sweep
 """
 from __future__ import annotations

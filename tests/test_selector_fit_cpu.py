@@ -110,3 +110,29 @@ def test_coefficient_header_round_trip(lib, tmp_path):
     after = A.read_coefficients(str(copy))
     assert after["chain"] == pytest.approx(fake["chain"]["coef"])
     assert after["stage"] == before["stage"] and after["fused_latency"] == before["fused_latency"]
+
+
+def test_model_terms_error_paths(lib):
+    import ctypes
+    raw = B.load()
+    shape = B.make_shape(batch=32, C=128, N=128, H=28, W=28, R1=32, R2=32, K=3, stride=1, pad=1)
+    pick = B.tdc_select_tuning(shape)
+    terms = (ctypes.c_double * 64)()
+    names = (ctypes.c_char_p * 64)()
+    n, model = ctypes.c_int(0), ctypes.c_char_p()
+    ok = raw.tdc_model_terms(ctypes.byref(shape), ctypes.byref(pick), 256, 160 * 1024, terms, names, 64, ctypes.byref(n), ctypes.byref(model))
+    assert ok == B.TDC_OK and n.value > 0 and model.value in (b"chain", b"fused_throughput")
+    assert [names[i] for i in range(n.value)][0] == b"launch"
+    # names and model are optional
+    assert raw.tdc_model_terms(ctypes.byref(shape), ctypes.byref(pick), 256, 160 * 1024, terms, None, 64, ctypes.byref(n), None) == B.TDC_OK
+    # too few slots, missing pointers, a tuning that names no kernel, a device that cannot exist
+    assert raw.tdc_model_terms(ctypes.byref(shape), ctypes.byref(pick), 256, 160 * 1024, terms, names, 3, ctypes.byref(n), None) == B.TDC_ERR_BAD_SHAPE
+    assert raw.tdc_model_terms(None, ctypes.byref(pick), 256, 160 * 1024, terms, names, 64, ctypes.byref(n), None) == B.TDC_ERR_NULL
+    assert raw.tdc_model_terms(ctypes.byref(shape), ctypes.byref(pick), 256, 160 * 1024, None, names, 64, ctypes.byref(n), None) == B.TDC_ERR_NULL
+    auto = B.make_tuning(variant=B.VARIANT_AUTO)
+    assert raw.tdc_model_terms(ctypes.byref(shape), ctypes.byref(auto), 256, 160 * 1024, terms, names, 64, ctypes.byref(n), None) == B.TDC_ERR_BAD_TUNING
+    assert raw.tdc_model_terms(ctypes.byref(shape), ctypes.byref(pick), 0, 160 * 1024, terms, names, 64, ctypes.byref(n), None) == B.TDC_ERR_BAD_TUNING
+    # a tile the LDS cannot hold is refused like in tdc_plan_create
+    big = B.make_tuning(variant=B.VARIANT_CHAIN, tile_h=16, tile_w=32, waves=(8, 8, 8), mb=(1, 1, 1), pb=(1, 1, 1))
+    wide = B.make_shape(batch=1, C=512, N=512, H=64, W=64, R1=256, R2=128, K=3, stride=1, pad=1)
+    assert raw.tdc_model_terms(ctypes.byref(wide), ctypes.byref(big), 256, 64 * 1024, terms, names, 64, ctypes.byref(n), None) == B.TDC_ERR_BAD_TUNING
