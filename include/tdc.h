@@ -227,12 +227,6 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
 int tdc_model_terms(const tdc_shape *shape, const tdc_tuning *tuning, int compute_units, int lds_bytes,
                     double *terms, const char **names, int max_terms, int *n_terms, const char **model);
 
-/* Measurement aid: enqueue one empty kernel (a single wavefront that does nothing) on the stream,
- * so that a harness can report the launch floor next to per-layer latencies, which at batch 1
- * are of the same order (the paper, section 6, also notes that launch time of the extra 1x1
- * kernels can outweigh the saved FLOPs). */
-int tdc_launch_null(void *hip_stream);
-
 /* Hardware-aware rank selection, host only (paper section 6; first step of Algorithm 1).
  * For each layer, in the order given: among the entries of its measured latency table whose Tucker
  * MACs  P = H*W*C*R1 + Ho*Wo*K*K*R1*R2 + Ho*Wo*N*R2  (section 3; batch included) respect the FLOPs

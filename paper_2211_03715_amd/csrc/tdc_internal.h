@@ -22,6 +22,7 @@
 #include <stdint.h>
 
 #include "tdc.h"
+#include "tdc_measure.h"
 
 // Optional output epilogue, applied as the last kernel stores y:
 //   y = acc + bias[n] + residual[same element as y], then max(., 0) if relu.

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "tdc.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(tdc_[a-z0-9_]+)\s*\(", text)))
 
@@ -24,7 +25,7 @@ def test_header_symbols_are_exported_and_bound():
     assert "tdc_conv_tucker2" in names and "tdc_plan_create" in names and "tdc_plan_destroy" in names
     for n in names:
         assert hasattr(lib, n), "libtdc.so does not export %s" % n
-    assert sorted(B.EXPORTS) == names, "binding.EXPORTS and include/tdc.h disagree"
+    assert sorted(B.EXPORTS) == names, "binding.EXPORTS and include/*.h disagree"
     for n in names:
         assert hasattr(B, n), "binding has no wrapper named %s" % n
 
