@@ -552,7 +552,10 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     if (forced.variant == TDC_VARIANT_AUTO && chain_pays) {
         tdc_tuning free_choice = forced;
         const FusedChoice c = best_chain(d, dev, free_choice);
-        if (c.us < f.us) {
+        // The two tables are fitted separately, and where the estimates are close FUSED's is the optimistic one (its
+        // measured best lies 8-15 % further behind CHAIN's than estimated on the NCHW layers of the sweeps): FUSED has to
+        // win by 7 %.
+        if (0.93 * c.us < f.us) {
             t->variant = TDC_VARIANT_CHAIN;
             t->tile_h = c.th; t->tile_w = c.tw;
             t->waves[0] = t->waves[1] = t->waves[2] = c.nw;

@@ -8,7 +8,7 @@
 // fused, latency regime: launch s1_unit s1_kg s1_mfma s1r_unit s1r_kg s1r_mfma s2_kg_lds s2_kg_glb s2_mfma s3_unit s3_kg_lds s3_kg_glb s3_mfma w_kb x_mb_nchw x_mb_nhwc x_mb_runs y_mb_nchw y_mb_nhwc x_rows y_rows
 static const double kFusedLatencyCoef[22] = {3.5583, 1.2599, 0.0435, 0.0751, 0, 0, 0, 0.0186, 0.0356, 0, 0.3151, 0.0806, 0.0875, 0.2474, 0.0340, 0, 0, 0, 0, 0, 0, 0};
 // fused, throughput regime: same terms
-static const double kFusedThroughputCoef[22] = {3.5123, 0, 0.1115, 0.0341, 0.0252, 0.3487, 0.0031, 0.0431, 0.0854, 0.0200, 0.1737, 0.0333, 0.0021, 0.1422, 0.0217, 18.0504, 8.2973, 14.7543, 45.5832, 38.7019, 0, 2.7232};
+static const double kFusedThroughputCoef[22] = {3.8605, 0, 0.0988, 0.0347, 0.6828, 0.1891, 0.0176, 0.0560, 0.0826, 0.0210, 0.1531, 0.0330, 0.0167, 0.1457, 0.0207, 19.2123, 11.7344, 6.1081, 48.2178, 30.6810, 0.2834, 0.4272};
 // chain: launch s1_unit s1_kg s1_mfma s1r_unit s1r_kg s1r_mfma kg2_lds kg2_glb blk2 nb3_lds blk3 w_kb x_mb_nchw x_mb_nhwc x_mb_runs y_mb x_rows y_rows novec
 static const double kChainCoef[20] = {3.6918, 0.5859, 0.0211, 0.0906, 0.2783, 0.3798, 0.0096, 0.0298, 0.2335, 0.0141, 0.2690, 0.0402, 0.0235, 6.4658, 0, 15.9944, 32.4026, 0.2683, 2.9056, 0.1707};
 // fused-merged: launch s1_unit s1_kg s1_mfma frag reduce x_mb_nchw x_mb_nhwc wgs
