@@ -98,7 +98,7 @@ hipError_t tdc_launch_fused(const TdcDims &d, const tdc_tuning &t, const TdcFuse
                             const float *x, const float *uin_p, const float *core_p,
                             const float *uout_p, float *y, const TdcEpi &epi, bool prepare_only = false);
 
-// ---- fused MFMA kernel with stages 2 and 3 chained in registers (tdc_chain.hip)
+// ---- fused MFMA kernel with stages 2 and 3 chained in registers (tdc_chain.hip, kernel in tdc_chain_kernel.h)
 bool tdc_chain_supported(int nb2, int mb1, int pb);
 TdcFusedGeom tdc_chain_geometry(const TdcDims &d, int tile_h, int tile_w, int nw, int pb, int lds_limit);
 hipError_t tdc_launch_chain(const TdcDims &d, const tdc_tuning &t, const TdcFusedGeom &g, hipStream_t s,

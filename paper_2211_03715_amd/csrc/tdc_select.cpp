@@ -211,7 +211,9 @@ void chain_terms(double (&f)[C_TERMS], const TdcDims &d, const TdcDeviceInfo &de
     const bool wl = g.weights_fit;
     const size_t w_bytes = (size_t)(d.NB2 * KG2 + d.NB3 * d.NB2) * 1024;
     const size_t lds_as_staged = g.lds_bytes + (g.weights_fit && !g.weights_in_lds ? w_bytes : 0);
-    const int resident = resident_wgs(dev, lds_as_staged, nw, 2);   // 170-250 registers: two wavefronts per SIMD
+    // two wavefronts per SIMD: what the instances needed when the table was fitted (they hold three or four since the
+    // stage-1 width became a template parameter; the coefficients absorb the difference)
+    const int resident = resident_wgs(dev, lds_as_staged, nw, 2);
     const int per_cu = (int)std::min<long>(resident, (wgs + dev.cus - 1) / dev.cus);
     *cu_waves = per_cu * nw;
     const double rounds = std::ceil((double)wgs / ((double)dev.cus * resident));
