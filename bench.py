@@ -415,14 +415,19 @@ def main():
             # (default priority) per call, launched round-robin.  The next call's workgroups then start as those of
             # the previous one finish and share compute units with them in different phases, which back-to-back
             # launches on one stream (each waits for the last workgroup of the one before) cannot offer.  Timed with
-            # 2, 3 and 4 calls in flight, each on fresh streams: which hardware queue (4 per process) a stream lands on
-            # depends on the streams the process made before, and two streams on one queue serialise; the best of the
-            # three is reported with its count, all three are listed.
-            def in_flight(n_str):
+            # 2, 3 and 4 calls in flight, each on fresh streams (which hardware queue, 4 per process, a stream lands on
+            # depends on the streams the process made before, and two streams on one queue serialise), and with plans
+            # chosen for the whole chip (the default) and for half of it (tdc_select_tuning with half the compute
+            # units: a call that shares the GPU is better off with fewer, larger workgroups).  The best of the six is
+            # reported with its settings, all six are listed.
+            shape_t = B.make_shape(**Lt.asdict(), layout=layout)
+
+            def in_flight(n_str, share):
                 streams = [torch.cuda.Stream() for _ in range(n_str)]
                 cs, ls, keep = [], [], []
                 for st in streams:
-                    c = TuckerConv2d(Lt, 0, None, layout=layout)
+                    tun = B.tdc_select_tuning(shape_t, compute_units=256 // share) if share > 1 else None
+                    c = TuckerConv2d(Lt, 0, tun, layout=layout)
                     c.pack(t["U_in"], t["core"], t["U_out"])
                     xs_, ys_ = xt.clone(), torch.empty_like(yt)
                     keep.append((xs_, ys_))
@@ -443,17 +448,18 @@ def main():
                     rounds(100)
                     torch.cuda.synchronize()
                     per_call.append((time.perf_counter() - t0) / (100 * n_str))
+                plan = cs[0].describe()
                 for c in cs:
                     c.close()
                 per_call.sort()
-                return per_call
+                return per_call, plan
 
-            tried = {n: in_flight(n) for n in (2, 3, 4)}
-            n_best = min(tried, key=lambda n: tried[n][2])
-            c_sec = tried[n_best][2]
-            entry["concurrent"] = {"streams": n_best, "us_per_call": c_sec * 1e6, "us_per_call_min": tried[n_best][0] * 1e6,
-                                   "us_per_call_max": tried[n_best][-1] * 1e6,
-                                   "us_per_call_by_streams": {str(n): v[2] * 1e6 for n, v in tried.items()},
+            tried = {(n, sh): in_flight(n, sh) for sh in (1, 2) for n in (2, 3, 4)}
+            k_best = min(tried, key=lambda k: tried[k][0][2])
+            (pc, plan_best), c_sec = tried[k_best], tried[k_best][0][2]
+            entry["concurrent"] = {"streams": k_best[0], "planned_for_chip_share": "1/%d" % k_best[1], "plan": plan_best,
+                                   "us_per_call": c_sec * 1e6, "us_per_call_min": pc[0] * 1e6, "us_per_call_max": pc[-1] * 1e6,
+                                   "us_per_call_by_streams_and_share": {"%d streams, 1/%d" % k: v[0][2] * 1e6 for k, v in tried.items()},
                                    "roofline": {"bound": "mfma", "achieved": R.flops(Lt) / c_sec / 1e12,
                                                 "peak": R.FP32_MFMA_PEAK / 1e12, "unit": "TFLOP/s",
                                                 "frac": R.flops(Lt) / c_sec / R.FP32_MFMA_PEAK}}

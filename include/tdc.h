@@ -212,7 +212,10 @@ int tdc_version(void);
 
 /* The selector by itself (host only, touches no device): fill every zero field of *inout for a
  * device with `compute_units` CUs and `lds_bytes` of LDS per workgroup.  This is the a-priori
- * model tdc_plan_create uses; see tdc_select.cpp for its terms. */
+ * model tdc_plan_create uses; see tdc_select.cpp for its terms.  A caller that keeps k independent calls
+ * in flight on k streams can ask for a tuning for compute_units / k and hand it to tdc_plan_create_tuned:
+ * fewer, larger workgroups per call then leave room for the other calls (measured: up to 20 % more
+ * throughput at batch 32 than k plans made for the whole chip). */
 int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, tdc_tuning *inout);
 
 /* The selector's estimate, opened up for calibration (host only, touches no device).  The estimate of a tuning is a

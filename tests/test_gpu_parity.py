@@ -373,11 +373,12 @@ def test_two_plans_on_two_streams(orc):
             conv.close()
 
 
+@pytest.mark.parametrize("share", [1, 2], ids=["planned_for_the_chip", "planned_for_half_the_chip"])
 @pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
-def test_three_calls_in_flight_at_full_size(orc, layout):
-    """The configuration bench.py's `concurrent` figures time: three plans of one batch-32 layer (selector's choice, the
-    one-launch kernels) on three streams, launched round-robin so that their workgroups share compute units; every
-    call's output against the oracle on its own input."""
+def test_three_calls_in_flight_at_full_size(orc, layout, share):
+    """The configuration bench.py's `concurrent` figures time: three plans of one batch-32 layer (the selector's choice
+    for the whole chip or for half of its compute units, the one-launch kernels) on three streams, launched round-robin
+    so that their workgroups share compute units; every call's output against the oracle on its own input."""
     import torch
     from paper_2211_03715_amd.layer import TuckerConv2d
     dev = torch.device("cuda:0")
@@ -392,7 +393,8 @@ def test_three_calls_in_flight_at_full_size(orc, layout):
         x = torch.from_numpy(inputs["x"]).to(dev)
         if layout == B.LAYOUT_NHWC:
             x, want = x.permute(0, 2, 3, 1).contiguous(), np.ascontiguousarray(np.transpose(want, (0, 2, 3, 1)))
-        conv = TuckerConv2d(layer, 0, None, layout=layout)
+        tuning = B.tdc_select_tuning(B.make_shape(**layer.asdict(), layout=layout), compute_units=256 // share) if share > 1 else None
+        conv = TuckerConv2d(layer, 0, tuning, layout=layout)
         conv.pack(w["U_in"], w["core"], w["U_out"])
         y = torch.full(conv.out_shape(), float("nan"), device=dev)
         stream = torch.cuda.Stream()
