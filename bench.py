@@ -421,12 +421,13 @@ def main():
             # units: a call that shares the GPU is better off with fewer, larger workgroups).  The best of the six is
             # reported with its settings, all six are listed.
             shape_t = B.make_shape(**Lt.asdict(), layout=layout)
+            n_cus = torch.cuda.get_device_properties(dev).multi_processor_count
 
             def in_flight(n_str, share):
                 streams = [torch.cuda.Stream() for _ in range(n_str)]
                 cs, ls, keep = [], [], []
                 for st in streams:
-                    tun = B.tdc_select_tuning(shape_t, compute_units=256 // share) if share > 1 else None
+                    tun = B.tdc_select_tuning(shape_t, compute_units=n_cus // share) if share > 1 else None
                     c = TuckerConv2d(Lt, 0, tun, layout=layout)
                     c.pack(t["U_in"], t["core"], t["U_out"])
                     xs_, ys_ = xt.clone(), torch.empty_like(yt)

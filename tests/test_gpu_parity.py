@@ -393,7 +393,7 @@ def test_three_calls_in_flight_at_full_size(orc, layout, share):
         x = torch.from_numpy(inputs["x"]).to(dev)
         if layout == B.LAYOUT_NHWC:
             x, want = x.permute(0, 2, 3, 1).contiguous(), np.ascontiguousarray(np.transpose(want, (0, 2, 3, 1)))
-        tuning = B.tdc_select_tuning(B.make_shape(**layer.asdict(), layout=layout), compute_units=256 // share) if share > 1 else None
+        tuning = B.tdc_select_tuning(B.make_shape(**layer.asdict(), layout=layout), compute_units=torch.cuda.get_device_properties(dev).multi_processor_count // share) if share > 1 else None
         conv = TuckerConv2d(layer, 0, tuning, layout=layout)
         conv.pack(w["U_in"], w["core"], w["U_out"])
         y = torch.full(conv.out_shape(), float("nan"), device=dev)
