@@ -144,12 +144,15 @@ int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
         if (t.tile_h < 1 || t.tile_w < 1 || t.tile_h * t.tile_w > 4096) return TDC_ERR_BAD_TUNING;
         if (!tdc_fused_unit_supported(t.mb[0], t.mb[1], t.mb[2], t.pb[0])) return TDC_ERR_BAD_TUNING;
         if ((long)p.geom.lds_bytes > dev.lds_per_wg) return TDC_ERR_BAD_TUNING;
+        // the kernels number their workgroups over the whole grid, batch included, in 32-bit arithmetic
+        if ((long long)p.geom.tiles_x * p.geom.tiles_y * p.dims.B > 0x7fffffffLL) return TDC_ERR_BAD_TUNING;
         return TDC_OK;
     }
     if (t.variant == TDC_VARIANT_CHAIN) {
         if (t.tile_h < 1 || t.tile_w < 1 || t.tile_h * t.tile_w > 4096) return TDC_ERR_BAD_TUNING;
         if (!tdc_chain_supported(p.dims.NB2, t.mb[0], t.pb[0])) return TDC_ERR_BAD_TUNING;
         if ((long)p.geom.lds_bytes > dev.lds_per_wg) return TDC_ERR_BAD_TUNING;
+        if ((long long)p.geom.tiles_x * p.geom.tiles_y * p.dims.B > 0x7fffffffLL) return TDC_ERR_BAD_TUNING;
         return TDC_OK;
     }
     return TDC_ERR_BAD_TUNING;
