@@ -412,6 +412,72 @@ def test_three_calls_in_flight_at_full_size(orc, layout, share):
             conv.close()
 
 
+def _random_cases(n, seed):
+    """Seeded random layers and one-launch tunings: batches of 1 to 9 images, tile counts and workgroup totals that are
+    not multiples of the 8 XCDs the kernels renumber their workgroups over, every stage-1 width."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        K = int(rng.choice([1, 3, 3, 3, 5]))
+        stride = int(rng.choice([1, 1, 2]))
+        pad = int(rng.integers(0, K))
+        H, W = int(rng.integers(K, 30)), int(rng.integers(K, 34))
+        C, N = int(rng.integers(1, 70)), int(rng.integers(1, 70))
+        R1, R2 = int(rng.choice([4, 8, 16, 24, 32, 40, 64])), int(rng.choice([4, 8, 16, 24, 32, 48]))
+        layer = Layer(int(rng.integers(1, 10)), C, N, H, W, R1, R2, K, stride, pad)
+        if layer.Ho < 1 or layer.Wo < 1:
+            continue
+        variant = str(rng.choice(["fused", "chain", "fused_merged"]))
+        nb1 = (R1 + 15) // 16
+        mb1 = int(rng.choice([m for m in (1, 2, 4) if nb1 % m == 0]))
+        tuning = dict(tile_h=int(rng.integers(1, min(layer.Ho, 8) + 1)), tile_w=int(rng.integers(1, min(layer.Wo, 16) + 1)),
+                      waves=(int(rng.choice([1, 2, 4, 8])), 0, 0), mb=(mb1, 0, 0))
+        out.append((layer, variant, tuning))
+    return out
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
+def test_random_layers_and_tilings_through_the_one_launch_kernels(orc, layout):
+    """40 seeded random (layer, variant, tile, wavefronts, stage-1 width) combinations per layout; a combination the
+    library refuses (register tile not compiled, tile too large for LDS) is skipped, at least 20 must run."""
+    ran = 0
+    for layer, variant, tuning in _random_cases(40, 20221103 + layout):
+        if layout == B.LAYOUT_NHWC and (layer.C % 4 or layer.N % 4):
+            layer = Layer(layer.batch, 4 * ((layer.C + 3) // 4), 4 * ((layer.N + 3) // 4), layer.H, layer.W, layer.R1, layer.R2,
+                          layer.K, layer.stride, layer.pad)
+        _announce("random", layer.name(), variant, tuning, "layout", layout)
+        inputs = make_inputs(layer, 1000 + ran)
+        try:
+            got, desc = run_gpu_layout(layer, inputs, B.make_tuning(variant=VARIANTS[variant], **tuning), layout)
+        except B.TdcError as e:
+            assert e.status in (B.TDC_ERR_BAD_TUNING, B.TDC_ERR_UNSUPPORTED), e
+            continue
+        want = _oracle(orc, layer, inputs)
+        if layout == B.LAYOUT_NHWC:
+            want = np.ascontiguousarray(np.transpose(want, (0, 2, 3, 1)))
+        assert_parity(got, want, desc)
+        ran += 1
+    assert ran >= 20, ran
+
+
+def run_gpu_layout(layer, inputs, tuning, layout):
+    """One call on cuda:0 in the given activation layout; returns (y as numpy in that layout, plan description)."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    dev = torch.device("cuda:0")
+    t = {k: torch.from_numpy(v).to(dev) for k, v in inputs.items()}
+    conv = TuckerConv2d(layer, 0, tuning, layout=layout)
+    try:
+        conv.pack(t["U_in"], t["core"], t["U_out"])
+        x = t["x"].permute(0, 2, 3, 1).contiguous() if layout == B.LAYOUT_NHWC else t["x"]
+        y = torch.full(conv.out_shape(), float("nan"), device=dev)
+        conv(x, y)
+        torch.cuda.synchronize()
+        return y.cpu().numpy(), conv.describe()
+    finally:
+        conv.close()
+
+
 def test_error_paths_on_device():
     import ctypes
     import torch
