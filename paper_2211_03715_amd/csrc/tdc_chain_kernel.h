@@ -240,8 +240,8 @@ __global__ __launch_bounds__(512) void tdc_chain_kernel(TdcChainArgs a)
                 for (int pb = 0; pb < PB; ++pb)
                     if (ypix[pb] >= 0 && n < a.N) {
                         const size_t cell = ((size_t)b * P2 + ypix[pb]) * a.N + n;
-                        if constexpr (EPI) tdc_store_nhwc(a.y, a.epi, acc3[pb], n, cell);
-                        else *reinterpret_cast<tdc_f4 *>(a.y + cell) = acc3[pb];
+                        if constexpr (EPI) tdc_store_nhwc<true>(a.y, a.epi, acc3[pb], n, cell);
+                        else tdc_store4_stream(reinterpret_cast<tdc_f4 *>(a.y + cell), acc3[pb]);
                     }
                 return;
             }
