@@ -16,7 +16,9 @@ weights already resident in HBM.  Prints ONE JSON line.
                layer's roofline max(bytes/8 TB/s, flops/157.3 TFLOP/s), dense_conv_us (this
                library's kernel for the undecomposed K x K layer, timed the same way) and oracle_us
                (the CPU oracle's three-stage and dense paths, all host threads and one thread),
-               achieved_hbm_gbs (compulsory bytes over the cold-cache latency), traffic_bytes (see roofline)
+               achieved_hbm_gbs (compulsory bytes over the cold-cache latency), traffic_bytes (see roofline);
+               one_launch, for a layer whose plan takes two launches (MERGED): the same work in ONE launch
+               (MERGED_XCD, with a barrier among the workgroups of each XCD), timed like latency_us
   roofline     the same for the dominant (slowest) layer's kernel; traffic = HBM bytes per call measured with
                rocprofv3 for exactly this plan, looked up in profiles/traffic.txt (null for a plan not profiled)
   null_launch_us  an empty kernel timed the same way: the floor any batch-1 layer sits on
@@ -167,7 +169,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="workload id 1..6 (default 2: the ResNet-18-shaped sweep)")
-    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged", "fused_merged"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged", "fused_merged", "merged_xcd"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"],
                     help="activation layout (default NCHW, the layout the metric's workload is stated in)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the per-layer oracle times")
@@ -196,17 +198,18 @@ def main():
     torch.cuda.set_device(dev)
     variant = {"auto": B.VARIANT_AUTO, "naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT,
                "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN, "merged": B.VARIANT_MERGED,
-               "fused_merged": B.VARIANT_FUSED_MERGED}[args.variant]
+               "fused_merged": B.VARIANT_FUSED_MERGED, "merged_xcd": B.VARIANT_MERGED_XCD}[args.variant]
 
     layout = B.LAYOUT_NHWC if args.layout == "nhwc" else B.LAYOUT_NCHW
     layers = config_layers(args.config)
     host_inputs = [make_inputs(L, layer_seed(args.config, i)) for i, L in enumerate(layers)]
-    convs, xs, ys = [], [], []
+    convs, xs, ys, ws = [], [], [], []
     for L, inp in zip(layers, host_inputs):
         t = {k: torch.from_numpy(v).to(dev) for k, v in inp.items()}
         conv = TuckerConv2d(L, 0, B.make_tuning(variant=variant) if variant else None, layout=layout)
         conv.pack(t["U_in"], t["core"], t["U_out"])         # one-off re-layout, untimed (as in the paper)
         convs.append(conv)
+        ws.append(t)
         xs.append(t["x"].permute(0, 2, 3, 1).contiguous() if layout == B.LAYOUT_NHWC else t["x"])
         ys.append(torch.empty(conv.out_shape(), device=dev, dtype=torch.float32))
     torch.cuda.synchronize()
@@ -294,6 +297,22 @@ def main():
             row["speedup_vs_dense_conv"] = row["dense_conv_us"] / row["latency_us"]
             torch.cuda.synchronize()
             dense.close()
+            if conv.kernel_count() == 2:
+                # the two-launch MERGED plan against the same work in ONE launch (MERGED_XCD, never the selector's choice)
+                try:
+                    one = TuckerConv2d(L, 0, B.make_tuning(variant=B.VARIANT_MERGED_XCD), layout=layout)
+                except B.TdcError:
+                    one = None
+                if one is not None:
+                    one.pack(ws[i]["U_in"], ws[i]["core"], ws[i]["U_out"])
+                    ol = one.bind(xs[i], ys[i])
+                    for _ in range(100):
+                        ol()
+                    o_sec, o_min, o_max = _time_repeats(ol, max(100, iters // 4), 7, torch)
+                    torch.cuda.synchronize()
+                    row["one_launch"] = {"plan": one.describe(), "latency_us": o_sec * 1e6, "latency_us_min": o_min * 1e6,
+                                         "latency_us_max": o_max * 1e6, "status": B.tdc_plan_status(one.plan)}
+                    one.close()
             launch()                              # ys[i] holds the Tucker layer's output again
         per_layer.append(row)
     import ctypes

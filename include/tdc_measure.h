@@ -12,6 +12,13 @@ extern "C" {
  * can outweigh the saved FLOPs).  Returns TDC_OK or TDC_ERR_HIP. */
 int tdc_launch_null(void *hip_stream);
 
+/* Testing aid for TDC_VARIANT_MERGED_XCD plans: the number of times a workgroup polls for the others before it
+ * gives up (default 1 << 17, tens of milliseconds).  0 makes every workgroup that is not the last to arrive give
+ * up at once -- the way the tests reach the TDC_ERR_WAIT path with kernels that still end normally.  Also clears
+ * the plan's sticky status.  TDC_ERR_BAD_TUNING for plans of other variants. */
+struct tdc_plan;
+int tdc_plan_set_wait_limit(struct tdc_plan *plan, unsigned polls);
+
 #ifdef __cplusplus
 }
 #endif

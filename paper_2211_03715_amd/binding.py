@@ -28,7 +28,10 @@ STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_SPLIT, VARIANT_FUSED, VARIANT_CHAIN, VARIANT_DENSE, VARIANT_MERGED = 0, 1, 2, 3, 4, 5, 6
 VARIANT_FUSED_MERGED = 7
-VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense", 6: "merged", 7: "fused_merged"}
+VARIANT_MERGED_XCD = 8
+VARIANT_NAMES = {0: "auto", 1: "naive", 2: "split", 3: "fused", 4: "chain", 5: "dense", 6: "merged", 7: "fused_merged",
+                 8: "merged_xcd"}
+ERR_WAIT = -10
 
 # every symbol include/tdc.h declares
 EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", "tdc_conv_tucker2",
@@ -36,7 +39,7 @@ EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", 
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
            "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks",
            "tdc_conv_tucker2_ex", "tdc_conv_dense_ex", "tdc_hosvd_tucker2", "tdc_admm_project",
-           "tdc_conv_tucker2_static", "tdc_model_terms"]
+           "tdc_conv_tucker2_static", "tdc_model_terms", "tdc_plan_status", "tdc_plan_set_wait_limit"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -134,6 +137,10 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_model_terms.restype = ip
     lib.tdc_launch_null.argtypes = [vp]
     lib.tdc_launch_null.restype = ip
+    lib.tdc_plan_status.argtypes = [vp]
+    lib.tdc_plan_status.restype = ip
+    lib.tdc_plan_set_wait_limit.argtypes = [vp, ctypes.c_uint]
+    lib.tdc_plan_set_wait_limit.restype = ip
     lib.tdc_select_ranks.argtypes = [ctypes.POINTER(tdc_rank_layer), ip, ctypes.c_double, ctypes.c_double,
                                      ctypes.c_double, ctypes.POINTER(tdc_rank_choice)]
     lib.tdc_select_ranks.restype = ip
@@ -309,6 +316,17 @@ def tdc_plan_workspace_bytes(plan) -> int:
 
 def tdc_plan_kernel_count(plan) -> int:
     return int(load().tdc_plan_kernel_count(plan))
+
+
+def tdc_plan_status(plan) -> int:
+    """TDC_OK, or ERR_WAIT once a kernel of a MERGED_XCD plan has given up a wait (read after synchronising)."""
+    return int(load().tdc_plan_status(plan))
+
+
+def tdc_plan_set_wait_limit(plan, polls: int) -> None:
+    rc = load().tdc_plan_set_wait_limit(plan, polls)
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_set_wait_limit")
 
 
 def tdc_launch_null(stream=None) -> None:

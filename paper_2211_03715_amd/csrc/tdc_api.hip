@@ -17,6 +17,9 @@ struct tdc_plan {
     float *uin_p, *core_p, *uout_p;    // re-laid-out weights (SPLIT, FUSED, CHAIN; MERGED keeps the merged kernel in core_p)
     float *wm;                         // MERGED: core x_2 U_out in the caller's layout, before re-layout
     const float *packed_from[3];       // caller pointers the stored copy was made from, or NULLs
+    unsigned *arrive = nullptr;        // MERGED_XCD: arrival words, 8 XCDs x 32 roles
+    unsigned *status = nullptr;        // MERGED_XCD: one word of pinned host memory the kernel writes when a wait gives up
+    unsigned wait_limit = 1u << 17;
     size_t ws_bytes;
     double model_us;                   // the selector's latency estimate for this tuning
     char desc[320];
@@ -111,7 +114,8 @@ int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
         if (t.waves[i] < 1 || t.waves[i] > 8) return TDC_ERR_BAD_TUNING;
     const bool dense = t.variant == TDC_VARIANT_DENSE;   // one kernel, tiled over the blocks of N
     // MERGED, FUSED_MERGED: the second field tiles the blocks of N
-    const bool merged = t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_FUSED_MERGED;
+    const bool merged = t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_FUSED_MERGED ||
+                        t.variant == TDC_VARIANT_MERGED_XCD;
     const int nb[3] = {dense ? p.dims.NB2 : p.dims.NB1, merged ? p.dims.NB3 : p.dims.NB2, dense ? p.dims.NB2 : p.dims.NB3};
     for (int i = 0; i < 3; ++i)
         if (t.mb[i] < 1 || nb[i] % t.mb[i]) return TDC_ERR_BAD_TUNING;   // whole register tiles only
@@ -131,6 +135,14 @@ int check_tuning(const tdc_plan &p, const TdcDeviceInfo &dev)
             if (!tdc_gemm_unit_supported(t.mb[i], t.pb[i])) return TDC_ERR_BAD_TUNING;
             if (t.waves[i] > 1 && (size_t)t.waves[i] * t.mb[i] * t.pb[i] * 1024 > 64 * 1024) return TDC_ERR_BAD_TUNING;
         }
+        return TDC_OK;
+    }
+    if (t.variant == TDC_VARIANT_MERGED_XCD) {
+        if (!tdc_merged_xcd_supported(t)) return TDC_ERR_BAD_TUNING;
+        // eight copies of z1, each behind a buffer descriptor and a 32-bit stride
+        if ((size_t)p.dims.B * 16 * p.dims.NB1 * p.dims.H * p.dims.W * sizeof(float) >= (1ull << 28)) return TDC_ERR_BAD_TUNING;
+        // the whole grid must be resident for its barrier to open: one workgroup per compute unit is what is counted on
+        if (dev.cus % 8 || tdc_merged_xcd_grid(p.dims, t) > dev.cus) return TDC_ERR_BAD_TUNING;
         return TDC_OK;
     }
     if (t.variant == TDC_VARIANT_SPLIT) {
@@ -180,6 +192,9 @@ void describe(tdc_plan &p)
     else if (t.variant == TDC_VARIANT_MERGED)
         snprintf(p.desc, sizeof(p.desc), "merged stage(mb,pb,waves)= s1(%d,%d,%d) s23(%d,%d,%d) model=%.1fus", t.mb[0], t.pb[0],
                  t.waves[0], t.mb[1], t.pb[1], t.waves[1], p.model_us);
+    else if (t.variant == TDC_VARIANT_MERGED_XCD)
+        snprintf(p.desc, sizeof(p.desc), "merged-xcd split-k(s1,s23)=(%d,%d) grid=%d model=%.1fus", t.waves[0], t.waves[1],
+                 tdc_merged_xcd_grid(p.dims, t), p.model_us);
     else if (t.variant == TDC_VARIANT_DENSE)
         snprintf(p.desc, sizeof(p.desc), "dense %dx%d conv (mb,pb,waves)=(%d,%d,%d) model=%.1fus", p.dims.K, p.dims.K,
                  t.mb[1], t.pb[1], t.waves[1], p.model_us);
@@ -241,6 +256,7 @@ const char *tdc_status_string(int status)
         case TDC_ERR_BAD_TUNING: return "forced tuning does not fit the shape or the device";
         case TDC_ERR_TOO_LARGE: return "layer needs more scratch memory than the static buffer holds";
         case TDC_ERR_NO_CONVERGENCE: return "eigen-decomposition did not converge within the sweep limit";
+        case TDC_ERR_WAIT: return "a one-launch kernel gave up waiting for the other workgroups of its launch";
         default: return "unknown status";
     }
 }
@@ -252,7 +268,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
     const int want = forced ? forced->variant : TDC_VARIANT_AUTO;
-    if (want < TDC_VARIANT_AUTO || want > TDC_VARIANT_FUSED_MERGED) return TDC_ERR_BAD_TUNING;
+    if (want < TDC_VARIANT_AUTO || want > TDC_VARIANT_MERGED_XCD) return TDC_ERR_BAD_TUNING;
     const tdc_shape kshape = kernel_shape(*shape, want);
     rc = validate(kshape);
     if (rc != TDC_OK) return rc;
@@ -271,6 +287,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     tdc_plan *p = new (std::nothrow) tdc_plan();
     if (!p) return TDC_ERR_ALLOC;
     memset(p, 0, sizeof(*p));
+    p->wait_limit = 1u << 17;
     p->shape = *shape;
     p->dims = make_dims(kshape);
     p->device = device;
@@ -286,6 +303,11 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
         p->geom = tdc_fm_geometry(p->dims, p->tuning.tile_h, p->tuning.tile_w, p->tuning.waves[0], p->tuning.mb[1]);
     if (rc == TDC_OK) rc = check_tuning(*p, dev);
+    if (rc == TDC_OK && p->tuning.variant == TDC_VARIANT_MERGED_XCD) {
+        bool fits = false;
+        if (tdc_merged_xcd_resident(tdc_merged_xcd_grid(p->dims, p->tuning), p->dims.nhwc, &fits) != hipSuccess) rc = TDC_ERR_HIP;
+        else if (!fits) rc = TDC_ERR_BAD_TUNING;
+    }
     if (rc != TDC_OK) {
         delete p;
         return rc;
@@ -297,12 +319,21 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     bool ok = true;
     const bool dense = p->tuning.variant == TDC_VARIANT_DENSE;
     const bool fm = p->tuning.variant == TDC_VARIANT_FUSED_MERGED;
-    const bool merged = p->tuning.variant == TDC_VARIANT_MERGED || fm;
+    const bool xcd = p->tuning.variant == TDC_VARIANT_MERGED_XCD;
+    const bool merged = p->tuning.variant == TDC_VARIANT_MERGED || fm || xcd;
     if (merged) {
         const size_t n_wm = (size_t)d.R1 * d.N * d.K * d.K, n_wmp = (size_t)d.NB3 * d.K * d.K * d.NB1 * 256;
         if (!fm) {
-            ok = ok && hipMalloc((void **)&p->z1, n_z1 * sizeof(float)) == hipSuccess;
-            p->ws_bytes += n_z1 * sizeof(float);
+            const size_t copies = xcd ? 8 : 1;
+            ok = ok && hipMalloc((void **)&p->z1, copies * n_z1 * sizeof(float)) == hipSuccess;
+            p->ws_bytes += copies * n_z1 * sizeof(float);
+        }
+        if (xcd) {
+            ok = ok && hipMalloc((void **)&p->arrive, 8 * 32 * sizeof(unsigned)) == hipSuccess;
+            ok = ok && hipMemset(p->arrive, 0, 8 * 32 * sizeof(unsigned)) == hipSuccess;
+            ok = ok && hipHostMalloc((void **)&p->status, sizeof(unsigned), hipHostMallocDefault) == hipSuccess;
+            if (ok) *p->status = 0;
+            p->ws_bytes += 8 * 32 * sizeof(unsigned);
         }
         ok = ok && hipMalloc((void **)&p->uin_p, n_w1 * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->wm, n_wm * sizeof(float)) == hipSuccess;
@@ -356,7 +387,7 @@ int tdc_select_tuning(const tdc_shape *shape, int compute_units, int lds_bytes, 
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
     if (compute_units < 1 || lds_bytes < 1024) return TDC_ERR_BAD_TUNING;
-    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_FUSED_MERGED) return TDC_ERR_BAD_TUNING;
+    if (inout->variant < TDC_VARIANT_AUTO || inout->variant > TDC_VARIANT_MERGED_XCD) return TDC_ERR_BAD_TUNING;
     const tdc_shape kshape = kernel_shape(*shape, inout->variant);
     rc = validate(kshape);
     if (rc != TDC_OK) return rc;
@@ -386,7 +417,7 @@ int tdc_model_terms(const tdc_shape *shape, const tdc_tuning *tuning, int comput
     int rc = validate(*shape);
     if (rc != TDC_OK) return rc;
     if (compute_units < 1 || lds_bytes < 1024) return TDC_ERR_BAD_TUNING;
-    if (tuning->variant <= TDC_VARIANT_NAIVE || tuning->variant > TDC_VARIANT_FUSED_MERGED) return TDC_ERR_BAD_TUNING;
+    if (tuning->variant <= TDC_VARIANT_NAIVE || tuning->variant > TDC_VARIANT_MERGED_XCD) return TDC_ERR_BAD_TUNING;
     const tdc_shape kshape = kernel_shape(*shape, tuning->variant);
     rc = validate(kshape);
     if (rc != TDC_OK) return rc;
@@ -421,6 +452,8 @@ int tdc_plan_destroy(tdc_plan *p)
     float *bufs[] = {p->z1, p->z2, p->uin_p, p->core_p, p->uout_p, p->wm};
     for (float *b : bufs)
         if (b && hipFree(b) != hipSuccess) rc = TDC_ERR_HIP;
+    if (p->arrive && hipFree(p->arrive) != hipSuccess) rc = TDC_ERR_HIP;
+    if (p->status && hipHostFree(p->status) != hipSuccess) rc = TDC_ERR_HIP;
     delete p;
     return rc;
 }
@@ -436,7 +469,8 @@ int tdc_plan_pack_weights(tdc_plan *p, void *hip_stream, const float *U_in, cons
     }
     DeviceGuard guard(p->device);
     if (!guard.ok) return TDC_ERR_HIP;
-    const bool merged_weights = p->tuning.variant == TDC_VARIANT_MERGED || p->tuning.variant == TDC_VARIANT_FUSED_MERGED;
+    const bool merged_weights = p->tuning.variant == TDC_VARIANT_MERGED || p->tuning.variant == TDC_VARIANT_FUSED_MERGED ||
+                                p->tuning.variant == TDC_VARIANT_MERGED_XCD;
     const hipError_t e = merged_weights
                              ? tdc_launch_pack_merged(p->dims, (hipStream_t)hip_stream, U_in, core, U_out, p->uin_p, p->wm, p->core_p)
                              : tdc_launch_pack(p->dims, (hipStream_t)hip_stream, U_in, core, U_out, p->uin_p, p->core_p, p->uout_p);
@@ -460,6 +494,7 @@ int tdc_conv_tucker2_ex(tdc_plan *p, void *hip_stream, const float *x, const flo
     if (p->tuning.variant == TDC_VARIANT_DENSE) return TDC_ERR_BAD_TUNING;
     if (p->dims.nhwc && misaligned16(x, y, epi.residual)) return TDC_ERR_UNSUPPORTED;
     if (p->dims.s1_runs && misaligned16(x, nullptr, nullptr)) return TDC_ERR_UNSUPPORTED;
+    if (p->status && *(volatile unsigned *)p->status) return TDC_ERR_WAIT;
     DeviceGuard guard(p->device);
     if (!guard.ok) return TDC_ERR_HIP;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -472,7 +507,8 @@ int tdc_conv_tucker2_ex(tdc_plan *p, void *hip_stream, const float *x, const flo
     const bool packed = p->packed_from[0] == U_in && p->packed_from[1] == core && p->packed_from[2] == U_out;
     if (!packed) {   // no stored copy for these pointers: re-lay out on the stream, remember nothing
         p->packed_from[0] = p->packed_from[1] = p->packed_from[2] = nullptr;
-        e = (p->tuning.variant == TDC_VARIANT_MERGED || p->tuning.variant == TDC_VARIANT_FUSED_MERGED)
+        e = (p->tuning.variant == TDC_VARIANT_MERGED || p->tuning.variant == TDC_VARIANT_FUSED_MERGED ||
+             p->tuning.variant == TDC_VARIANT_MERGED_XCD)
                 ? tdc_launch_pack_merged(d, s, U_in, core, U_out, p->uin_p, p->wm, p->core_p)
                 : tdc_launch_pack(d, s, U_in, core, U_out, p->uin_p, p->core_p, p->uout_p);
         if (e != hipSuccess) return TDC_ERR_HIP;
@@ -481,6 +517,8 @@ int tdc_conv_tucker2_ex(tdc_plan *p, void *hip_stream, const float *x, const flo
         e = tdc_launch_fm(d, p->tuning, p->geom, s, x, p->uin_p, p->core_p, y, epi);
     else if (p->tuning.variant == TDC_VARIANT_MERGED)
         e = tdc_launch_merged(d, p->tuning, s, x, p->uin_p, p->core_p, p->z1, y, epi);
+    else if (p->tuning.variant == TDC_VARIANT_MERGED_XCD)
+        e = tdc_launch_merged_xcd(d, p->tuning, s, x, p->uin_p, p->core_p, p->z1, p->arrive, p->status, p->wait_limit, y, epi);
     else if (p->tuning.variant == TDC_VARIANT_SPLIT)
         e = tdc_launch_split(d, p->tuning, s, x, p->uin_p, p->core_p, p->uout_p, p->z1, p->z2, y, epi);
     else if (p->tuning.variant == TDC_VARIANT_CHAIN)
@@ -546,7 +584,23 @@ int tdc_plan_kernel_count(const tdc_plan *p)
     if (!p) return 0;
     const int v = p->tuning.variant;
     if (v == TDC_VARIANT_MERGED) return 2;
+    if (v == TDC_VARIANT_MERGED_XCD) return 1;
     return (v == TDC_VARIANT_FUSED || v == TDC_VARIANT_CHAIN || v == TDC_VARIANT_DENSE || v == TDC_VARIANT_FUSED_MERGED) ? 1 : 3;
+}
+
+int tdc_plan_status(const tdc_plan *p)
+{
+    if (!p) return TDC_ERR_NULL;
+    return p->status && *(volatile unsigned *)p->status ? TDC_ERR_WAIT : TDC_OK;
+}
+
+int tdc_plan_set_wait_limit(tdc_plan *p, unsigned polls)
+{
+    if (!p) return TDC_ERR_NULL;
+    if (p->tuning.variant != TDC_VARIANT_MERGED_XCD) return TDC_ERR_BAD_TUNING;
+    p->wait_limit = polls;
+    *p->status = 0;
+    return TDC_OK;
 }
 
 int tdc_launch_null(void *hip_stream)

@@ -274,6 +274,301 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
     TDC_PROBE((MODE - 1) * 5 + 4);
 }
 
+// ---- MERGED in one launch.  What the two-launch form loses at batch 1 is the boundary between its kernels (the
+// write-back at the end of the first, the dispatch of the second, its first loads: 1.7-2.3 us of a 7-9 us layer).
+// Here the workgroups that run on one XCD -- they share its L2 -- first compute stage 1 (Eq. 2) together, all of
+// it, into a copy of z1 that belongs to their XCD (stage 1 is done once per XCD, eight times in all: it is a ninth
+// of the layer's work at these shapes and there is no cheaper way to put z1 into every L2), meet at a barrier
+// among themselves, and then run their share of the merged K x K GEMM on that copy.  Nothing crosses an XCD inside
+// the launch, so no L2 write-back is needed: a wavefront waits for its own stores (they are then in the L2, the
+// L1 being write-through), the workgroup bumps its arrival word, and one wavefront polls the arrival words of its
+// XCD with loads that miss the L1.  z1 is read by nobody before the barrier, so plain loads see it afterwards.
+//   The XCD of a workgroup is read from the hardware (XCC_ID), never inferred; its role among the workgroups of
+// that XCD is blockIdx.x / 8, which assumes what the XCD-aware numbering elsewhere in this library assumes for
+// speed only: workgroups are dealt to the 8 XCDs round-robin.  Were that ever not so, a role would be missing on
+// some XCD, its arrival word would lag, and the bounded wait below ends with the plan's status word set: an
+// error the host reports, not a wrong result.  Arrival words count calls (each workgroup adds one to its own
+// word), so nothing depends on host state and a captured graph can be replayed.
+//   Units are single 16x16 output blocks; tw1 (tw2) wavefronts of a workgroup split the contraction of a unit and
+// add their partial sums through LDS in a fixed order, as in the kernel above; 8/tw teams work side by side.
+struct XcdArgs {
+    const float *x, *uin_p, *wm_p;
+    float *z1c;            // 8 copies of z1, blocked layout, z1_stride floats apart
+    float *y;
+    unsigned *arrive;      // [8 XCDs][32 roles]
+    unsigned *status;      // host-visible; set non-zero when a wait gave up
+    TdcEpi epi;
+    unsigned z1_stride, wait_limit;
+    int C, N, HW, P, NB1, NB3, KG1, KG2, H, W, Wo, K, stride, pad;
+    int lg1, lg2;          // log2 of the wavefronts per team in stage 1 / in the merged GEMM
+    int q1, rem1, q2, rem2;   // k-groups per wavefront of a team: the first rem take q + 1
+    int n1, n2, npb1, npb2, Wn, rounds1, rounds2, nhwc;
+    TdcDiv div_Wo, div_NBk, div_K, div_npb1, div_npb2, div_NB1, div_NB3;
+};
+
+// NK > 0: the merged GEMM takes one pass (every team has at most one unit) and a wavefront at most NK k-groups of
+// it.  Its weight fragments are then requested at the very start of the kernel and wait in registers, so that
+// behind the barrier only the z1 loads and the MFMAs remain.
+// NK == 0: any size, operands streamed through TdcPipe as in the GEMM kernel.
+template <int ACT, int NK>
+__global__ __launch_bounds__(512) void tdc_merged_xcd_kernel(XcdArgs a)
+{
+    __shared__ float red[8 * 256];
+    __shared__ int go;
+    constexpr int U = 4;
+    // the kernel arguments span several cache lines of host-visible memory: ask for all of them now, at once
+    TDC_FETCH_NOW(TDC_OUTS("+s"(a.z1_stride), "+s"(a.wait_limit)), "s"(a.x), "s"(a.uin_p), "s"(a.wm_p), "s"(a.z1c), "s"(a.y),
+                  "s"(a.arrive), "s"(a.epi.bias), "s"(a.epi.residual), "s"(a.epi.relu), "s"(a.C), "s"(a.N), "s"(a.HW), "s"(a.P),
+                  "s"(a.NB1), "s"(a.NB3), "s"(a.KG1), "s"(a.KG2), "s"(a.H), "s"(a.W), "s"(a.Wo), "s"(a.K), "s"(a.stride),
+                  "s"(a.pad), "s"(a.lg1), "s"(a.lg2), "s"(a.q1), "s"(a.rem1), "s"(a.q2), "s"(a.rem2), "s"(a.n1), "s"(a.n2), "s"(a.npb1), "s"(a.npb2), "s"(a.Wn), "s"(a.rounds1),
+                  "s"(a.rounds2), "s"(a.nhwc), "s"(a.div_Wo.m), "s"(a.div_Wo.sh1), "s"(a.div_Wo.sh2), "s"(a.div_NBk.m),
+                  "s"(a.div_NBk.sh1), "s"(a.div_NBk.sh2), "s"(a.div_K.m), "s"(a.div_K.sh1), "s"(a.div_K.sh2), "s"(a.div_npb1.m),
+                  "s"(a.div_npb1.sh1), "s"(a.div_npb1.sh2), "s"(a.div_npb2.m), "s"(a.div_npb2.sh1), "s"(a.div_npb2.sh2),
+                  "s"(a.div_NB1.m), "s"(a.div_NB1.sh1), "s"(a.div_NB1.sh2), "s"(a.div_NB3.m), "s"(a.div_NB3.sh1), "s"(a.div_NB3.sh2));
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, l16 = lane & 15;
+    unsigned xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    xcc &= 15u;
+    const int role = blockIdx.x >> 3;
+    TDC_PROBE(0);
+    if (xcc >= 8u || role >= 32) {   // not the chip this kernel was written for
+        if (threadIdx.x == 0) __hip_atomic_store(a.status, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        return;
+    }
+    unsigned *my_arrive = a.arrive + xcc * 32;
+    const tdc_rsrc ars_flags = tdc_make_rsrc(my_arrive, 32 * 4);
+    // this workgroup's own word, written by it (same XCD, same role) in the call before: the value to reach
+    // (every wavefront loads it: a load inside a branch is waited for where the branch ends, and this one must not be)
+    const unsigned own = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(ars_flags, role * 4, 0, 16);
+    float *z1x = a.z1c + (size_t)xcc * a.z1_stride;
+    tdc_f4 *__restrict__ red4 = reinterpret_cast<tdc_f4 *>(red);
+
+    // ---- what the second phase will need (NK > 0: its single unit), worked out before anything waits
+    const int G = (int)gridDim.x;
+    const int tw2 = 1 << a.lg2, teams2 = 8 >> a.lg2, team2 = wave >> a.lg2, wt2 = wave & (tw2 - 1);
+    const int q2 = a.q2, rem2 = a.rem2;
+    const int lw = tdc_logical_block(blockIdx.x, G);
+    const int kg02 = wt2 * q2 + min(wt2, rem2);
+    int tap0, dg0, r0, s0;
+    {
+        tap0 = tdc_div(kg02, a.div_NBk);
+        dg0 = kg02 - tap0 * a.NB1;
+        r0 = tdc_div(tap0, a.div_K);
+        s0 = tap0 - r0 * a.K;
+    }
+    tdc_f4 wk[NK > 0 ? NK : 1];
+    int u2 = 0, b2 = 0, mg2 = 0, pg2 = 0, cnt2 = 0, ih2 = 0, iw2 = 0;
+    bool live2 = false;
+    // ---- stage 1, all of it, by the workgroups of this XCD
+    {
+        const int tw = 1 << a.lg1, teams = 8 >> a.lg1, team = wave >> a.lg1, wt = wave & (tw - 1);
+        const int q = a.q1, rem = a.rem1;
+        for (int r = 0; r < a.rounds1; ++r) {
+            const int u = (r * a.Wn + role) * teams + team;
+            const bool live = u < a.n1;
+            const int pgb = tdc_div(live ? u : 0, a.div_NB1), mg = (live ? u : 0) - pgb * a.NB1;   // (b, pixel group), channel block
+            const int b = tdc_div(pgb, a.div_npb1), pg = pgb - b * a.npb1;
+            GemmNext<1, ACT, 1, 1> next;
+            next.wstride = 0;
+            next.wrs = tdc_make_rsrc(a.uin_p + (size_t)mg * a.KG1 * 256, (unsigned)a.KG1 * 1024u);
+            next.ars = tdc_make_rsrc(a.x + (size_t)b * a.C * a.HW, (unsigned)a.C * a.HW * 4u);
+            next.wlane = lane * 16u;
+            next.act_pix = a.HW; next.C = a.C; next.NBk = 1; next.K = a.K; next.H = a.H; next.W = a.W; next.g = g;
+            const int p = 16 * pg + l16;
+            next.pval[0] = p < a.HW; next.ih0[0] = next.iw0[0] = 0; next.poff[0] = p;
+            const int kg0 = wt * q + min(wt, rem);
+            next.kg = kg0;
+            next.kg_end = live ? kg0 + q + (wt < rem ? 1 : 0) : kg0;
+            next.dg = next.r = next.s = 0;
+            tdc_f4 acc[1][1];
+            TdcPipe<1, 1, U> pipe;
+            pipe.start(next);
+            TDC_PROBE(1);
+            if (NK > 0 && r == 0) {
+                u2 = lw * teams2 + team2;
+                live2 = u2 < a.n2;
+                const int bm = tdc_div(live2 ? u2 : 0, a.div_npb2);
+                pg2 = (live2 ? u2 : 0) - bm * a.npb2;
+                b2 = tdc_div(bm, a.div_NB3);
+                mg2 = bm - b2 * a.NB3;
+                cnt2 = live2 ? q2 + (wt2 < rem2 ? 1 : 0) : 0;
+                const int p = 16 * pg2 + l16;
+                const int i = tdc_div(p, a.div_Wo), j = p - i * a.Wo;
+                ih2 = i * a.stride - a.pad;
+                iw2 = j * a.stride - a.pad;
+                // the merged GEMM's weight fragments of this wavefront, requested right behind the first operands of
+                // stage 1: they come from HBM (every workgroup has its own) and have all of stage 1 to arrive
+                const tdc_rsrc wrs2 = tdc_make_rsrc(a.wm_p + (size_t)mg2 * a.KG2 * 256, (unsigned)a.KG2 * 1024u);
+#pragma unroll
+                for (int k = 0; k < NK; ++k)
+                    wk[k] = tdc_buf_load4(wrs2, ((unsigned)(kg02 + k) * 1024u + lane * 16u) | (k < cnt2 ? 0u : TDC_OOB));
+            }
+            pipe.run(acc, next.kg_end - kg0, next);
+            TDC_PROBE(2);
+            tdc_f4 *__restrict__ z14 = reinterpret_cast<tdc_f4 *>(z1x + (size_t)b * 16 * a.NB1 * a.HW);
+            if (tw == 1) {
+                if (live && p < a.HW) z14[((size_t)mg * a.HW + p) * 4 + g] = acc[0][0];
+            } else {
+                red4[wave * 64 + lane] = acc[0][0];
+                __syncthreads();
+                for (int e = wt * 64 + lane; e < 256; e += tw * 64) {
+                    float sum = red[team * tw * 256 + e];
+                    for (int ww = 1; ww < tw; ++ww) sum += red[(team * tw + ww) * 256 + e];
+                    const int i = e & 3, ln = (e >> 2) & 63;
+                    const int pp = 16 * pg + (ln & 15);
+                    if (live && pp < a.HW)
+                        z1x[(size_t)b * 16 * a.NB1 * a.HW + (((size_t)mg * a.HW + pp) * 4 + (ln >> 4)) * 4 + i] = sum;
+                }
+                __syncthreads();
+            }
+        }
+    }
+    // ---- the barrier among the workgroups of this XCD
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's z1 stores are in the L2 (and its weight loads have landed)
+    __syncthreads();
+    TDC_PROBE(3);
+    if (wave == 0) {
+        const unsigned target = own + 1u;
+        if (lane == 0) __hip_atomic_store(my_arrive + role, target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        unsigned polls = 0;
+        bool ok;
+        while (true) {
+            unsigned v = target;
+            if (lane < a.Wn) v = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(ars_flags, lane * 4, 0, 16);   // sc1: misses the L1
+            ok = __builtin_amdgcn_ballot_w64((int)(v - target) < 0) == 0;
+            if (ok || polls++ >= a.wait_limit) break;
+        }
+        if (lane == 0) {
+            go = ok ? 1 : 0;
+            if (!ok) __hip_atomic_store(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+    __syncthreads();
+    if (!go) return;
+    TDC_PROBE(4);
+
+    // ---- the merged K x K GEMM R1 -> N on this XCD's z1
+    {
+        const int tw = tw2, teams = teams2, team = team2, wt = wt2;
+        const int rounds = NK > 0 ? 1 : a.rounds2;
+        for (int r = 0; r < rounds; ++r) {
+            int b, mg, pg;
+            bool live;
+            tdc_f4 acc[1][1];
+            if (NK > 0) {
+                b = b2; mg = mg2; pg = pg2; live = live2;
+                const tdc_rsrc zrs = tdc_make_rsrc(z1x + (size_t)b * 16 * a.NB1 * a.HW, (unsigned)(16 * a.NB1) * a.HW * 4u);
+                const bool pval = 16 * pg + l16 < a.P;
+                const int poff = ih2 * a.W + iw2;
+                tdc_f4 zk[NK > 0 ? NK : 1];
+                int dg = dg0, rr = r0, ss = s0;
+#pragma unroll
+                for (int k = 0; k < NK; ++k) {
+                    const int h = ih2 + rr, w = iw2 + ss;
+                    const bool ok = pval && k < cnt2 && h >= 0 && h < a.H && w >= 0 && w < a.W;
+                    zk[k] = tdc_buf_load4(zrs, ((unsigned)((dg * a.HW + poff + rr * a.W + ss) * 16 + 4 * g) * 4u) | (ok ? 0u : TDC_OOB));
+                    if (++dg == a.NB1) {
+                        dg = 0;
+                        if (++ss == a.K) {
+                            ss = 0;
+                            ++rr;
+                        }
+                    }
+                }
+                TDC_PROBE(5);
+                acc[0][0] = tdc_f4_zero();
+#pragma unroll
+                for (int k = 0; k < NK; ++k)
+                    if (k < cnt2) {
+                        const tdc_f4 av[1] = {wk[k]}, bv[1] = {zk[k]};
+                        tdc_mma_group<1, 1>(acc, av, bv);
+                    }
+            } else {
+                const int u = (r * G + lw) * teams + team;
+                live = u < a.n2;
+                const int bm = tdc_div(live ? u : 0, a.div_npb2);
+                pg = (live ? u : 0) - bm * a.npb2;   // (b, channel block), pixel group
+                b = tdc_div(bm, a.div_NB3);
+                mg = bm - b * a.NB3;
+                GemmNext<2, TDC_ACT_BLOCKED, 1, 1> next;
+                next.wstride = 0;
+                next.wrs = tdc_make_rsrc(a.wm_p + (size_t)mg * a.KG2 * 256, (unsigned)a.KG2 * 1024u);
+                next.ars = tdc_make_rsrc(z1x + (size_t)b * 16 * a.NB1 * a.HW, (unsigned)(16 * a.NB1) * a.HW * 4u);
+                next.wlane = lane * 16u;
+                next.act_pix = a.HW; next.C = 16 * a.NB1; next.NBk = a.NB1; next.K = a.K; next.H = a.H; next.W = a.W; next.g = g;
+                const int p = 16 * pg + l16;
+                next.pval[0] = p < a.P;
+                {
+                    const int i = tdc_div(p, a.div_Wo), j = p - i * a.Wo;
+                    next.ih0[0] = i * a.stride - a.pad;
+                    next.iw0[0] = j * a.stride - a.pad;
+                    next.poff[0] = next.ih0[0] * a.W + next.iw0[0];
+                }
+                next.kg = kg02;
+                next.kg_end = live ? kg02 + q2 + (wt < rem2 ? 1 : 0) : kg02;
+                next.dg = dg0; next.r = r0; next.s = s0;
+                TdcPipe<1, 1, U> pipe;
+                pipe.start(next);
+                TDC_PROBE(5);
+                pipe.run(acc, next.kg_end - kg02, next);
+            }
+            TDC_PROBE(6);
+            const int p = 16 * pg + l16;
+            float *__restrict__ yb = a.y + (size_t)b * a.N * a.P;
+            if (tw == 1) {
+                if (live && p < a.P) {
+                    if (a.nhwc) {
+                        const int m = 16 * mg + 4 * g;
+                        if (m < a.N) tdc_store_nhwc(a.y, a.epi, acc[0][0], m, ((size_t)b * a.P + p) * a.N + m);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int m = 16 * mg + 4 * g + i;
+                            if (m < a.N) {
+                                const size_t idx = (size_t)m * a.P + p;
+                                yb[idx] = tdc_apply_epilogue(a.epi, acc[0][0][i], m, (size_t)b * a.N * a.P + idx);
+                            }
+                        }
+                    }
+                }
+                continue;
+            }
+            if (a.nhwc) {
+                red4[wave * 64 + lane] = acc[0][0];
+                __syncthreads();
+                for (int e = wt * 64 + lane; e < 256; e += tw * 64) {
+                    float sum = red[team * tw * 256 + e];
+                    for (int ww = 1; ww < tw; ++ww) sum += red[(team * tw + ww) * 256 + e];
+                    const int i = e & 3, ln = (e >> 2) & 63;
+                    const int pp = 16 * pg + (ln & 15), m = 16 * mg + 4 * (ln >> 4) + i;
+                    if (live && pp < a.P && m < a.N) {
+                        const size_t idx = ((size_t)b * a.P + pp) * a.N + m;
+                        a.y[idx] = tdc_apply_epilogue(a.epi, sum, m, idx);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) red[wave * 256 + i * 64 + lane] = acc[0][0][i];
+                __syncthreads();
+                for (int e = wt * 64 + lane; e < 256; e += tw * 64) {
+                    float sum = red[team * tw * 256 + e];
+                    for (int ww = 1; ww < tw; ++ww) sum += red[(team * tw + ww) * 256 + e];
+                    const int ln = e & 63, i = e >> 6;
+                    const int pp = 16 * pg + (ln & 15), m = 16 * mg + 4 * (ln >> 4) + i;
+                    if (live && pp < a.P && m < a.N) {
+                        const size_t idx = (size_t)m * a.P + pp;
+                        yb[idx] = tdc_apply_epilogue(a.epi, sum, m, (size_t)b * a.N * a.P + idx);
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    TDC_PROBE(7);
+}
+
 // k-groups fetched per register buffer: 2*U covers up to eight k-groups per wavefront, beyond
 // that the choice among the compiled sizes minimises dead MFMA slots in the last buffer.
 int pick_u(int kg_per_wave, int umax)
@@ -411,4 +706,80 @@ hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t 
     a.NBm = d.NB3; a.KG = d.K * d.K * d.NB1; a.NBk = d.NB1;
     a.n_pgroups = ((P + 15) / 16 + t.pb[1] - 1) / t.pb[1];
     return launch_stage<2, TDC_ACT_BLOCKED>(a, t.mb[1], t.pb[1], t.waves[1], d.B, s);
+}
+
+// MERGED_XCD: see tdc_merged_xcd_kernel.  `waves[0]`, `waves[1]`: wavefronts that split the contraction of one
+// stage-1 / one merged-GEMM unit (1, 2, 4 or 8; a workgroup always has 8 wavefronts).
+bool tdc_merged_xcd_supported(const tdc_tuning &t)
+{
+    for (int i = 0; i < 2; ++i) {
+        const int w = t.waves[i];
+        if (!(w == 1 || w == 2 || w == 4 || w == 8) || t.mb[i] != 1 || t.pb[i] != 1) return false;
+    }
+    return true;
+}
+
+int tdc_merged_xcd_grid(const TdcDims &d, const tdc_tuning &t)
+{
+    const long n1 = (long)d.B * d.NB1 * ((d.H * d.W + 15) / 16), n2 = (long)d.B * d.NB3 * ((d.Ho * d.Wo + 15) / 16);
+    const long teams1 = 8 / t.waves[0], teams2 = 8 / t.waves[1];
+    long wn = std::max((n1 + teams1 - 1) / teams1, (n2 + 8 * teams2 - 1) / (8 * teams2));
+    wn = std::min(32L, std::max(1L, wn));
+    return (int)(8 * wn);
+}
+
+hipError_t tdc_launch_merged_xcd(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x, const float *uin_p,
+                                 const float *wm_p, float *z1c, unsigned *arrive, unsigned *status, unsigned wait_limit,
+                                 float *y, const TdcEpi &epi)
+{
+    XcdArgs a;
+    a.x = x; a.uin_p = uin_p; a.wm_p = wm_p; a.z1c = z1c; a.y = y; a.arrive = arrive; a.status = status; a.epi = epi;
+    a.HW = d.H * d.W; a.P = d.Ho * d.Wo;
+    a.z1_stride = (unsigned)((size_t)d.B * 16 * d.NB1 * a.HW);
+    a.wait_limit = wait_limit;
+    a.C = d.C; a.N = d.N; a.NB1 = d.NB1; a.NB3 = d.NB3; a.KG1 = d.KG1; a.KG2 = d.K * d.K * d.NB1;
+    a.H = d.H; a.W = d.W; a.Wo = d.Wo; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
+    const int tw1 = t.waves[0], tw2 = t.waves[1];
+    a.lg1 = tw1 == 8 ? 3 : tw1 == 4 ? 2 : tw1 == 2 ? 1 : 0;
+    a.lg2 = tw2 == 8 ? 3 : tw2 == 4 ? 2 : tw2 == 2 ? 1 : 0;
+    a.q1 = a.KG1 / tw1; a.rem1 = a.KG1 % tw1; a.q2 = a.KG2 / tw2; a.rem2 = a.KG2 % tw2;
+    a.npb1 = (a.HW + 15) / 16; a.npb2 = (a.P + 15) / 16;
+    a.n1 = d.B * d.NB1 * a.npb1; a.n2 = d.B * d.NB3 * a.npb2;
+    const int G = tdc_merged_xcd_grid(d, t);
+    a.Wn = G / 8;
+    const int teams1 = 8 / tw1, teams2 = 8 / tw2;
+    a.rounds1 = (a.n1 + a.Wn * teams1 - 1) / (a.Wn * teams1);
+    a.rounds2 = (a.n2 + G * teams2 - 1) / (G * teams2);
+    a.nhwc = d.nhwc;
+    a.div_Wo = tdc_make_div((unsigned)d.Wo); a.div_NBk = tdc_make_div((unsigned)d.NB1); a.div_K = tdc_make_div((unsigned)d.K);
+    a.div_npb1 = tdc_make_div((unsigned)a.npb1); a.div_npb2 = tdc_make_div((unsigned)a.npb2);
+    a.div_NB1 = tdc_make_div((unsigned)d.NB1); a.div_NB3 = tdc_make_div((unsigned)d.NB3);
+    // weight fragments held in registers across the barrier: when the merged GEMM is one pass of at most 10 k-groups
+    // per wavefront (compiled sizes 3, 5, 7, 10)
+    const int kpw = (a.KG2 + tw2 - 1) / tw2;
+    const int nk = a.rounds2 > 1 || kpw > 10 ? 0 : kpw <= 3 ? 3 : kpw <= 5 ? 5 : kpw <= 7 ? 7 : 10;
+#define TDC_CASE(N_)                                                                                            \
+    if (nk == N_) {                                                                                             \
+        if (d.nhwc) hipLaunchKernelGGL((tdc_merged_xcd_kernel<TDC_ACT_NHWC, N_>), dim3(G), dim3(512), 0, s, a); \
+        else hipLaunchKernelGGL((tdc_merged_xcd_kernel<TDC_ACT_NCHW, N_>), dim3(G), dim3(512), 0, s, a);        \
+        return hipGetLastError();                                                                               \
+    }
+    TDC_CASE(0) TDC_CASE(3) TDC_CASE(5) TDC_CASE(7) TDC_CASE(10)
+#undef TDC_CASE
+    return hipErrorInvalidValue;
+}
+
+// Can `grid` workgroups of the kernel be resident on the current device at once?
+hipError_t tdc_merged_xcd_resident(int grid, bool nhwc, bool *fits)
+{
+    int dev = 0, cus = 0, per_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess)
+        // the instance with the most registers stands for all
+        e = nhwc ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tdc_merged_xcd_kernel<TDC_ACT_NHWC, 10>, 512, 0)
+                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tdc_merged_xcd_kernel<TDC_ACT_NCHW, 10>, 512, 0);
+    // every XCD must hold its eighth of the grid on its own compute units
+    *fits = e == hipSuccess && cus % 8 == 0 && (long)(grid / 8) <= (long)(cus / 8) * per_cu;
+    return e;
 }

@@ -78,6 +78,15 @@ hipError_t tdc_launch_dense(const TdcDims &d, const tdc_tuning &t, hipStream_t s
 hipError_t tdc_launch_merged(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x,
                              const float *uin_p, const float *wm_p, float *z1, float *y, const TdcEpi &epi);
 
+// MERGED in one launch (tdc_gemm.hip): `z1c` holds 8 copies of z1, `arrive` 8 x 32 words that start at zero,
+// `status` is host-visible.  The grid (a multiple of 8, at most 256 workgroups of 512 threads) must be resident at once.
+bool tdc_merged_xcd_supported(const tdc_tuning &t);
+int tdc_merged_xcd_grid(const TdcDims &d, const tdc_tuning &t);
+hipError_t tdc_launch_merged_xcd(const TdcDims &d, const tdc_tuning &t, hipStream_t s, const float *x, const float *uin_p,
+                                 const float *wm_p, float *z1c, unsigned *arrive, unsigned *status, unsigned wait_limit,
+                                 float *y, const TdcEpi &epi);
+hipError_t tdc_merged_xcd_resident(int grid, bool nhwc, bool *fits);
+
 // The one-launch kernels' launchers take `prepare_only`: do what must precede a first launch (raise the
 // kernel's LDS limit) and return without launching, so that plan creation can get it out of the way
 // of a later stream capture.

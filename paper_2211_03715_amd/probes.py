@@ -6,6 +6,8 @@
 The kernels mark phase boundaries with TDC_PROBE(slot) (tdc_mfma.h).  One-launch kernels: 0 = kernel entry, 3 = end
 of stage 1, 4 = after the barrier behind it, 5 = end of stage 2, 7 = end of the kernel.  GEMM kernels (split, merged,
 dense): slots 5*(stage - 1) + {0: entry, 1: operands placed, 2: first loads issued, 3: MFMA loop done, 4: stored}.
+merged_xcd: 0 entry, 1 stage-1 loads issued, 2 its MFMAs done, 3 z1 stored, 4 past the barrier, 5 loads of the merged
+GEMM issued, 6 its MFMAs done, 7 end.
 This prints, per pair of consecutive marks (in time order), the median / min / max time over all wavefronts of one
 call and the shader clock in between -- which is how the per-phase budgets quoted in the design notes were taken.
 """
@@ -76,13 +78,13 @@ def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("shapes", nargs="+", metavar="B,C,N,H,W,R1,R2[,K,stride,pad]")
     ap.add_argument("--nhwc", action="store_true")
-    ap.add_argument("--variant", default="auto", choices=["auto", "fused", "chain", "fused_merged", "merged", "split"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "fused", "chain", "fused_merged", "merged", "merged_xcd", "split"])
     args = ap.parse_args(argv)
     import torch
     if not torch.cuda.is_available():
         sys.exit("probes needs a GPU")
     variant = {"auto": None, "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN, "fused_merged": B.VARIANT_FUSED_MERGED,
-               "merged": B.VARIANT_MERGED, "split": B.VARIANT_SPLIT}[args.variant]
+               "merged": B.VARIANT_MERGED, "merged_xcd": B.VARIANT_MERGED_XCD, "split": B.VARIANT_SPLIT}[args.variant]
     for spec in args.shapes:
         L = Layer(*[int(v) for v in spec.split(",")])
         desc, us, phases = phase_times(L, B.make_tuning(variant=variant) if variant else None,

@@ -15,7 +15,8 @@ from parity_util import assert_parity
 pytestmark = pytest.mark.gpu
 
 VARIANTS = {"naive": B.VARIANT_NAIVE, "split": B.VARIANT_SPLIT, "fused": B.VARIANT_FUSED, "chain": B.VARIANT_CHAIN,
-            "merged": B.VARIANT_MERGED, "fused_merged": B.VARIANT_FUSED_MERGED, "auto": B.VARIANT_AUTO}
+            "merged": B.VARIANT_MERGED, "fused_merged": B.VARIANT_FUSED_MERGED, "merged_xcd": B.VARIANT_MERGED_XCD,
+            "auto": B.VARIANT_AUTO}
 
 # C and N multiples of 4 (the layout's requirement), everything else ragged
 SMALL = [
