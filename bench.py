@@ -163,6 +163,77 @@ def cpu_baseline(layers, inputs, budget_s=12.0, max_sweeps=100000):
             "us_per_sweep": dt / sweeps * 1e6}
 
 
+def _in_flight(torch, Lt, t, xt, yt, layout, n_cus, n_str, share, rounds_timed=100, repeats=5):
+    """`n_str` independent calls of layer Lt in flight: one plan, one set of buffers and one stream (default priority)
+    per call, launched round-robin; plans made for 1/`share` of the chip.  Returns (sorted seconds per call, plan)."""
+    from paper_2211_03715_amd import binding as B
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    shape_t = B.make_shape(**Lt.asdict(), layout=layout)
+    streams = [torch.cuda.Stream() for _ in range(n_str)]
+    cs, ls, keep = [], [], []
+    for st in streams:
+        tun = B.tdc_select_tuning(shape_t, compute_units=n_cus // share) if share > 1 else None
+        c = TuckerConv2d(Lt, 0, tun, layout=layout)
+        c.pack(t["U_in"], t["core"], t["U_out"])
+        xs_, ys_ = xt.clone(), torch.empty_like(yt)
+        keep.append((xs_, ys_))
+        torch.cuda.synchronize()
+        ls.append(c.bind(xs_, ys_, stream=st.cuda_stream))
+        cs.append(c)
+
+    def rounds(n):
+        for _ in range(n):
+            for l in ls:
+                l()
+
+    rounds(30)
+    torch.cuda.synchronize()
+    per_call = []
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        rounds(rounds_timed)
+        torch.cuda.synchronize()
+        per_call.append((time.perf_counter() - t0) / (rounds_timed * n_str))
+    plan = cs[0].describe()
+    for c in cs:
+        c.close()
+    per_call.sort()
+    return per_call, plan
+
+
+def in_flight_only(args):
+    """--in-flight LAYER:STREAMS:SHARE -- only that measurement, for a kernel trace of calls in flight: layer LAYER of
+    workload 6 with STREAMS calls in flight and plans made for 1/SHARE of the chip; then the same layer on one stream."""
+    import torch
+    from paper_2211_03715_amd import binding as B, roofline as R
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    from paper_2211_03715_amd.workloads import config_layers, layer_seed, make_inputs
+    idx, n_str, share = (int(v) for v in args.in_flight.split(":"))
+    B.load()
+    dev = torch.device("cuda:0")
+    layout = B.LAYOUT_NHWC if args.layout == "nhwc" else B.LAYOUT_NCHW
+    Lt = config_layers(6)[idx]
+    t = {k: torch.from_numpy(v).to(dev) for k, v in make_inputs(Lt, layer_seed(6, idx)).items()}
+    xt = t["x"].permute(0, 2, 3, 1).contiguous() if layout == B.LAYOUT_NHWC else t["x"]
+    ct = TuckerConv2d(Lt, 0, None, layout=layout)
+    yt = torch.empty(ct.out_shape(), device=dev, dtype=torch.float32)
+    n_cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    pc, plan = _in_flight(torch, Lt, t, xt, yt, layout, n_cus, n_str, share, rounds_timed=200, repeats=3)
+    ct.pack(t["U_in"], t["core"], t["U_out"])
+    lt = ct.bind(xt, yt)
+    for _ in range(100):
+        lt()
+    alone, _, _ = _time_repeats(lt, 200, 3, torch)
+    torch.cuda.synchronize()
+    print(json.dumps({"layer": Lt.name(), "layout": args.layout, "streams": n_str, "planned_for_chip_share": "1/%d" % share,
+                      "plan_in_flight": plan, "us_per_call_in_flight": pc[len(pc) // 2] * 1e6,
+                      "frac_of_fp32_mfma_peak_in_flight": R.flops(Lt) / pc[len(pc) // 2] / R.FP32_MFMA_PEAK,
+                      "plan_alone": ct.describe(), "us_per_call_alone": alone * 1e6,
+                      "frac_of_fp32_mfma_peak_alone": R.flops(Lt) / alone / R.FP32_MFMA_PEAK}))
+    ct.close()
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,6 +243,8 @@ def main():
     ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged", "fused_merged", "merged_xcd"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"],
                     help="activation layout (default NCHW, the layout the metric's workload is stated in)")
+    ap.add_argument("--in-flight", default="", metavar="LAYER:STREAMS:SHARE",
+                    help="only: layer LAYER of workload 6 with STREAMS calls in flight, plans for 1/SHARE of the chip (for a kernel trace)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the per-layer oracle times")
     ap.add_argument("--brief", action="store_true",
                     help="only the queued latency per layer (no sync / cold-cache / dense-kernel columns)")
@@ -184,6 +257,11 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if args.in_flight:
+        import torch
+        if not torch.cuda.is_available():
+            sys.exit("bench.py needs a GPU")
+        return in_flight_only(args)
 
     import torch
     from paper_2211_03715_amd import binding as B
@@ -439,40 +517,10 @@ def main():
             # chosen for the whole chip (the default) and for half of it (tdc_select_tuning with half the compute
             # units: a call that shares the GPU is better off with fewer, larger workgroups).  The best of the six is
             # reported with its settings, all six are listed.
-            shape_t = B.make_shape(**Lt.asdict(), layout=layout)
             n_cus = torch.cuda.get_device_properties(dev).multi_processor_count
 
             def in_flight(n_str, share):
-                streams = [torch.cuda.Stream() for _ in range(n_str)]
-                cs, ls, keep = [], [], []
-                for st in streams:
-                    tun = B.tdc_select_tuning(shape_t, compute_units=n_cus // share) if share > 1 else None
-                    c = TuckerConv2d(Lt, 0, tun, layout=layout)
-                    c.pack(t["U_in"], t["core"], t["U_out"])
-                    xs_, ys_ = xt.clone(), torch.empty_like(yt)
-                    keep.append((xs_, ys_))
-                    torch.cuda.synchronize()
-                    ls.append(c.bind(xs_, ys_, stream=st.cuda_stream))
-                    cs.append(c)
-
-                def rounds(n):
-                    for _ in range(n):
-                        for l in ls:
-                            l()
-
-                rounds(30)
-                torch.cuda.synchronize()
-                per_call = []
-                for _ in range(5):
-                    t0 = time.perf_counter()
-                    rounds(100)
-                    torch.cuda.synchronize()
-                    per_call.append((time.perf_counter() - t0) / (100 * n_str))
-                plan = cs[0].describe()
-                for c in cs:
-                    c.close()
-                per_call.sort()
-                return per_call, plan
+                return _in_flight(torch, Lt, t, xt, yt, layout, n_cus, n_str, share)
 
             tried = {(n, sh): in_flight(n, sh) for sh in (1, 2) for n in (2, 3, 4)}
             k_best = min(tried, key=lambda k: tried[k][0][2])
