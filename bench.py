@@ -27,7 +27,8 @@ weights already resident in HBM.  Prints ONE JSON line.
                other batched layers (28x28 and 14x14 at batch 32 and 128, the stride-2 layer at batch 64); each
                carries `concurrent`: time per call with 2 / 3 / 4 independent calls in flight on as many streams
   resnet50_body  the 16 bottleneck blocks (65 kernels) of a ResNet-50-shaped network at batch 1, eagerly and as
-               one HIP graph, NCHW and NHWC
+               one HIP graph, NCHW and NHWC; resnet18_body the same for the 8 basic blocks (16 Tucker-2 layers) of a
+               ResNet-18-shaped one
   graph_replay_us_per_step  the step replayed from a HIP graph (--graph-study explains the difference to eager)
   cpu_baseline the CPU oracle (three-stage, fp64) timed on the host cores on the same sweep
 """
@@ -550,6 +551,19 @@ def main():
             chains.append(entry)
             net.close()
         out["resnet50_body"] = chains
+        # and the ResNet-18-shaped one: 8 basic blocks whose 16 3x3 convolutions are all Tucker-2 layers (the shapes of
+        # this sweep and their stride-2 neighbours, chained with shortcuts and epilogues)
+        from paper_2211_03715_amd.bottleneck import TuckerResNet18Body
+        chains18 = []
+        for lay_name, lay in (("nchw", B.LAYOUT_NCHW), ("nhwc", B.LAYOUT_NHWC)):
+            net = TuckerResNet18Body(1, layout=lay)
+            entry = {"network": "ResNet-18 residual stages (8 basic blocks, 16 Tucker-2 3x3 layers), 64x56x56 in, 512x7x7 out, batch 1",
+                     "layout": lay_name, "kernels": net.kernels(), "gflop": net.flops() / 1e9}
+            entry.update(time_network(net))
+            entry["graph_gflops"] = net.flops() / entry["graph_us"] / 1e3
+            chains18.append(entry)
+            net.close()
+        out["resnet18_body"] = chains18
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, host_inputs)
         if not args.brief:

@@ -16,8 +16,15 @@ A block that changes width or resolution (the first of a ResNet stage) has strid
 a projection shortcut, one more dense 1x1 launch:   s = Wp (*) x + bp,   y = relu(W3 (*) t2 + b3 + s).
 TuckerResNetBody strings 3 + 4 + 6 + 3 such blocks into the residual stages of a ResNet-50-shaped network.
 
+TuckerBasicBlock is the two-convolution block of the shallower networks, both 3x3 convolutions in Tucker-2 form:
+    t1 = relu(Tucker3x3_a(x) + b1)             C -> M, stride s
+    y  = relu(Tucker3x3_b(t1) + b2 + s(x))     M -> M; s(x) = x, or Wp (*) x + bp where the block changes shape
+and TuckerResNet18Body the 2 + 2 + 2 + 2 of them of a ResNet-18-shaped network (16 Tucker layers: the shapes of the
+batch-1 benchmark sweep, in sequence, with their shortcuts and epilogues).
+
     python -m paper_2211_03715_amd.bottleneck [--nhwc]             # eager vs graph latency of a few block shapes
     python -m paper_2211_03715_amd.bottleneck --resnet50 [--nhwc] [--batch B]   # the 16-block network
+    python -m paper_2211_03715_amd.bottleneck --resnet18 [--nhwc] [--batch B]   # the 8 basic blocks
 """
 from __future__ import annotations
 
@@ -133,6 +140,82 @@ class TuckerBottleneck:
             c.close()
 
 
+def make_basic_weights(C: int, M: int, Ra: tuple, Rb: tuple, seed: int, projection: bool = False) -> Dict[str, np.ndarray]:
+    """Seeded float32 weights of one basic block, N(0, 1/fan_in); biases N(0, 0.01).  Ra, Rb = (R1, R2) of the two layers."""
+    rng = np.random.default_rng(seed)
+    n = lambda shape, fan: (rng.standard_normal(shape, dtype=np.float32) * np.float32(fan ** -0.5))
+    w = {"Ua_in": n((C, Ra[0]), C), "core_a": n((Ra[0], Ra[1], 3, 3), Ra[0] * 9), "Ua_out": n((Ra[1], M), Ra[1]), "b1": n((M,), 100.0),
+         "Ub_in": n((M, Rb[0]), M), "core_b": n((Rb[0], Rb[1], 3, 3), Rb[0] * 9), "Ub_out": n((Rb[1], M), Rb[1]), "b2": n((M,), 100.0)}
+    if projection:
+        w["Wp"], w["bp"] = n((C, M, 1, 1), C), n((M,), 100.0)
+    return w
+
+
+class TuckerBasicBlock:
+    def __init__(self, batch: int, C: int, M: int, H: int, W: int, Ra: tuple, Rb: tuple, weights: Dict, device: int = 0,
+                 layout: int = B.LAYOUT_NCHW, stride: int = 1):
+        """Two Tucker-2 3x3 convolutions, C -> M (``stride``) and M -> M, ranks Ra = (R1, R2) and Rb; a projection
+        shortcut (dense 1x1, same stride, weights "Wp", "bp") when stride != 1 or M != C."""
+        import torch
+        self.dev = torch.device("cuda", device)
+        self.layout = layout
+        self.projection = stride != 1 or M != C
+        self.la = Layer(batch, C, M, H, W, Ra[0], Ra[1], 3, stride, 1)
+        self.lb = Layer(batch, M, M, self.la.Ho, self.la.Wo, Rb[0], Rb[1], 3, 1, 1)
+        self.lp = Layer(batch, C, M, H, W, 1, 1, 1, stride, 0) if self.projection else None
+        self.w = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.dev) for k, v in weights.items()}
+        self.conva, self.convb = TuckerConv2d(self.la, device, layout=layout), TuckerConv2d(self.lb, device, layout=layout)
+        self.convp = DenseConv2d(self.lp, device, layout=layout) if self.projection else None
+        self.conva.pack(self.w["Ua_in"], self.w["core_a"], self.w["Ua_out"])
+        self.convb.pack(self.w["Ub_in"], self.w["core_b"], self.w["Ub_out"])
+        self.t1 = torch.empty(self.conva.out_shape(), device=self.dev, dtype=torch.float32)
+        self.y = torch.empty(self.convb.out_shape(), device=self.dev, dtype=torch.float32)
+        self.s = None
+        if self.projection:
+            self.convp.pack(self.w["Wp"])
+            self.s = torch.empty(self.convp.out_shape(), device=self.dev, dtype=torch.float32)
+            assert tuple(self.s.shape) == tuple(self.y.shape)
+        self._launchers = None
+        self._x = None
+
+    def bind(self, x):
+        self._x = x
+        first = (self.convp.bind(x, self.s, bias=self.w["bp"]),) if self.projection else ()
+        wa = (self.w["Ua_in"], self.w["core_a"], self.w["Ua_out"])
+        wb = (self.w["Ub_in"], self.w["core_b"], self.w["Ub_out"])
+        self._launchers = first + (
+            self.conva.bind(x, self.t1, weights=wa, bias=self.w["b1"], relu=True),
+            self.convb.bind(self.t1, self.y, weights=wb, bias=self.w["b2"], residual=self.s if self.projection else x, relu=True),
+        )
+        return self
+
+    def __call__(self, x=None):
+        if x is None:
+            x = self._x
+        if self._launchers is None or x.data_ptr() != self._x.data_ptr():
+            self.bind(x)
+        for launch in self._launchers:
+            launch()
+        return self.y
+
+    def kernels(self) -> int:
+        return self.conva.kernel_count() + self.convb.kernel_count() + (1 if self.projection else 0)
+
+    def flops(self) -> int:
+        from . import roofline as R
+        dense = lambda L: 2 * L.batch * L.C * L.N * L.K * L.K * L.Ho * L.Wo
+        return R.flops(self.la) + R.flops(self.lb) + (dense(self.lp) if self.projection else 0)
+
+    def describe(self) -> str:
+        head = "shortcut 1x1: %s | " % self.convp.describe() if self.projection else ""
+        return head + "3x3: %s | 3x3: %s" % (self.conva.describe(), self.convb.describe())
+
+    def close(self) -> None:
+        for c in (self.conva, self.convb, self.convp):
+            if c is not None:
+                c.close()
+
+
 def default_rank(M: int) -> int:
     """The rank the synthetic networks give a 3x3 layer of M channels: 0.3 M rounded to a multiple of 8, at least 8."""
     return max(8, int(round(0.3 * M / 8.0)) * 8)
@@ -205,6 +288,35 @@ class TuckerResNetBody:
             b.close()
 
 
+class TuckerResNet18Body(TuckerResNetBody):
+    """The four residual stages of a ResNet-18-shaped network: ``blocks`` = (2, 2, 2, 2) basic blocks of widths width,
+    2 width, 4 width, 8 width, every 3x3 convolution in Tucker-2 form with ranks ``rank(channels)`` on each side (default
+    a quarter of the channels: the ranks of the batch-1 benchmark sweep); from the second stage on the first block of a
+    stage has stride 2 and a projection shortcut.  Input: the stem's output, [batch][width][H][W] (64 x 56 x 56)."""
+
+    def __init__(self, batch: int, H: int = 56, W: int = 56, width: int = 64, blocks=(2, 2, 2, 2), rank=lambda ch: max(1, ch // 4),
+                 seed: int = 0, device: int = 0, layout: int = B.LAYOUT_NCHW):
+        import torch
+        self.dev = torch.device("cuda", device)
+        self.layout = layout
+        self.batch, self.width = batch, width
+        self.blocks = []
+        self.weights = []
+        C, h, w = width, H, W
+        for stage, count in enumerate(blocks):
+            M = width << stage
+            for i in range(count):
+                stride = 2 if (i == 0 and stage > 0) else 1
+                Ra, Rb = (rank(C), rank(M)), (rank(M), rank(M))
+                wts = make_basic_weights(C, M, Ra, Rb, seed + 100 * stage + i, projection=stride != 1 or M != C)
+                blk = TuckerBasicBlock(batch, C, M, h, w, Ra, Rb, wts, device, layout, stride=stride)
+                self.blocks.append(blk)
+                self.weights.append(wts)
+                C, h, w = M, blk.la.Ho, blk.la.Wo
+        self.in_shape = (batch, H, W, width) if layout == B.LAYOUT_NHWC else (batch, width, H, W)
+        self.y = self.blocks[-1].y
+
+
 def time_network(net, iters: int = 100, repeats: int = 5) -> Dict[str, float]:
     """Median over ``repeats`` of the time per pass (HIP events around ``iters`` passes), eagerly and from one graph."""
     import torch
@@ -238,13 +350,15 @@ def main(argv=None) -> int:
         sys.exit("bottleneck needs a GPU")
     B.load()
     layout = B.LAYOUT_NHWC if argv and "--nhwc" in argv else B.LAYOUT_NCHW
-    if argv and "--resnet50" in argv:
+    if argv and ("--resnet50" in argv or "--resnet18" in argv):
         batch = int(argv[argv.index("--batch") + 1]) if "--batch" in argv else 1
-        net = TuckerResNetBody(batch, layout=layout)
+        deep = "--resnet50" in argv
+        net = TuckerResNetBody(batch, layout=layout) if deep else TuckerResNet18Body(batch, layout=layout)
         r = time_network(net)
         print(net.describe())
-        print("ResNet-50 body, batch %d, %s: %d blocks, %d kernels, %.3f GFLOP; eager %.1f us, one graph %.1f us" % (
-            batch, "NHWC" if layout else "NCHW", len(net.blocks), net.kernels(), net.flops() / 1e9, r["eager_us"], r["graph_us"]))
+        print("ResNet-%d body, batch %d, %s: %d blocks, %d kernels, %.3f GFLOP; eager %.1f us, one graph %.1f us" % (
+            50 if deep else 18, batch, "NHWC" if layout else "NCHW", len(net.blocks), net.kernels(), net.flops() / 1e9,
+            r["eager_us"], r["graph_us"]))
         net.close()
         return 0
     print("%-34s %8s %10s %10s  %s" % ("block (batch 1, %s)" % ("NHWC" if layout else "NCHW"), "kernels", "eager us", "graph us", "plans"),

@@ -207,3 +207,75 @@ def test_resnet_body_eager_and_one_graph(orc, case, layout):
             assert torch.equal(eager, replayed)
     finally:
         net.close()
+
+
+def _oracle_basic_block(orc, blk, w, x):
+    ya, _ = orc.conv_factored(orc.Shape(**blk.la.asdict()), x, w["Ua_in"], w["core_a"], w["Ua_out"])
+    t1 = orc.apply_epilogue(ya, w["b1"], None, True).astype(np.float32)        # the GPU stores t1 in fp32
+    yb, _ = orc.conv_factored(orc.Shape(**blk.lb.asdict()), t1, w["Ub_in"], w["core_b"], w["Ub_out"])
+    s = x
+    if blk.projection:
+        yp, _ = orc.conv_dense_with(orc.Shape(**blk.lp.asdict()), x, w["Wp"].astype(np.float64))
+        s = orc.apply_epilogue(yp, w["bp"], None, False).astype(np.float32)
+    return orc.apply_epilogue(yb, w["b2"], s, True)
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_NCHW, B.LAYOUT_NHWC], ids=["nchw", "nhwc"])
+@pytest.mark.parametrize("case", [(2, 16, 32, 32), (1, 64, 56, 56)], ids=["b2_width16_32x32", "resnet18_b1_width64_56x56"])
+def test_resnet18_body_eager_and_one_graph(orc, case, layout):
+    """2 + 2 + 2 + 2 basic blocks, both 3x3 convolutions of each in Tucker-2 form (16 Tucker layers: at full size the
+    shapes of the batch-1 benchmark sweep and its stride-2 layers, chained with their shortcuts).  Every block's output
+    against the oracle chained from the network input, every block alone on the input the GPU gave it, and the whole
+    network replayed from ONE HIP graph on changing inputs with eager runs in between."""
+    import torch
+    from paper_2211_03715_amd.bottleneck import TuckerResNet18Body
+    batch, width, H, W = case
+    print("[case] resnet18 body", case, "layout", layout, flush=True)
+    sys.stdout.flush()
+    net = TuckerResNet18Body(batch, H, W, width, layout=layout, seed=60)
+    perm, unperm = _perm(layout), _unperm(layout)
+
+    def oracle_network(x):
+        outs = []
+        for blk, w in zip(net.blocks, net.weights):
+            x = _oracle_basic_block(orc, blk, w, x).astype(np.float32)
+            outs.append(x)
+        return outs
+
+    try:
+        assert len(net.blocks) == 8 and [b.projection for b in net.blocks] == [i in (2, 4, 6) for i in range(8)]
+        assert [b.la.stride for b in net.blocks] == [2 if i in (2, 4, 6) else 1 for i in range(8)]
+        assert [(b.la.R1, b.la.R2) for b in net.blocks[:3]] == [(width // 4, width // 4)] * 2 + [(width // 4, width // 2)]
+        rng = np.random.default_rng(9)
+        xs = [rng.standard_normal((batch, width, H, W), dtype=np.float32) for _ in range(2)]
+        x_static = torch.from_numpy(perm(xs[0])).to(net.dev)
+        got = net(x_static)
+        torch.cuda.synchronize()
+        assert tuple(got.shape) == ((batch, H // 8, W // 8, 8 * width) if layout == B.LAYOUT_NHWC else (batch, 8 * width, H // 8, W // 8))
+        wants = oracle_network(xs[0])
+        for i, (blk, want) in enumerate(zip(net.blocks, wants)):
+            assert_parity(blk.y.cpu().numpy(), perm(want), "network up to block %d" % i)
+        x_in = xs[0]
+        for i, (blk, w) in enumerate(zip(net.blocks, net.weights)):
+            assert_parity(blk.y.cpu().numpy(), perm(_oracle_basic_block(orc, blk, w, x_in)), "block %d alone" % i)
+            x_in = unperm(blk.y.cpu().numpy())
+        eager_first = got.clone()
+        graph = net.capture(x_static)
+        assert net.kernels() >= 16 + 3
+        for rep, k in enumerate((1, 0, 1)):
+            x_static.copy_(torch.from_numpy(perm(xs[k])).to(net.dev))
+            for blk in net.blocks:
+                blk.y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            replayed = net.y.clone()
+            if k == 0:
+                assert torch.equal(replayed, eager_first)
+            else:
+                assert_parity(replayed.cpu().numpy(), perm(oracle_network(xs[1])[-1]), "graph replay %d" % rep)
+            eager = net(x_static).clone()
+            torch.cuda.synchronize()
+            assert torch.equal(eager, replayed)
+    finally:
+        net.close()
