@@ -240,7 +240,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=2, help="workload id 1..6 (default 2: the ResNet-18-shaped sweep)")
+    ap.add_argument("--config", type=int, default=2, help="workload id 1..7 (default 2: the ResNet-18-shaped sweep)")
     ap.add_argument("--variant", default="auto", choices=["auto", "naive", "split", "fused", "chain", "merged", "fused_merged", "merged_xcd"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"],
                     help="activation layout (default NCHW, the layout the metric's workload is stated in)")
@@ -436,7 +436,9 @@ def main():
             4: "stride/batch variants: 128->256 s2 56->28 r32/64 and 128->128 28x28 r32, batch 1/8/32",
             5: "ResNet-50-style chain of 16 Tucker-2 3x3 layers, ranks round(0.3C) to 8, batch 1",
             6: "throughput set: 128->256 s2 56->28 r32/64 at batch 32 and 64, 128->128 28x28 r32 at batch 32 and 128, "
-               "256->256 14x14 r64 at batch 32 and 128"}[args.config]),
+               "256->256 14x14 r64 at batch 32 and 128",
+            7: "large-image layers of a VGG-16-shaped network, batch 1: 64->64 224x224 r64/32, 128->128 112x112 r64/32, 128->256 and "
+               "256->256 56x56, 512->512 28x28 and 14x14 at a quarter of the channels"}[args.config]),
             "layers_per_step": len(layers), "variant": args.variant, "layout": args.layout},
         "roofline": roof,
         "layers": per_layer,

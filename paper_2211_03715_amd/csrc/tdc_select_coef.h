@@ -6,7 +6,7 @@
 #define TDC_SELECT_COEF_H
 
 // fused, latency regime: launch s1_unit s1_kg s1_mfma s1r_unit s1r_kg s1r_mfma s2_kg_lds s2_kg_glb s2_mfma s3_unit s3_kg_lds s3_kg_glb s3_mfma w_kb x_mb_nchw x_mb_nhwc x_mb_runs y_mb_nchw y_mb_nhwc x_rows y_rows
-static const double kFusedLatencyCoef[22] = {3.5583, 1.2599, 0.0435, 0.0751, 0, 0, 0, 0.0186, 0.0356, 0, 0.3151, 0.0806, 0.0875, 0.2474, 0.0340, 0, 0, 0, 0, 0, 0, 0};
+static const double kFusedLatencyCoef[22] = {3.0025, 0.1184, 0, 0.0828, 0, 0, 0, 0.1051, 0.1331, 0.0037, 0.1798, 0.0151, 0, 0.1193, 0.0166, 42.3792, 28.4607, 0, 7.0969, 0, 0.9402, 0};
 // fused, throughput regime: same terms
 static const double kFusedThroughputCoef[22] = {3.8605, 0, 0.0988, 0.0347, 0.6828, 0.1891, 0.0176, 0.0560, 0.0826, 0.0210, 0.1531, 0.0330, 0.0167, 0.1457, 0.0207, 19.2123, 11.7344, 6.1081, 48.2178, 30.6810, 0.2834, 0.4272};
 // chain: launch s1_unit s1_kg s1_mfma s1r_unit s1r_kg s1r_mfma kg2_lds kg2_glb blk2 nb3_lds blk3 w_kb x_mb_nchw x_mb_nhwc x_mb_runs y_mb x_rows y_rows novec

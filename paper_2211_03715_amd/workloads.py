@@ -62,8 +62,8 @@ def _round8(v: float) -> int:
 
 
 def config_layers(config_id: int) -> List[Layer]:
-    """The five synthetic workloads, numbered 1..5, and 6: this library's own throughput set (layers of 4 and a
-    14x14 layer at batch sizes that fill the chip)."""
+    """The five synthetic workloads, numbered 1..5; 6: this library's own throughput set (layers of 4 and a
+    14x14 layer at batch sizes that fill the chip); 7: the large-image layers of a VGG-16-shaped network at batch 1."""
     if config_id == 1:   # single layer, the primary parity case
         return [Layer(1, 64, 64, 56, 56, 16, 16)]
     if config_id == 2:   # ResNet-18-shaped sweep, R = C/4
@@ -90,7 +90,12 @@ def config_layers(config_id: int) -> List[Layer]:
         return [Layer(32, 128, 256, 56, 56, 32, 64, 3, 2, 1), Layer(32, 128, 128, 28, 28, 32, 32),
                 Layer(32, 256, 256, 14, 14, 64, 64), Layer(128, 256, 256, 14, 14, 64, 64),
                 Layer(128, 128, 128, 28, 28, 32, 32), Layer(64, 128, 256, 56, 56, 32, 64, 3, 2, 1)]
-    raise ValueError("config_id must be 1..6")
+    if config_id == 7:   # large images, few channels (section 7.2 names core shapes (64, 32) at 224x224 and 112x112 as its
+        # kernel's weak spot); then the deeper VGG-16-shaped layers at a quarter of the channels
+        return [Layer(1, 64, 64, 224, 224, 64, 32), Layer(1, 128, 128, 112, 112, 64, 32),
+                Layer(1, 128, 256, 56, 56, 32, 64), Layer(1, 256, 256, 56, 56, 64, 64),
+                Layer(1, 512, 512, 28, 28, 128, 128), Layer(1, 512, 512, 14, 14, 128, 128)]
+    raise ValueError("config_id must be 1..7")
 
 
 def layer_seed(config_id: int, layer_index: int) -> int:

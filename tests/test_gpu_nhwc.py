@@ -116,7 +116,7 @@ def test_nhwc_epilogue(orc, variant, layer):
     assert_parity(got, nhwc(want), "nhwc epilogue %s %s [%s]" % (variant, layer.name(), desc))
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6, 7])
 def test_nhwc_full_size_workloads(orc, cfg):
     """All five workloads at full size with the selector's choice."""
     for i, layer in enumerate(config_layers(cfg)):

@@ -146,7 +146,7 @@ def test_fused_merged_refuses_what_it_cannot_hold():
     assert err.value.status == B.TDC_ERR_BAD_TUNING
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6, 7])
 def test_full_size_workloads(orc, cfg):
     """Every layer of the synthetic workloads (the five stated ones and the throughput set) at full size, in the launch configuration the
     benchmark times (selector's choice, weights re-laid out once), compared element by element."""
