@@ -24,7 +24,7 @@ weights already resident in HBM.  Prints ONE JSON line.
   null_launch_us  an empty kernel timed the same way: the floor any batch-1 layer sits on
   throughput_regime  the batch-32 128->256 stride-2 layer (config 4) timed the same way, against the
                fp32 MFMA peak: a side figure, not part of value; throughput_layers lists it with the
-               other batched layers (28x28 and 14x14 at batch 32 and 128, the stride-2 layer at batch 64); each
+               other batched layers (28x28 and 14x14 at batch 32, 128 and 256, the stride-2 layer at batch 64); each
                carries `concurrent`: time per call with 2 / 3 / 4 independent calls in flight on as many streams
   resnet50_body  the 16 bottleneck blocks (65 kernels) of a ResNet-50-shaped network at batch 1, eagerly and as
                one HIP graph, NCHW and NHWC; resnet18_body the same for the 8 basic blocks (16 Tucker-2 layers) of a
@@ -435,8 +435,8 @@ def main():
             3: "rank sweep at C=N=256, 14x14, (R1,R2) in {8,16,32,64,128}^2, batch 1",
             4: "stride/batch variants: 128->256 s2 56->28 r32/64 and 128->128 28x28 r32, batch 1/8/32",
             5: "ResNet-50-style chain of 16 Tucker-2 3x3 layers, ranks round(0.3C) to 8, batch 1",
-            6: "throughput set: 128->256 s2 56->28 r32/64 at batch 32 and 64, 128->128 28x28 r32 at batch 32 and 128, "
-               "256->256 14x14 r64 at batch 32 and 128",
+            6: "throughput set: 128->256 s2 56->28 r32/64 at batch 32 and 64, 128->128 28x28 r32 at batch 32, 128 and 256, "
+               "256->256 14x14 r64 at batch 32, 128 and 256",
             7: "large-image layers of a VGG-16-shaped network, batch 1: 64->64 224x224 r64/32, 128->128 112x112 r64/32, 128->256 and "
                "256->256 56x56, 512->512 28x28 and 14x14 at a quarter of the channels"}[args.config]),
             "layers_per_step": len(layers), "variant": args.variant, "layout": args.layout},

@@ -89,7 +89,8 @@ def config_layers(config_id: int) -> List[Layer]:
     if config_id == 6:   # throughput regime: every compute unit gets work
         return [Layer(32, 128, 256, 56, 56, 32, 64, 3, 2, 1), Layer(32, 128, 128, 28, 28, 32, 32),
                 Layer(32, 256, 256, 14, 14, 64, 64), Layer(128, 256, 256, 14, 14, 64, 64),
-                Layer(128, 128, 128, 28, 28, 32, 32), Layer(64, 128, 256, 56, 56, 32, 64, 3, 2, 1)]
+                Layer(128, 128, 128, 28, 28, 32, 32), Layer(64, 128, 256, 56, 56, 32, 64, 3, 2, 1),
+                Layer(256, 256, 256, 14, 14, 64, 64), Layer(256, 128, 128, 28, 28, 32, 32)]
     if config_id == 7:   # large images, few channels (section 7.2 names core shapes (64, 32) at 224x224 and 112x112 as its
         # kernel's weak spot); then the deeper VGG-16-shaped layers at a quarter of the channels
         return [Layer(1, 64, 64, 224, 224, 64, 32), Layer(1, 128, 128, 112, 112, 64, 32),
