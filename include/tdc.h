@@ -60,10 +60,10 @@ typedef enum tdc_status {
                                      TDC_STATIC_SCRATCH_BYTES                                  */
     TDC_ERR_NO_CONVERGENCE = -9,  /* tdc_hosvd_tucker2 / tdc_admm_project: an eigen-decomposition did not reach
                                      its tolerance within the sweep limit; outputs are not written             */
-    TDC_ERR_WAIT = -10            /* a TDC_VARIANT_MERGED_XCD kernel gave up waiting for the other workgroups of its
-                                     launch; the y of that call is incomplete.  Kernels run asynchronously, so the
-                                     error is returned by tdc_plan_status and by every LATER tdc_conv_tucker2 call
-                                     on the plan, which then enqueues nothing                                  */
+    TDC_ERR_WAIT = -10            /* a TDC_VARIANT_MERGED_XCD kernel found itself on a device whose XCD or workgroup
+                                     numbering it was not written for and wrote nothing.  Kernels run asynchronously,
+                                     so the error is returned by tdc_plan_status and by every LATER tdc_conv_tucker2
+                                     call on the plan, which then enqueues nothing                             */
 } tdc_status;
 
 /* Layer geometry.  Supported domain: square K in 1..7; stride in 1..4; pad in 0..K-1; any
@@ -107,13 +107,13 @@ enum {
                                MERGED's two kernels is a quarter of the layer's time: the workgroups that
                                run on one XCD (they share its L2) compute all of stage 1 into that XCD's own
                                copy of z1, meet at a barrier among themselves, and run their share of the
-                               merged K x K GEMM on it.  Every wait is bounded (TDC_ERR_WAIT).  One call at a
-                               time per GPU is what it is made for: the up to 256 workgroups of a launch must
-                               all be resident for the barrier to open, so launches that crowd the GPU from
-                               other streams can make it wait, at worst until it gives up.  Tuning: waves[0],
+                               merged K x K GEMM on it.  The wait at the barrier is bounded: a workgroup whose
+                               partners do not arrive in time (a launch of up to 256 workgroups is only fully
+                               resident when other streams leave it the room) stops waiting and computes all of
+                               stage 1 itself -- slower, same bits, never a deadlock.  Tuning: waves[0],
                                waves[1] = wavefronts that split the contraction of one 16x16 output block in
                                stage 1 / in the merged GEMM (1, 2, 4 or 8); mb and pb must be 1.  Workspace:
-                               8 copies of z1                                                       */
+                               8 copies of z1.  Never chosen by AUTO                                */
     TDC_VARIANT_DENSE = 5   /* not a Tucker kernel: the undecomposed K x K layer as one implicit-GEMM
                                MFMA kernel, for tdc_conv_dense only.  Never chosen by AUTO; a plan
                                made with it ignores R1 and R2                                   */
@@ -222,9 +222,9 @@ int tdc_plan_get_tuning(const tdc_plan *plan, tdc_tuning *out);          /* what
 int tdc_plan_describe(const tdc_plan *plan, char *buf, size_t buf_len);  /* one line of text        */
 size_t tdc_plan_workspace_bytes(const tdc_plan *plan);                   /* device bytes owned      */
 int tdc_plan_kernel_count(const tdc_plan *plan);                         /* launches per conv call (weights packed) */
-/* TDC_OK, or TDC_ERR_WAIT once a kernel of a TDC_VARIANT_MERGED_XCD plan has given up a wait (sticky; reads a word
- * in pinned host memory that the kernel writes, so call it after the stream has been synchronised to learn about
- * the calls enqueued so far).  Always TDC_OK for other variants; TDC_ERR_NULL for a NULL plan. */
+/* TDC_OK, or TDC_ERR_WAIT once a kernel of a TDC_VARIANT_MERGED_XCD plan has reported that it cannot run on this
+ * device (sticky; reads a word in pinned host memory that the kernel writes, so call it after the stream has been
+ * synchronised to learn about the calls enqueued so far).  Always TDC_OK for other variants; TDC_ERR_NULL for a NULL plan. */
 int tdc_plan_status(const tdc_plan *plan);
 const char *tdc_status_string(int status);                               /* static string           */
 int tdc_version(void);

@@ -12,12 +12,15 @@ extern "C" {
  * can outweigh the saved FLOPs).  Returns TDC_OK or TDC_ERR_HIP. */
 int tdc_launch_null(void *hip_stream);
 
-/* Testing aid for TDC_VARIANT_MERGED_XCD plans: the number of times a workgroup polls for the others before it
- * gives up (default 1 << 17, tens of milliseconds).  0 makes every workgroup that is not the last to arrive give
- * up at once -- the way the tests reach the TDC_ERR_WAIT path with kernels that still end normally.  Also clears
- * the plan's sticky status.  TDC_ERR_BAD_TUNING for plans of other variants. */
+/* Testing aids for TDC_VARIANT_MERGED_XCD plans (TDC_ERR_BAD_TUNING for plans of other variants).
+ * tdc_plan_set_wait_limit: the number of times a workgroup polls for the others of its XCD before it stops waiting and
+ * computes all of stage 1 itself (default 512, some hundred microseconds).  0 makes every workgroup that is not the
+ * last to arrive take that path at once -- the way the tests exercise it.
+ * tdc_plan_waits_given_up: how many workgroups have taken it since the plan was made (copies one word from the
+ * device: synchronises). */
 struct tdc_plan;
 int tdc_plan_set_wait_limit(struct tdc_plan *plan, unsigned polls);
+int tdc_plan_waits_given_up(struct tdc_plan *plan, unsigned *count);
 
 #ifdef __cplusplus
 }

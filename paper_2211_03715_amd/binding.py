@@ -39,7 +39,7 @@ EXPORTS = ["tdc_plan_create", "tdc_plan_create_tuned", "tdc_plan_pack_weights", 
            "tdc_plan_kernel_count", "tdc_status_string", "tdc_version", "tdc_out_size",
            "tdc_select_tuning", "tdc_launch_null", "tdc_plan_pack_dense", "tdc_conv_dense", "tdc_select_ranks",
            "tdc_conv_tucker2_ex", "tdc_conv_dense_ex", "tdc_hosvd_tucker2", "tdc_admm_project",
-           "tdc_conv_tucker2_static", "tdc_model_terms", "tdc_plan_status", "tdc_plan_set_wait_limit"]
+           "tdc_conv_tucker2_static", "tdc_model_terms", "tdc_plan_status", "tdc_plan_set_wait_limit", "tdc_plan_waits_given_up"]
 
 
 class tdc_shape(ctypes.Structure):
@@ -141,6 +141,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.tdc_plan_status.restype = ip
     lib.tdc_plan_set_wait_limit.argtypes = [vp, ctypes.c_uint]
     lib.tdc_plan_set_wait_limit.restype = ip
+    lib.tdc_plan_waits_given_up.argtypes = [vp, ctypes.POINTER(ctypes.c_uint)]
+    lib.tdc_plan_waits_given_up.restype = ip
     lib.tdc_select_ranks.argtypes = [ctypes.POINTER(tdc_rank_layer), ip, ctypes.c_double, ctypes.c_double,
                                      ctypes.c_double, ctypes.POINTER(tdc_rank_choice)]
     lib.tdc_select_ranks.restype = ip
@@ -319,7 +321,7 @@ def tdc_plan_kernel_count(plan) -> int:
 
 
 def tdc_plan_status(plan) -> int:
-    """TDC_OK, or ERR_WAIT once a kernel of a MERGED_XCD plan has given up a wait (read after synchronising)."""
+    """TDC_OK, or ERR_WAIT once a kernel of a MERGED_XCD plan has reported that it cannot run here (read after synchronising)."""
     return int(load().tdc_plan_status(plan))
 
 
@@ -327,6 +329,14 @@ def tdc_plan_set_wait_limit(plan, polls: int) -> None:
     rc = load().tdc_plan_set_wait_limit(plan, polls)
     if rc != TDC_OK:
         raise TdcError(rc, "tdc_plan_set_wait_limit")
+
+
+def tdc_plan_waits_given_up(plan) -> int:
+    n = ctypes.c_uint(0)
+    rc = load().tdc_plan_waits_given_up(plan, ctypes.byref(n))
+    if rc != TDC_OK:
+        raise TdcError(rc, "tdc_plan_waits_given_up")
+    return int(n.value)
 
 
 def tdc_launch_null(stream=None) -> None:

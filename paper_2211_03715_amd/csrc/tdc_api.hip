@@ -17,9 +17,9 @@ struct tdc_plan {
     float *uin_p, *core_p, *uout_p;    // re-laid-out weights (SPLIT, FUSED, CHAIN; MERGED keeps the merged kernel in core_p)
     float *wm;                         // MERGED: core x_2 U_out in the caller's layout, before re-layout
     const float *packed_from[3];       // caller pointers the stored copy was made from, or NULLs
-    unsigned *arrive = nullptr;        // MERGED_XCD: arrival words, 8 XCDs x 32 roles
-    unsigned *status = nullptr;        // MERGED_XCD: one word of pinned host memory the kernel writes when a wait gives up
-    unsigned wait_limit = 1u << 17;
+    unsigned *arrive = nullptr;        // MERGED_XCD: arrival words, 8 XCDs x 32 roles, then the count of waits that gave up
+    unsigned *status = nullptr;        // MERGED_XCD: one word of pinned host memory the kernel writes when it cannot run here
+    unsigned wait_limit = 512;
     size_t ws_bytes;
     double model_us;                   // the selector's latency estimate for this tuning
     char desc[320];
@@ -256,7 +256,7 @@ const char *tdc_status_string(int status)
         case TDC_ERR_BAD_TUNING: return "forced tuning does not fit the shape or the device";
         case TDC_ERR_TOO_LARGE: return "layer needs more scratch memory than the static buffer holds";
         case TDC_ERR_NO_CONVERGENCE: return "eigen-decomposition did not converge within the sweep limit";
-        case TDC_ERR_WAIT: return "a one-launch kernel gave up waiting for the other workgroups of its launch";
+        case TDC_ERR_WAIT: return "a one-launch kernel found XCD or workgroup numbers it was not written for";
         default: return "unknown status";
     }
 }
@@ -287,7 +287,7 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
     tdc_plan *p = new (std::nothrow) tdc_plan();
     if (!p) return TDC_ERR_ALLOC;
     memset(p, 0, sizeof(*p));
-    p->wait_limit = 1u << 17;
+    p->wait_limit = 512;
     p->shape = *shape;
     p->dims = make_dims(kshape);
     p->device = device;
@@ -329,11 +329,11 @@ int tdc_plan_create_tuned(tdc_plan **out, const tdc_shape *shape, int device, co
             p->ws_bytes += copies * n_z1 * sizeof(float);
         }
         if (xcd) {
-            ok = ok && hipMalloc((void **)&p->arrive, 8 * 32 * sizeof(unsigned)) == hipSuccess;
-            ok = ok && hipMemset(p->arrive, 0, 8 * 32 * sizeof(unsigned)) == hipSuccess;
+            ok = ok && hipMalloc((void **)&p->arrive, (8 * 32 + 8) * sizeof(unsigned)) == hipSuccess;
+            ok = ok && hipMemset(p->arrive, 0, (8 * 32 + 8) * sizeof(unsigned)) == hipSuccess;
             ok = ok && hipHostMalloc((void **)&p->status, sizeof(unsigned), hipHostMallocDefault) == hipSuccess;
             if (ok) *p->status = 0;
-            p->ws_bytes += 8 * 32 * sizeof(unsigned);
+            p->ws_bytes += (8 * 32 + 8) * sizeof(unsigned);
         }
         ok = ok && hipMalloc((void **)&p->uin_p, n_w1 * sizeof(float)) == hipSuccess;
         ok = ok && hipMalloc((void **)&p->wm, n_wm * sizeof(float)) == hipSuccess;
@@ -599,8 +599,16 @@ int tdc_plan_set_wait_limit(tdc_plan *p, unsigned polls)
     if (!p) return TDC_ERR_NULL;
     if (p->tuning.variant != TDC_VARIANT_MERGED_XCD) return TDC_ERR_BAD_TUNING;
     p->wait_limit = polls;
-    *p->status = 0;
     return TDC_OK;
+}
+
+int tdc_plan_waits_given_up(tdc_plan *p, unsigned *count)
+{
+    if (!p || !count) return TDC_ERR_NULL;
+    if (p->tuning.variant != TDC_VARIANT_MERGED_XCD) return TDC_ERR_BAD_TUNING;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return TDC_ERR_HIP;
+    return hipMemcpy(count, p->arrive + 8 * 32, sizeof(unsigned), hipMemcpyDeviceToHost) == hipSuccess ? TDC_OK : TDC_ERR_HIP;
 }
 
 int tdc_launch_null(void *hip_stream)

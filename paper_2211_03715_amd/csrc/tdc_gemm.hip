@@ -286,17 +286,19 @@ __global__ __launch_bounds__(512) void tdc_gemm_kernel(GemmArgs a)
 //   The XCD of a workgroup is read from the hardware (XCC_ID), never inferred; its role among the workgroups of
 // that XCD is blockIdx.x / 8, which assumes what the XCD-aware numbering elsewhere in this library assumes for
 // speed only: workgroups are dealt to the 8 XCDs round-robin.  Were that ever not so, a role would be missing on
-// some XCD, its arrival word would lag, and the bounded wait below ends with the plan's status word set: an
-// error the host reports, not a wrong result.  Arrival words count calls (each workgroup adds one to its own
-// word), so nothing depends on host state and a captured graph can be replayed.
+// some XCD and its arrival word would lag.  The wait is bounded for that case and for the likelier one that some
+// workgroups of the launch are not resident yet (other streams' kernels hold their compute units): a workgroup
+// that has waited long enough computes all of stage 1 for its XCD itself and goes on -- slower, the same bits, and
+// no workgroup ever depends on another for more than time.  Arrival words count calls (each workgroup adds one to
+// its own word), so nothing depends on host state and a captured graph can be replayed.
 //   Units are single 16x16 output blocks; tw1 (tw2) wavefronts of a workgroup split the contraction of a unit and
 // add their partial sums through LDS in a fixed order, as in the kernel above; 8/tw teams work side by side.
 struct XcdArgs {
     const float *x, *uin_p, *wm_p;
     float *z1c;            // 8 copies of z1, blocked layout, z1_stride floats apart
     float *y;
-    unsigned *arrive;      // [8 XCDs][32 roles]
-    unsigned *status;      // host-visible; set non-zero when a wait gave up
+    unsigned *arrive;      // [8 XCDs][32 roles], then one word that counts the waits given up
+    unsigned *status;      // host-visible; set non-zero by a kernel that finds XCD or role numbers it does not know
     TdcEpi epi;
     unsigned z1_stride, wait_limit;
     int C, N, HW, P, NB1, NB3, KG1, KG2, H, W, Wo, K, stride, pad;
@@ -339,9 +341,7 @@ __global__ __launch_bounds__(512) void tdc_merged_xcd_kernel(XcdArgs a)
     }
     unsigned *my_arrive = a.arrive + xcc * 32;
     const tdc_rsrc ars_flags = tdc_make_rsrc(my_arrive, 32 * 4);
-    // this workgroup's own word, written by it (same XCD, same role) in the call before: the value to reach
-    // (every wavefront loads it: a load inside a branch is waited for where the branch ends, and this one must not be)
-    const unsigned own = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(ars_flags, role * 4, 0, 16);
+    unsigned own = 0;   // this workgroup's own arrival word as the call before left it; loaded behind stage 1's first operands
     float *z1x = a.z1c + (size_t)xcc * a.z1_stride;
     tdc_f4 *__restrict__ red4 = reinterpret_cast<tdc_f4 *>(red);
 
@@ -361,12 +361,14 @@ __global__ __launch_bounds__(512) void tdc_merged_xcd_kernel(XcdArgs a)
     tdc_f4 wk[NK > 0 ? NK : 1];
     int u2 = 0, b2 = 0, mg2 = 0, pg2 = 0, cnt2 = 0, ih2 = 0, iw2 = 0;
     bool live2 = false;
-    // ---- stage 1, all of it, by the workgroups of this XCD
-    {
+    // ---- stage 1, all of it, by the workgroups of this XCD (pass 0); by this workgroup alone if the others did not
+    // show up at the barrier in time (pass 1, see there)
+    int role1 = role, wn1 = a.Wn, rounds1 = a.rounds1;
+    for (int pass = 0;; ++pass) {
         const int tw = 1 << a.lg1, teams = 8 >> a.lg1, team = wave >> a.lg1, wt = wave & (tw - 1);
         const int q = a.q1, rem = a.rem1;
-        for (int r = 0; r < a.rounds1; ++r) {
-            const int u = (r * a.Wn + role) * teams + team;
+        for (int r = 0; r < rounds1; ++r) {
+            const int u = (r * wn1 + role1) * teams + team;
             const bool live = u < a.n1;
             const int pgb = tdc_div(live ? u : 0, a.div_NB1), mg = (live ? u : 0) - pgb * a.NB1;   // (b, pixel group), channel block
             const int b = tdc_div(pgb, a.div_npb1), pg = pgb - b * a.npb1;
@@ -386,7 +388,11 @@ __global__ __launch_bounds__(512) void tdc_merged_xcd_kernel(XcdArgs a)
             TdcPipe<1, 1, U> pipe;
             pipe.start(next);
             TDC_PROBE(1);
-            if (NK > 0 && r == 0) {
+            // written by this workgroup (same XCD, same role) in the call before: one more than it is the value to reach.
+            // Every wavefront loads it, and here: a load in front of the loop, or inside a branch only wavefront 0 takes,
+            // is waited for on the spot, a memory round trip before the first operand is even requested.
+            if (r == 0 && pass == 0) own = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(ars_flags, role * 4, 0, 16);
+            if (NK > 0 && r == 0 && pass == 0) {
                 u2 = lw * teams2 + team2;
                 live2 = u2 < a.n2;
                 const int bm = tdc_div(live2 ? u2 : 0, a.div_npb2);
@@ -424,29 +430,36 @@ __global__ __launch_bounds__(512) void tdc_merged_xcd_kernel(XcdArgs a)
                 __syncthreads();
             }
         }
-    }
-    // ---- the barrier among the workgroups of this XCD
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's z1 stores are in the L2 (and its weight loads have landed)
-    __syncthreads();
-    TDC_PROBE(3);
-    if (wave == 0) {
-        const unsigned target = own + 1u;
-        if (lane == 0) __hip_atomic_store(my_arrive + role, target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        unsigned polls = 0;
-        bool ok;
-        while (true) {
-            unsigned v = target;
-            if (lane < a.Wn) v = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(ars_flags, lane * 4, 0, 16);   // sc1: misses the L1
-            ok = __builtin_amdgcn_ballot_w64((int)(v - target) < 0) == 0;
-            if (ok || polls++ >= a.wait_limit) break;
+        // ---- the barrier among the workgroups of this XCD
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's z1 stores are in the L2 (and its weight loads have landed)
+        __syncthreads();
+        TDC_PROBE(3);
+        if (pass == 1) break;
+        if (wave == 0) {
+            const unsigned target = own + 1u;
+            if (lane == 0) __hip_atomic_store(my_arrive + role, target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            unsigned polls = 0;
+            bool ok;
+            while (true) {
+                unsigned v = target;
+                if (lane < a.Wn) v = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(ars_flags, lane * 4, 0, 16);   // sc1: misses the L1
+                ok = __builtin_amdgcn_ballot_w64((int)(v - target) < 0) == 0;
+                if (ok || polls++ >= a.wait_limit) break;
+            }
+            if (lane == 0) {
+                go = ok ? 1 : 0;
+                if (!ok) atomicAdd(a.arrive + 8 * 32, 1u);   // counted, for the curious
+            }
         }
-        if (lane == 0) {
-            go = ok ? 1 : 0;
-            if (!ok) __hip_atomic_store(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        }
+        __syncthreads();
+        if (go) break;
+        // The others did not all arrive within the wait: their workgroups may not be resident yet (other streams' kernels
+        // hold the compute units), and a workgroup that spins for them keeps its own compute unit from them.  So it stops
+        // waiting and computes every stage-1 unit itself, into the same copy of z1: the values are bit-identical to what
+        // the others write or will write (same teams, same order of sums), so concurrent writers and readers of a cell
+        // see one and the same value.  Slow (all of stage 1 on one workgroup) and never a deadlock.
+        role1 = 0; wn1 = 1; rounds1 = (a.n1 + teams - 1) / teams;
     }
-    __syncthreads();
-    if (!go) return;
     TDC_PROBE(4);
 
     // ---- the merged K x K GEMM R1 -> N on this XCD's z1
