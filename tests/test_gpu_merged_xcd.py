@@ -222,6 +222,41 @@ def test_two_plans_in_flight_on_two_streams(orc):
         cb.close()
 
 
+def test_next_to_launches_that_fill_the_gpu(orc):
+    """A one-launch plan on one stream while batch-128 calls of 256 large workgroups keep the compute units busy from another:
+    its workgroups become resident a few at a time, waits may run out, and every call must still be right."""
+    import torch
+    from paper_2211_03715_amd.layer import TuckerConv2d
+    small, big = Layer(1, 512, 512, 7, 7, 128, 128), Layer(128, 128, 128, 28, 28, 32, 32)
+    _announce("merged_xcd beside a full GPU", small.name(), big.name())
+    i_small, i_big = make_inputs(small, 31), make_inputs(big, 32)
+    want = _oracle(orc, small, i_small)
+    c_small = _conv(small, {}, B.LAYOUT_NCHW)
+    c_big = TuckerConv2d(big, 0, None)
+    try:
+        ts, tb = _tensors(i_small, B.LAYOUT_NCHW), _tensors(i_big, B.LAYOUT_NCHW)
+        c_small.pack(ts["U_in"], ts["core"], ts["U_out"])
+        c_big.pack(tb["U_in"], tb["core"], tb["U_out"])
+        y_small = torch.full(c_small.out_shape(), float("nan"), device="cuda:0")
+        y_big = torch.empty(c_big.out_shape(), device="cuda:0")
+        torch.cuda.synchronize()
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        l_small, l_big = c_small.bind(ts["x"], y_small, stream=s1.cuda_stream), c_big.bind(tb["x"], y_big, stream=s2.cuda_stream)
+        for rep in range(3):
+            y_small.fill_(float("nan"))
+            torch.cuda.synchronize()
+            for _ in range(60):
+                l_big()
+                l_small()
+            torch.cuda.synchronize()
+            assert B.tdc_plan_status(c_small.plan) == B.TDC_OK
+            assert_parity(y_small.cpu().numpy(), want, "repeat %d %s" % (rep, c_small.describe()))
+        print("    waits given up: %d in 180 calls" % B.tdc_plan_waits_given_up(c_small.plan), flush=True)
+    finally:
+        c_small.close()
+        c_big.close()
+
+
 def test_refusals():
     s = B.make_shape(1, 256, 256, 14, 14, 64, 64)
     for bad in (dict(waves=(3, 8, 8)), dict(waves=(8, 8, 8), mb=(2, 1, 1)), dict(waves=(8, 8, 8), pb=(1, 2, 2))):
