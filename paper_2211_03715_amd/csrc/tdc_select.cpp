@@ -409,8 +409,15 @@ void stage_terms(double (&f)[G_TERMS], const TdcDeviceInfo &dev, int batch, int 
 
 // one GEMM launch: n_mblocks x n_pblocks output blocks per image, `kgroups` k-groups;
 // conv_stride = 0 for a 1x1 stage, the stride for the K x K stage
+// `y_nchw`: the launch writes the layer's y in NCHW, where a thread stores (and, with a residual, first loads) its
+// outputs four bytes at a time: 4 * mb * pb of them per lane when a wavefront works alone, mb * pb * 4 / nw when nw
+// wavefronts sum through LDS and share the stores.  The fitted terms do not see that (they were calibrated on launches
+// without a residual); measured on the 1x1 expansions of the bottleneck networks, 64 -> 256 at 56x56 and 128 -> 512 at
+// 28x28 with bias, residual and ReLU, every output a thread owns costs 0.12 us (5.8 us with 2, 7.3 us with 16).
+constexpr double kNchwOutputUs = 0.12;
+
 StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n_pblocks, int kgroups, int fmb,
-                       int fpb, int fnw, int conv_stride)
+                       int fpb, int fnw, int conv_stride, bool y_nchw = false)
 {
     StageChoice best;
     for (int mb : kMb)
@@ -424,7 +431,8 @@ StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n
                 if ((size_t)nw * mb * pb * 1024 > 64 * 1024 && nw > 1) continue;
                 double f[G_TERMS];
                 stage_terms(f, dev, batch, n_mblocks, n_pblocks, kgroups, mb, pb, nw, conv_stride);
-                const double us = dot(kStageCoef, f, G_TERMS);
+                double us = dot(kStageCoef, f, G_TERMS);
+                if (y_nchw) us += kNchwOutputUs * (4.0 * mb * pb / nw);
                 if (us < best.us) {
                     best.us = us;
                     best.mb = mb; best.pb = pb; best.nw = nw;
@@ -523,7 +531,7 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     if (forced.variant == TDC_VARIANT_DENSE) {
         // the stage-2 kernel on the layer's own channels: `d` has R1 = C and R2 = N
         const StageChoice c = best_stage(dev, d.B, d.NB2, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1],
-                                         forced.pb[1], forced.waves[1], d.stride);
+                                         forced.pb[1], forced.waves[1], d.stride, !d.nhwc);
         if (c.us >= 1e299) return TDC_ERR_BAD_TUNING;
         t->tile_h = t->tile_w = 0;
         for (int i = 0; i < 3; ++i) {
