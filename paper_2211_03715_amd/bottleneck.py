@@ -25,6 +25,7 @@ batch-1 benchmark sweep, in sequence, with their shortcuts and epilogues).
     python -m paper_2211_03715_amd.bottleneck [--nhwc]             # eager vs graph latency of a few block shapes
     python -m paper_2211_03715_amd.bottleneck --resnet50 [--nhwc] [--batch B]   # the 16-block network
     python -m paper_2211_03715_amd.bottleneck --resnet18 [--nhwc] [--batch B]   # the 8 basic blocks
+    ... --oracle    # then once more with every convolution's tuning found by exhaustive search (minutes)
 """
 from __future__ import annotations
 
@@ -54,10 +55,12 @@ def make_block_weights(C: int, M: int, R1: int, R2: int, seed: int, C_out: int =
 
 class TuckerBottleneck:
     def __init__(self, batch: int, C: int, M: int, H: int, W: int, R1: int, R2: int, weights: Dict, device: int = 0,
-                 layout: int = B.LAYOUT_NCHW, stride: int = 1, C_out: int = 0):
+                 layout: int = B.LAYOUT_NCHW, stride: int = 1, C_out: int = 0, tunings=None):
         """``layout``: LAYOUT_NCHW (x, y [batch][C][H][W]) or LAYOUT_NHWC ([batch][H][W][C]); C, M multiples of 4 for NHWC.
         ``stride`` sits on the 3x3 convolution; with stride != 1 or C_out != C the shortcut is the projection
-        s = Wp (*) x + bp (1x1, same stride, no activation: weights "Wp", "bp") and y = relu(W3 (*) t2 + b3 + s)."""
+        s = Wp (*) x + bp (1x1, same stride, no activation: weights "Wp", "bp") and y = relu(W3 (*) t2 + b3 + s).
+        ``tunings``: a function (kind, layer, epilogue) -> tdc_tuning or None that overrides the selector per
+        convolution (see oracle_tunings); kind is "dense" or "tucker", epilogue a (bias, residual, relu) triple of bools."""
         import torch
         self.dev = torch.device("cuda", device)
         self.layout = layout
@@ -68,9 +71,11 @@ class TuckerBottleneck:
         self.l3 = Layer(batch, M, C_out, self.l2.Ho, self.l2.Wo, 1, 1, 1, 1, 0)
         self.lp = Layer(batch, C, C_out, H, W, 1, 1, 1, stride, 0) if self.projection else None
         self.w = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.dev) for k, v in weights.items()}
-        self.conv1, self.conv2, self.conv3 = (DenseConv2d(self.l1, device, layout=layout), TuckerConv2d(self.l2, device, layout=layout),
-                                              DenseConv2d(self.l3, device, layout=layout))
-        self.convp = DenseConv2d(self.lp, device, layout=layout) if self.projection else None
+        pick = tunings or (lambda kind, layer, epilogue: None)
+        self.conv1 = DenseConv2d(self.l1, device, pick("dense", self.l1, (True, False, True)), layout=layout)
+        self.conv2 = TuckerConv2d(self.l2, device, pick("tucker", self.l2, (True, False, True)), layout=layout)
+        self.conv3 = DenseConv2d(self.l3, device, pick("dense", self.l3, (True, True, True)), layout=layout)
+        self.convp = DenseConv2d(self.lp, device, pick("dense", self.lp, (True, False, False)), layout=layout) if self.projection else None
         self.conv1.pack(self.w["W1"])
         self.conv2.pack(self.w["U_in"], self.w["core"], self.w["U_out"])
         self.conv3.pack(self.w["W3"])
@@ -153,7 +158,7 @@ def make_basic_weights(C: int, M: int, Ra: tuple, Rb: tuple, seed: int, projecti
 
 class TuckerBasicBlock:
     def __init__(self, batch: int, C: int, M: int, H: int, W: int, Ra: tuple, Rb: tuple, weights: Dict, device: int = 0,
-                 layout: int = B.LAYOUT_NCHW, stride: int = 1):
+                 layout: int = B.LAYOUT_NCHW, stride: int = 1, tunings=None):
         """Two Tucker-2 3x3 convolutions, C -> M (``stride``) and M -> M, ranks Ra = (R1, R2) and Rb; a projection
         shortcut (dense 1x1, same stride, weights "Wp", "bp") when stride != 1 or M != C."""
         import torch
@@ -164,8 +169,10 @@ class TuckerBasicBlock:
         self.lb = Layer(batch, M, M, self.la.Ho, self.la.Wo, Rb[0], Rb[1], 3, 1, 1)
         self.lp = Layer(batch, C, M, H, W, 1, 1, 1, stride, 0) if self.projection else None
         self.w = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.dev) for k, v in weights.items()}
-        self.conva, self.convb = TuckerConv2d(self.la, device, layout=layout), TuckerConv2d(self.lb, device, layout=layout)
-        self.convp = DenseConv2d(self.lp, device, layout=layout) if self.projection else None
+        pick = tunings or (lambda kind, layer, epilogue: None)
+        self.conva = TuckerConv2d(self.la, device, pick("tucker", self.la, (True, False, True)), layout=layout)
+        self.convb = TuckerConv2d(self.lb, device, pick("tucker", self.lb, (True, True, True)), layout=layout)
+        self.convp = DenseConv2d(self.lp, device, pick("dense", self.lp, (True, False, False)), layout=layout) if self.projection else None
         self.conva.pack(self.w["Ua_in"], self.w["core_a"], self.w["Ua_out"])
         self.convb.pack(self.w["Ub_in"], self.w["core_b"], self.w["Ub_out"])
         self.t1 = torch.empty(self.conva.out_shape(), device=self.dev, dtype=torch.float32)
@@ -230,7 +237,7 @@ class TuckerResNetBody:
     synthetic (make_block_weights), ranks come from ``rank(M)``."""
 
     def __init__(self, batch: int, H: int = 56, W: int = 56, width: int = 64, blocks=(3, 4, 6, 3), rank=default_rank,
-                 seed: int = 0, device: int = 0, layout: int = B.LAYOUT_NCHW):
+                 seed: int = 0, device: int = 0, layout: int = B.LAYOUT_NCHW, tunings=None):
         import torch
         self.dev = torch.device("cuda", device)
         self.layout = layout
@@ -245,7 +252,7 @@ class TuckerResNetBody:
                 stride = 2 if (first and stage > 0) else 1
                 R = rank(M)
                 wts = make_block_weights(C, M, R, R, seed + 100 * stage + i, C_out=4 * M, projection=first)
-                blk = TuckerBottleneck(batch, C, M, h, w, R, R, wts, device, layout, stride=stride, C_out=4 * M)
+                blk = TuckerBottleneck(batch, C, M, h, w, R, R, wts, device, layout, stride=stride, C_out=4 * M, tunings=tunings)
                 assert blk.projection == first
                 self.blocks.append(blk)
                 self.weights.append(wts)
@@ -295,7 +302,7 @@ class TuckerResNet18Body(TuckerResNetBody):
     stage has stride 2 and a projection shortcut.  Input: the stem's output, [batch][width][H][W] (64 x 56 x 56)."""
 
     def __init__(self, batch: int, H: int = 56, W: int = 56, width: int = 64, blocks=(2, 2, 2, 2), rank=lambda ch: max(1, ch // 4),
-                 seed: int = 0, device: int = 0, layout: int = B.LAYOUT_NCHW):
+                 seed: int = 0, device: int = 0, layout: int = B.LAYOUT_NCHW, tunings=None):
         import torch
         self.dev = torch.device("cuda", device)
         self.layout = layout
@@ -309,12 +316,64 @@ class TuckerResNet18Body(TuckerResNetBody):
                 stride = 2 if (i == 0 and stage > 0) else 1
                 Ra, Rb = (rank(C), rank(M)), (rank(M), rank(M))
                 wts = make_basic_weights(C, M, Ra, Rb, seed + 100 * stage + i, projection=stride != 1 or M != C)
-                blk = TuckerBasicBlock(batch, C, M, h, w, Ra, Rb, wts, device, layout, stride=stride)
+                blk = TuckerBasicBlock(batch, C, M, h, w, Ra, Rb, wts, device, layout, stride=stride, tunings=tunings)
                 self.blocks.append(blk)
                 self.weights.append(wts)
                 C, h, w = M, blk.la.Ho, blk.la.Wo
         self.in_shape = (batch, H, W, width) if layout == B.LAYOUT_NHWC else (batch, width, H, W)
         self.y = self.blocks[-1].y
+
+
+def oracle_tunings(layout: int = B.LAYOUT_NCHW, device: int = 0, iters: int = 100, progress=None):
+    """A ``tunings`` function for the blocks and networks above that replaces the selector's closed-form choice by
+    exhaustive search, the paper's "oracle" setting next to its "modeling" one (section 7): the first time a convolution
+    shape is asked for, every launchable tuning of it is timed on the GPU (Tucker layers: autotune.autotune, 500-2400
+    tunings; dense layers: the 36 register-tile / wavefront combinations, with the epilogue the layer will run with),
+    the fastest is kept and served from then on.  Returns (function, log) -- log lists (kind, layer, model us, best us)."""
+    import torch
+    from .autotune import _time, autotune
+    cache, log = {}, []
+
+    def dense(layer, epilogue):
+        dev = torch.device("cuda", device)
+        x = torch.randn((layer.batch, layer.H, layer.W, layer.C) if layout == B.LAYOUT_NHWC else (layer.batch, layer.C, layer.H, layer.W), device=dev)
+        W = torch.randn((layer.C, layer.N, layer.K, layer.K), device=dev) * float(layer.C * layer.K * layer.K) ** -0.5
+        rows = []
+        for tun in [None] + [dict(mb=(0, mb, 0), pb=(0, pb, 0), waves=(0, nw, 0)) for mb in (1, 2, 4) for pb in (1, 2, 4) for nw in (1, 2, 4, 8)]:
+            try:
+                conv = DenseConv2d(layer, device, B.make_tuning(**tun) if tun else None, layout=layout)
+            except B.TdcError:
+                continue
+            try:
+                conv.pack(W)
+                y = torch.empty(conv.out_shape(), device=dev)
+                launch = conv.bind(x, y, bias=torch.zeros(layer.N, device=dev) if epilogue[0] else None,
+                                   residual=torch.zeros_like(y) if epilogue[1] else None, relu=epilogue[2])
+                rows.append((_time(launch, iters), tun is None, B.tdc_plan_get_tuning(conv.plan)))
+                torch.cuda.synchronize()
+            finally:
+                conv.close()
+        best = min(rows, key=lambda r: r[0])
+        return [r for r in rows if r[1]][0][0], best[0], best[2]
+
+    def pick(kind, layer, epilogue):
+        key = (kind, layer.name(), epilogue if kind == "dense" else None)
+        if key not in cache:
+            if kind == "dense":
+                model_us, best_us, tuning = dense(layer, epilogue)
+            else:
+                r = autotune(layer, device, iters=iters, layout=layout)
+                model_us, best_us = r["auto"]["us"], r["best"]["us"]
+                d = r["best"]["tuning"]
+                tuning = B.make_tuning(variant={v: k for k, v in B.VARIANT_NAMES.items()}[d["variant"]], tile_h=d["tile_h"], tile_w=d["tile_w"],
+                                       waves=tuple(d["waves"]), mb=tuple(d["mb"]), pb=tuple(d["pb"]))
+            cache[key] = tuning
+            log.append((kind, layer.name(), model_us, best_us))
+            if progress:
+                progress("%-6s %-44s model %6.2f us  best %6.2f us" % (kind, layer.name(), model_us, best_us))
+        return cache[key]
+
+    return pick, log
 
 
 def time_network(net, iters: int = 100, repeats: int = 5) -> Dict[str, float]:
@@ -353,13 +412,23 @@ def main(argv=None) -> int:
     if argv and ("--resnet50" in argv or "--resnet18" in argv):
         batch = int(argv[argv.index("--batch") + 1]) if "--batch" in argv else 1
         deep = "--resnet50" in argv
-        net = TuckerResNetBody(batch, layout=layout) if deep else TuckerResNet18Body(batch, layout=layout)
+        cls = TuckerResNetBody if deep else TuckerResNet18Body
+        net = cls(batch, layout=layout)
         r = time_network(net)
         print(net.describe())
         print("ResNet-%d body, batch %d, %s: %d blocks, %d kernels, %.3f GFLOP; eager %.1f us, one graph %.1f us" % (
             50 if deep else 18, batch, "NHWC" if layout else "NCHW", len(net.blocks), net.kernels(), net.flops() / 1e9,
-            r["eager_us"], r["graph_us"]))
+            r["eager_us"], r["graph_us"]), flush=True)
         net.close()
+        if "--oracle" in argv:       # the same network with every convolution's tuning found by exhaustive search
+            pick, log = oracle_tunings(layout, progress=lambda m: print("   " + m, flush=True))
+            tuned = cls(batch, layout=layout, tunings=pick)
+            ro = time_network(tuned)
+            print(tuned.describe())
+            print("... with exhaustively searched tunings (%d shapes searched): %d kernels; eager %.1f us, one graph %.1f us; "
+                  "the selector's network is %.1f %% behind" % (len(log), tuned.kernels(), ro["eager_us"], ro["graph_us"],
+                                                              100 * (r["eager_us"] / ro["eager_us"] - 1)), flush=True)
+            tuned.close()
         return 0
     print("%-34s %8s %10s %10s  %s" % ("block (batch 1, %s)" % ("NHWC" if layout else "NCHW"), "kernels", "eager us", "graph us", "plans"),
           flush=True)
