@@ -279,3 +279,41 @@ def test_resnet18_body_eager_and_one_graph(orc, case, layout):
             assert torch.equal(eager, replayed)
     finally:
         net.close()
+
+
+def test_blocks_take_tunings_per_convolution(orc):
+    """The ``tunings`` hook of the blocks (what bottleneck.oracle_tunings plugs into): every convolution gets the tuning the
+    function returns for its kind, layer and epilogue, and the block still matches the oracle."""
+    import torch
+    from paper_2211_03715_amd.bottleneck import TuckerBasicBlock, make_basic_weights
+    print("[case] blocks with given tunings", flush=True)
+    sys.stdout.flush()
+    asked = []
+
+    def tunings(kind, layer, epilogue):
+        asked.append((kind, layer.name(), epilogue))
+        if kind == "dense":
+            return B.make_tuning(mb=(0, 1, 0), pb=(0, 2, 0), waves=(0, 2, 0))
+        return B.make_tuning(variant=B.VARIANT_SPLIT, waves=(2, 2, 2), mb=(1, 1, 1), pb=(1, 1, 1))
+
+    w = make_block_weights(32, 16, 8, 8, 3, C_out=64, projection=True)
+    blk = TuckerBottleneck(2, 32, 16, 14, 14, 8, 8, w, stride=2, C_out=64, tunings=tunings)
+    try:
+        assert [a[0] for a in asked] == ["dense", "tucker", "dense", "dense"] and asked[2][2] == (True, True, True)
+        assert "split" in blk.conv2.describe() and "(mb,pb,waves)=(1,2,2)" in blk.conv1.describe()
+        x = np.random.default_rng(4).standard_normal((2, 32, 14, 14), dtype=np.float32)
+        got = blk(torch.from_numpy(x).to(blk.dev))
+        torch.cuda.synchronize()
+        assert_parity(got.cpu().numpy(), _oracle_block(orc, blk, w, x), blk.describe())
+    finally:
+        blk.close()
+    wb = make_basic_weights(16, 32, (8, 8), (8, 8), 5, projection=True)
+    bb = TuckerBasicBlock(1, 16, 32, 12, 12, (8, 8), (8, 8), wb, stride=2, tunings=tunings)
+    try:
+        assert "split" in bb.conva.describe() and "split" in bb.convb.describe()
+        x = np.random.default_rng(6).standard_normal((1, 16, 12, 12), dtype=np.float32)
+        got = bb(torch.from_numpy(x).to(bb.dev))
+        torch.cuda.synchronize()
+        assert_parity(got.cpu().numpy(), _oracle_basic_block(orc, bb, wb, x), bb.describe())
+    finally:
+        bb.close()
