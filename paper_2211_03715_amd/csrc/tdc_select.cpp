@@ -426,6 +426,11 @@ StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n
                 if (fmb && mb != fmb) continue;
                 if (fpb && pb != fpb) continue;
                 if (fnw && nw != fnw) continue;
+                // 3 and 6 wavefronts are launchable and never chosen: they leave the four SIMDs of a compute unit with
+                // unequal shares (2, 2, 1, 1), and in every sweep the next power of two was as fast or faster (6 against
+                // 8 wavefronts: +0.5 to +1.0 us on the rank-40 and rank-80 layers) while the fitted terms, smooth in
+                // the wavefront count, put them in between
+                if (!fnw && (nw == 3 || nw == 6)) continue;
                 if (n_mblocks % mb) continue;         // whole register tiles only
                 if (!fnw && nw > kgroups) continue;   // idle wavefronts are legal, just never chosen
                 if ((size_t)nw * mb * pb * 1024 > 64 * 1024 && nw > 1) continue;
