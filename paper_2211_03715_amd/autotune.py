@@ -159,6 +159,51 @@ def autotune(L: Layer, device: int = 0, iters: int = 200, variants=("fused", "ch
             "by_variant": by_variant, "rows": rows}
 
 
+EPILOGUES = {"none": (False, False, False), "bias": (True, False, False), "bias_relu": (True, False, True),
+             "bias_residual_relu": (True, True, True)}
+
+
+def autotune_dense(L: Layer, device: int = 0, iters: int = 200, epilogue: str = "bias_residual_relu", progress=None,
+                   layout: int = B.LAYOUT_NCHW) -> Dict:
+    """The dense K x K layer of L's shape (tdc_conv_dense; R1, R2 are ignored) with every register-tile / wavefront
+    combination of its one GEMM launch, timed with the given epilogue.  Same result format as autotune()."""
+    import torch
+    from .layer import DenseConv2d
+    dev = torch.device("cuda", device)
+    bias, residual, relu = EPILOGUES[epilogue]
+    x = torch.randn((L.batch, L.H, L.W, L.C) if layout == B.LAYOUT_NHWC else (L.batch, L.C, L.H, L.W), device=dev)
+    W = torch.randn((L.C, L.N, L.K, L.K), device=dev) * float(L.C * L.K * L.K) ** -0.5
+
+    def run(tuning):
+        conv = DenseConv2d(L, device, tuning, layout=layout)
+        try:
+            conv.pack(W)
+            y = torch.empty(conv.out_shape(), device=dev)
+            us = _time(conv.bind(x, y, bias=torch.zeros(L.N, device=dev) if bias else None,
+                                 residual=torch.zeros_like(y) if residual else None, relu=relu), iters)
+            torch.cuda.synchronize()
+            return {"us": us, "plan": conv.describe(), "tuning": conv.tuning()}
+        finally:
+            conv.close()
+
+    auto = run(None)
+    rows = []
+    for mb, pb, nw in itertools.product((1, 2, 4), (1, 2, 4), STAGE_WAVES):
+        try:
+            rows.append(run(B.make_tuning(mb=(0, mb, 0), pb=(0, pb, 0), waves=(0, nw, 0))))
+        except B.TdcError as e:
+            if e.status != B.TDC_ERR_BAD_TUNING:
+                raise
+    rows.sort(key=lambda r: r["us"])
+    first, auto = auto, run(None)
+    auto["first_us"] = first["us"]
+    if progress:
+        progress("%s dense: auto %.2f us [%s]; best %.2f us [%s]; %d tunings timed" % (
+            L.name(), auto["us"], auto["plan"], rows[0]["us"], rows[0]["plan"], len(rows)))
+    return {"layer": L.name(), "layout": "nhwc" if layout == B.LAYOUT_NHWC else "nchw", "epilogue": epilogue, "auto": auto,
+            "best": rows[0], "by_variant": {"dense": rows[0]}, "rows": rows}
+
+
 def paper_tile_rule(L: Layer, rows: List[Dict], cus: int = 256, top: float = 0.05) -> Dict:
     """The paper's tile selection (sections 5.3-5.5) applied to the FUSED kernel's tilings of one layer.
 
@@ -227,7 +272,7 @@ def analyse(path: str) -> int:
 
 COEF_HEADER = __import__("os").path.join(__import__("os").path.dirname(__import__("os").path.abspath(__file__)), "csrc", "tdc_select_coef.h")
 COEF_TABLES = {"fused_latency": "kFusedLatencyCoef", "fused_throughput": "kFusedThroughputCoef", "chain": "kChainCoef",
-               "fused_merged": "kFmCoef", "stage": "kStageCoef"}
+               "fused_merged": "kFmCoef", "stage": "kStageCoef", "dense": "kDenseCoef"}
 _VARIANT_IDS = {v: k for k, v in B.VARIANT_NAMES.items()}
 _LAYER_RE = __import__("re").compile(r"b(\d+)_c(\d+)_n(\d+)_(\d+)x(\d+)_r(\d+)-(\d+)_k(\d+)_s(\d+)_p(\d+)$")
 
@@ -347,7 +392,8 @@ def selector_gap(paths: Iterable[str], default_layout: str = "nchw") -> List[Dic
             L = _layer_from_name(res["layer"])
             lay = res.get("layout", default_layout)
             shape = B.make_shape(**L.asdict(), layout=B.LAYOUT_NHWC if lay == "nhwc" else B.LAYOUT_NCHW)
-            pick = B.tdc_select_tuning(shape).as_dict()
+            dense = bool(res["rows"]) and res["rows"][0]["tuning"]["variant"] == "dense"     # a sweep made with --dense
+            pick = B.tdc_select_tuning(shape, tuning=B.make_tuning(variant=B.VARIANT_DENSE) if dense else None).as_dict()
             same = [r for r in res["rows"] if key(r["tuning"]) == key(pick)]
             best = min(r["us"] for r in res["rows"])
             out.append({"layer": res["layer"], "layout": lay, "best_us": best, "pick": pick,
@@ -434,6 +480,9 @@ def main(argv=None) -> int:
     ap.add_argument("--iters", type=int, default=200)
     ap.add_argument("--variants", nargs="*", default=["fused", "chain", "split", "merged", "fused_merged"])
     ap.add_argument("--layout", default="nchw", choices=["nchw", "nhwc"])
+    ap.add_argument("--dense", action="store_true", help="sweep the dense K x K layer of each shape (tdc_conv_dense; R1, R2 ignored) "
+                    "instead of the Tucker layer: the data of the `dense` coefficient table")
+    ap.add_argument("--epilogue", default="bias_residual_relu", choices=sorted(EPILOGUES), help="with --dense: what the timed calls carry")
     ap.add_argument("--out", default=None, help="JSON with every timed tuning")
     ap.add_argument("--analyse", default=None, metavar="JSON", help="no GPU: the paper's two-step tile rule on a sweep saved with --out")
     ap.add_argument("--fit", nargs="+", default=None, metavar="JSON",
@@ -471,8 +520,11 @@ def main(argv=None) -> int:
             if L.name() in seen:
                 continue
             seen.add(L.name())
-            r = autotune(L, 0, args.iters if L.batch == 1 else max(50, args.iters // 4), tuple(args.variants),
-                         layout=B.LAYOUT_NHWC if args.layout == "nhwc" else B.LAYOUT_NCHW)
+            lay = B.LAYOUT_NHWC if args.layout == "nhwc" else B.LAYOUT_NCHW
+            if args.dense:
+                r = autotune_dense(L, 0, args.iters, args.epilogue, layout=lay)
+            else:
+                r = autotune(L, 0, args.iters if L.batch == 1 else max(50, args.iters // 4), tuple(args.variants), layout=lay)
             results.append(r)
             print("%-46s %9.2f %9.2f %6.1f%%  %s   (model chose: %s)" % (
                 L.name(), r["auto"]["us"], r["best"]["us"], 100.0 * (r["auto"]["us"] / r["best"]["us"] - 1.0), r["best"]["plan"],

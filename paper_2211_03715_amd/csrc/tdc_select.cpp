@@ -407,17 +407,30 @@ void stage_terms(double (&f)[G_TERMS], const TdcDeviceInfo &dev, int batch, int 
     f[conv_stride ? G_ACT_CONV : G_ACT_1X1] = act_loads * (conv_stride ? conv_stride : 1);
 }
 
-// one GEMM launch: n_mblocks x n_pblocks output blocks per image, `kgroups` k-groups;
-// conv_stride = 0 for a 1x1 stage, the stride for the K x K stage
-// `y_nchw`: the launch writes the layer's y in NCHW, where a thread stores (and, with a residual, first loads) its
-// outputs four bytes at a time: 4 * mb * pb of them per lane when a wavefront works alone, mb * pb * 4 / nw when nw
-// wavefronts sum through LDS and share the stores.  The fitted terms do not see that (they were calibrated on launches
-// without a residual); measured on the 1x1 expansions of the bottleneck networks, 64 -> 256 at 56x56 and 128 -> 512 at
-// 28x28 with bias, residual and ReLU, every output a thread owns costs 0.12 us (5.8 us with 2, 7.3 us with 16).
-constexpr double kNchwOutputUs = 0.12;
+// The dense layer (tdc_conv_dense: one GEMM launch that writes the layer's y) has a table of its own: the terms of a GEMM
+// stage, fitted to launches that carry an epilogue as the layers of the bottleneck networks do, and the outputs a thread
+// owns -- 4 * mb * pb per lane when a wavefront works alone, 4 * mb * pb / nw when nw wavefronts sum through LDS and
+// share the stores.  In NCHW every one of them is a 4-byte store (and with a residual a 4-byte load before it), which
+// the stage table, calibrated on launches without an epilogue, had no term for: it took 1-wavefront units of four
+// channel blocks for the 64 -> 256 expansion at 56x56 (8.0 us, where two wavefronts on one block run in 5.8 us).
+enum { D_Y_NCHW = G_TERMS, D_Y_NHWC, D_TERMS };
+const char *const kDenseTermNames[D_TERMS] = {"launch", "wave", "kg", "mfma", "conv_b", "reduce", "act_1x1", "act_conv", "y_nchw", "y_nhwc"};
 
+void dense_terms(double (&f)[D_TERMS], const TdcDeviceInfo &dev, int batch, int n_mblocks, int n_pblocks, int kgroups, int mb, int pb,
+                 int nw, int conv_stride, bool nhwc)
+{
+    double g[G_TERMS];
+    stage_terms(g, dev, batch, n_mblocks, n_pblocks, kgroups, mb, pb, nw, conv_stride);
+    for (int i = 0; i < G_TERMS; ++i) f[i] = g[i];
+    const double per_thread = 4.0 * mb * pb / nw;
+    f[D_Y_NCHW] = nhwc ? 0.0 : per_thread;
+    f[D_Y_NHWC] = nhwc ? per_thread : 0.0;
+}
+
+// one GEMM launch: n_mblocks x n_pblocks output blocks per image, `kgroups` k-groups;
+// conv_stride = 0 for a 1x1 stage, the stride for the K x K stage; `dense`: priced by the dense layer's table
 StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n_pblocks, int kgroups, int fmb,
-                       int fpb, int fnw, int conv_stride, bool y_nchw = false)
+                       int fpb, int fnw, int conv_stride, bool dense = false, bool nhwc = false)
 {
     StageChoice best;
     for (int mb : kMb)
@@ -434,10 +447,16 @@ StageChoice best_stage(const TdcDeviceInfo &dev, int batch, int n_mblocks, int n
                 if (n_mblocks % mb) continue;         // whole register tiles only
                 if (!fnw && nw > kgroups) continue;   // idle wavefronts are legal, just never chosen
                 if ((size_t)nw * mb * pb * 1024 > 64 * 1024 && nw > 1) continue;
-                double f[G_TERMS];
-                stage_terms(f, dev, batch, n_mblocks, n_pblocks, kgroups, mb, pb, nw, conv_stride);
-                double us = dot(kStageCoef, f, G_TERMS);
-                if (y_nchw) us += kNchwOutputUs * (4.0 * mb * pb / nw);
+                double us;
+                if (dense) {
+                    double f[D_TERMS];
+                    dense_terms(f, dev, batch, n_mblocks, n_pblocks, kgroups, mb, pb, nw, conv_stride, nhwc);
+                    us = dot(kDenseCoef, f, D_TERMS);
+                } else {
+                    double f[G_TERMS];
+                    stage_terms(f, dev, batch, n_mblocks, n_pblocks, kgroups, mb, pb, nw, conv_stride);
+                    us = dot(kStageCoef, f, G_TERMS);
+                }
                 if (us < best.us) {
                     best.us = us;
                     best.mb = mb; best.pb = pb; best.nw = nw;
@@ -493,7 +512,9 @@ int tdc_select_terms(const TdcDims &d, const TdcDeviceInfo &dev, const tdc_tunin
             for (int i = 0; i < G_TERMS; ++i) sum[i] += f[i];
         };
         if (t.variant == TDC_VARIANT_DENSE) {
-            add(d.NB2, pb_out, KG2, 1, d.stride);
+            double fd[D_TERMS];
+            dense_terms(fd, dev, d.B, d.NB2, pb_out, KG2, t.mb[1], t.pb[1], t.waves[1], d.stride, d.nhwc != 0);
+            return emit(fd, kDenseTermNames, D_TERMS, "dense");
         } else {
             add(d.NB1, pb_in, d.KG1, 0, 0);
             if (t.variant == TDC_VARIANT_MERGED || t.variant == TDC_VARIANT_MERGED_XCD) {
@@ -536,7 +557,7 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     if (forced.variant == TDC_VARIANT_DENSE) {
         // the stage-2 kernel on the layer's own channels: `d` has R1 = C and R2 = N
         const StageChoice c = best_stage(dev, d.B, d.NB2, cdiv(d.Ho * d.Wo, 16), d.K * d.K * d.NB1, forced.mb[1],
-                                         forced.pb[1], forced.waves[1], d.stride, !d.nhwc);
+                                         forced.pb[1], forced.waves[1], d.stride, true, d.nhwc != 0);
         if (c.us >= 1e299) return TDC_ERR_BAD_TUNING;
         t->tile_h = t->tile_w = 0;
         for (int i = 0; i < 3; ++i) {

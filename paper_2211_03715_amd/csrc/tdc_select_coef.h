@@ -15,5 +15,7 @@ static const double kChainCoef[20] = {3.6918, 0.5859, 0.0211, 0.0906, 0.2783, 0.
 static const double kFmCoef[9] = {2.5879, 0.2174, 0.0197, 0.0407, 0.0803, 0.4477, 38.3935, 16.4747, 0.5418};
 // one GEMM launch (split, merged, dense): launch wave kg mfma conv_b reduce act_1x1 act_conv
 static const double kStageCoef[8] = {2.15, 0.05, 0.0649, 0.0785, 0.0255, 0.3158, 0.0653, 0.0246};
+// the dense K x K layer (one GEMM launch that writes y): the eight terms above, then y_nchw y_nhwc
+static const double kDenseCoef[10] = {2.4298, 0.0481, 0.0128, 0.0674, 0.0376, 0.3898, 0, 0.0158, 0.1439, 0.0498};
 
 #endif

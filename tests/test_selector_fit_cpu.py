@@ -136,3 +136,28 @@ def test_model_terms_error_paths(lib):
     big = B.make_tuning(variant=B.VARIANT_CHAIN, tile_h=16, tile_w=32, waves=(8, 8, 8), mb=(1, 1, 1), pb=(1, 1, 1))
     wide = B.make_shape(batch=1, C=512, N=512, H=64, W=64, R1=256, R2=128, K=3, stride=1, pad=1)
     assert raw.tdc_model_terms(ctypes.byref(wide), ctypes.byref(big), 256, 64 * 1024, terms, names, 64, ctypes.byref(n), None) == B.TDC_ERR_BAD_TUNING
+
+
+def test_dense_layer_has_its_own_table_with_output_terms():
+    """The dense layer is priced by the `dense` table: the eight terms of a GEMM stage and the outputs a thread owns,
+    booked under the layout the launch writes."""
+    coef = A.read_coefficients()
+    assert len(coef["dense"]) == 10 and len(coef["stage"]) == 8
+    for layout, live, dead in ((B.LAYOUT_NCHW, "y_nchw", "y_nhwc"), (B.LAYOUT_NHWC, "y_nhwc", "y_nchw")):
+        shape = B.make_shape(1, 64, 256, 56, 56, 1, 1, 1, 1, 0, layout)
+        for mb, pb, nw, want in ((4, 1, 1, 16.0), (2, 1, 4, 2.0), (1, 2, 8, 1.0)):
+            t = B.make_tuning(variant=B.VARIANT_DENSE, waves=(nw,) * 3, mb=(mb,) * 3, pb=(pb,) * 3)
+            model, names, terms = B.tdc_model_terms(shape, t)
+            assert model == "dense" and names[:8] == ["launch", "wave", "kg", "mfma", "conv_b", "reduce", "act_1x1", "act_conv"]
+            by = dict(zip(names, terms))
+            assert by[live] == want and by[dead] == 0.0
+        # the selector's own choice is the lowest estimate among the tunings it offers (no 3 or 6 wavefronts)
+        pick = B.tdc_select_tuning(shape, tuning=B.make_tuning(variant=B.VARIANT_DENSE)).as_dict()
+        est = {}
+        for mb in (1, 2, 4):
+            for pb in (1, 2, 4):
+                for nw in (1, 2, 4):          # 64 input channels are 4 k-groups: no more wavefronts than that
+                    t = B.make_tuning(variant=B.VARIANT_DENSE, waves=(nw,) * 3, mb=(mb,) * 3, pb=(pb,) * 3)
+                    _, _, terms = B.tdc_model_terms(shape, t)
+                    est[(mb, pb, nw)] = sum(c * f for c, f in zip(coef["dense"], terms))
+        assert (pick["mb"][1], pick["pb"][1], pick["waves"][1]) == min(est, key=est.get)
