@@ -688,8 +688,11 @@ int tdc_select(const TdcDims &d, const TdcDeviceInfo &dev, tdc_tuning *t, double
     if (variant == TDC_VARIANT_AUTO) {
         // The split estimate is calibrated on latency-bound launches (few workgroup rounds).  In the
         // throughput regime three launches that round-trip z1 and z2 through memory never beat the
-        // fused kernels in the sweep, so the comparison is not trusted there.
-        variant = (f.us <= split_us || (pixels_fill_chip && f.us < 1e299)) ? TDC_VARIANT_FUSED : TDC_VARIANT_SPLIT;
+        // fused kernels in the sweep, so the comparison is not trusted there.  Below it FUSED has to win by 8 %: where the
+        // two estimates are that close the layer is a heavy one (many channels on few pixels), the fused latency table
+        // ranks its own tunings badly there and the fused kernel measured 3-30 % behind SPLIT (512 channels on 7x7 at
+        // batch 64: 50.2 against 38.3 us; 256 channels on 56x56: 17.9 against 17.4 us), 2 % ahead at best.
+        variant = (f.us <= 0.92 * split_us || (pixels_fill_chip && f.us < 1e299)) ? TDC_VARIANT_FUSED : TDC_VARIANT_SPLIT;
     }
     if (variant == TDC_VARIANT_FUSED) {
         if (f.us >= 1e299) return TDC_ERR_BAD_TUNING;
