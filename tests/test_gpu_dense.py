@@ -130,3 +130,20 @@ def test_dense_and_tucker_plans_reject_each_others_calls():
     torch.cuda.synchronize()
     B.tdc_plan_destroy(dense)
     B.tdc_plan_destroy(tucker)
+
+
+def test_dense_sweep_tool_times_every_tuning_and_names_the_best():
+    """autotune --dense: the sweep behind the `dense` coefficient table, on a small layer with a handful of launches."""
+    from paper_2211_03715_amd import autotune as A
+    layer = Layer(1, 32, 64, 9, 11, 1, 1, 1, 1, 0)
+    print("[case] dense sweep tool", layer.name(), flush=True)
+    sys.stdout.flush()
+    r = A.autotune_dense(layer, iters=5, epilogue="bias_residual_relu", layout=B.LAYOUT_NHWC)
+    assert r["layout"] == "nhwc" and r["epilogue"] == "bias_residual_relu" and r["layer"] == layer.name()
+    assert len(r["rows"]) >= 12 and all(row["tuning"]["variant"] == "dense" and row["us"] > 0 for row in r["rows"])
+    assert r["best"]["us"] == min(row["us"] for row in r["rows"]) and r["auto"]["us"] > 0
+    # what the fit reads back: the dense model's terms for every timed tuning
+    shape = B.make_shape(**layer.asdict(), layout=B.LAYOUT_NHWC)
+    t = r["best"]["tuning"]
+    model, names, terms = B.tdc_model_terms(shape, B.make_tuning(variant=B.VARIANT_DENSE, waves=tuple(t["waves"]), mb=tuple(t["mb"]), pb=tuple(t["pb"])))
+    assert model == "dense" and names[-2:] == ["y_nchw", "y_nhwc"] and terms[-2] == 0.0 and terms[-1] > 0.0
